@@ -1,0 +1,217 @@
+"""Seeded synthetic inputs for the MoE-layer hot path.
+
+This module only draws random numbers and rounds them to the storage type.  It
+holds none of the method's arithmetic (no routing, no expert FFN, no combine)
+and is the one piece that both the CPU oracle's tests and the GPU path's tests
+and benchmark may share: each side receives the very same arrays.
+
+Recipe.  Every tensor is drawn from its own NumPy ``Generator(PCG64(sub_seed))``
+with ``sub_seed = seed*10**6 + layer*10**3 + tensor_id`` where ``tensor_id`` is
+0 for the activations X, 1 for the gate matrix Wg and ``2 + 3*e + {0,1,2}`` for
+W1, W3, W2 of expert ``e`` (shared experts follow the routed ones: e = E..E+S-1).
+Values are float32 normal draws, scaled, then (for bf16 workloads) rounded to
+bfloat16 with round-to-nearest-even; the rounded values are what both sides see.
+
+Shapes follow the paper's evaluated model family (Section 9.1: Mixtral-8x7B and
+Mixtral-8x22B, prompt 512 tokens, batch sizes 4-64) and the skewed expert
+popularity it reports (Section 3.3); the paper's datasets and trained weights are
+not available, these inputs stand in for them.
+"""
+from __future__ import annotations
+
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, field, replace
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+TID_X = 0
+TID_WG = 1
+
+
+def tid_expert(e: int, which: int) -> int:
+    """tensor_id of W1 (which=0), W3 (1) or W2 (2) of expert ``e``."""
+    return 2 + 3 * e + which
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One MoE-layer workload: shapes, batch structure and distributions."""
+    name: str
+    dtype: str            # "f32" or "bf16"
+    d_model: int
+    d_ff: int
+    n_experts: int
+    top_k: int
+    n_shared: int = 0
+    n_layers: int = 1
+    batch_tokens: tuple = (16, 16, 16, 16)   # tokens per batch of the batch group
+    streamed: bool = False
+    window_layers: int = 0
+    zipf_s: float = 0.0                      # >0: skewed router targets
+    corr: float = 0.0                        # layer-to-layer routing correlation
+    seed: int = 0
+    w_std: float = 0.02
+
+    @property
+    def n_tokens(self) -> int:
+        return int(sum(self.batch_tokens))
+
+    @property
+    def n_batches(self) -> int:
+        return len(self.batch_tokens)
+
+    @property
+    def batch_offsets(self) -> np.ndarray:
+        return np.concatenate([[0], np.cumsum(self.batch_tokens)]).astype(np.int32)
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+    @property
+    def elt_bytes(self) -> int:
+        return 4 if self.dtype == "f32" else 2
+
+    @property
+    def expert_bytes(self) -> int:
+        return 3 * self.d_model * self.d_ff * self.elt_bytes
+
+
+# The five workloads the build is measured and checked on.
+WORKLOADS: Dict[str, Workload] = {
+    "tiny_f32": Workload("tiny_f32", "f32", 256, 512, 8, 2, batch_tokens=(16,) * 4),
+    "mixtral8x7b_decode": Workload("mixtral8x7b_decode", "bf16", 4096, 14336, 8, 2,
+                                   batch_tokens=(64,) * 8),
+    "mixtral8x7b_prefill": Workload("mixtral8x7b_prefill", "bf16", 4096, 14336, 8, 2,
+                                    batch_tokens=(8 * 512,) * 4),
+    "mixtral8x22b_stream": Workload("mixtral8x22b_stream", "bf16", 6144, 16384, 8, 2,
+                                    n_layers=8, batch_tokens=(32,) * 16, streamed=True,
+                                    window_layers=2),
+    "finegrained_stream": Workload("finegrained_stream", "bf16", 2048, 1408, 64, 6,
+                                   n_shared=2, n_layers=12, batch_tokens=(16,) * 32,
+                                   streamed=True, window_layers=2, zipf_s=1.1, corr=0.6),
+}
+
+
+def scaled(w: Workload, **kw) -> Workload:
+    """A copy of ``w`` with some fields replaced (smaller shapes for tests)."""
+    return replace(w, **kw)
+
+
+def _sub_seed(seed: int, layer: int, tid: int) -> int:
+    return seed * 10**6 + layer * 10**3 + tid
+
+
+def _normal(seed: int, layer: int, tid: int, shape, std: float) -> np.ndarray:
+    g = np.random.Generator(np.random.PCG64(_sub_seed(seed, layer, tid)))
+    a = g.standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        a *= np.float32(std)
+    return a
+
+
+def to_storage(a: np.ndarray, dtype: str) -> torch.Tensor:
+    """float32 array -> CPU torch tensor in the workload's storage type (RNE for bf16)."""
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    return t if dtype == "f32" else t.to(torch.bfloat16)
+
+
+def as_f32(t: torch.Tensor) -> np.ndarray:
+    """Exact float32 view of a stored tensor (bf16 widens exactly)."""
+    return t.detach().cpu().to(torch.float32).numpy()
+
+
+def as_raw(t: torch.Tensor) -> np.ndarray:
+    """Raw storage as NumPy: float32 array, or uint16 bit patterns for bf16."""
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+@dataclass
+class LayerData:
+    """All tensors of one MoE layer, as CPU torch tensors in storage dtype."""
+    x: torch.Tensor                       # [N, d]
+    wg: torch.Tensor                      # [E, d]
+    w1: List[torch.Tensor] = field(default_factory=list)   # E+S tensors [f, d]
+    w3: List[torch.Tensor] = field(default_factory=list)   # E+S tensors [f, d]
+    w2: List[torch.Tensor] = field(default_factory=list)   # E+S tensors [d, f]
+
+
+def gen_gate(w: Workload, layer: int = 0) -> torch.Tensor:
+    return to_storage(_normal(w.seed, layer, TID_WG, (w.n_experts, w.d_model), w.w_std), w.dtype)
+
+
+def gen_expert(w: Workload, layer: int, e: int):
+    """(W1 [f,d], W3 [f,d], W2 [d,f]) of expert e (e >= E: shared expert)."""
+    w1 = to_storage(_normal(w.seed, layer, tid_expert(e, 0), (w.d_ff, w.d_model), w.w_std), w.dtype)
+    w3 = to_storage(_normal(w.seed, layer, tid_expert(e, 1), (w.d_ff, w.d_model), w.w_std), w.dtype)
+    w2 = to_storage(_normal(w.seed, layer, tid_expert(e, 2), (w.d_model, w.d_ff), w.w_std), w.dtype)
+    return w1, w3, w2
+
+
+def gen_x_gaussian(w: Workload, layer: int = 0) -> torch.Tensor:
+    return to_storage(_normal(w.seed, layer, TID_X, (w.n_tokens, w.d_model), 1.0), w.dtype)
+
+
+def zipf_target_logits(w: Workload, layer: int, prev_noise: Optional[np.ndarray]):
+    """Target router logits with Zipf-skewed expert popularity and layer correlation.
+
+    Rank r (1..E) gets log-popularity -s*ln r; a seeded permutation maps ranks to
+    experts per layer.  Per token a Gumbel(0,1) noise vector is added (so the
+    top-k of the targets is a Zipf sample without replacement).  With probability
+    ``corr`` a token re-uses its noise vector of the previous layer, which keeps
+    its rank set and so ties its expert set to the previous layer's.
+    Returns (targets [N,E] float64, noise [N,E] float64).
+    """
+    E, N = w.n_experts, w.n_tokens
+    g = np.random.Generator(np.random.PCG64(_sub_seed(w.seed, layer, 900)))
+    rank_to_expert = g.permutation(E)
+    u = g.random((N, E))
+    noise = -np.log(-np.log(np.clip(u, 1e-12, 1.0 - 1e-12)))
+    if prev_noise is not None and w.corr > 0:
+        keep = g.random(N) < w.corr
+        noise[keep] = prev_noise[keep]
+    base = -w.zipf_s * np.log(np.arange(1, E + 1, dtype=np.float64))
+    by_rank = base[None, :] + noise
+    targets = np.empty_like(by_rank)
+    targets[:, rank_to_expert] = by_rank
+    return targets, noise
+
+
+def gen_x_for_targets(w: Workload, layer: int, wg: torch.Tensor, targets: np.ndarray) -> torch.Tensor:
+    """Activations whose gate logits come out as ``targets`` (up to storage rounding).
+
+    x = z - Wg^T (Wg Wg^T)^-1 (Wg z - target): the minimum-norm correction of a
+    Gaussian draw z onto the affine set {x : Wg x = target}.
+    """
+    z = _normal(w.seed, layer, TID_X, (w.n_tokens, w.d_model), 1.0).astype(np.float64)
+    g = as_f32(wg).astype(np.float64)
+    resid = z @ g.T - targets                       # [N, E]
+    corr = np.linalg.solve(g @ g.T, resid.T).T @ g  # [N, d]
+    return to_storage((z - corr).astype(np.float32), w.dtype)
+
+
+def gen_layer(w: Workload, layer: int = 0, prev_noise: Optional[np.ndarray] = None,
+              threads: int = 8, with_experts: bool = True):
+    """Generate one layer.  Returns (LayerData, noise) — noise feeds the next layer."""
+    wg = gen_gate(w, layer)
+    noise = None
+    if w.zipf_s > 0:
+        targets, noise = zipf_target_logits(w, layer, prev_noise)
+        x = gen_x_for_targets(w, layer, wg, targets)
+    else:
+        x = gen_x_gaussian(w, layer)
+    data = LayerData(x=x, wg=wg)
+    if with_experts:
+        n_all = w.n_experts + w.n_shared
+        with ThreadPoolExecutor(max_workers=max(1, threads)) as pool:
+            trip = list(pool.map(lambda e: gen_expert(w, layer, e), range(n_all)))
+        for w1, w3, w2 in trip:
+            data.w1.append(w1)
+            data.w3.append(w3)
+            data.w2.append(w2)
+    return data, noise
