@@ -1,0 +1,227 @@
+/*
+ * moe.h -- C ABI of the MI355X MoE-layer hot path (expert-aware multi-batch pipeline).
+ *
+ * One call sequence evaluates one Mixture-of-Experts layer for a whole batch group
+ * (the tokens of B batches concatenated), expert by expert rather than batch by batch,
+ * while the expert weights may live in pinned host memory and be streamed into a window
+ * of device slots (paper Section 5 and Algorithm 1, expert-layer branch; Section 6.1 for
+ * pinned host residency; Section 8, "Overlapping Computation and I/O", for the streams).
+ *
+ * Conventions
+ *  - Every entry point returns a moe_status; nothing throws, aborts or keeps
+ *    process-global state.  A failed call leaves the context usable; the reason is
+ *    available from moe_last_error().
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses,
+ *    "pinned" host pointers must come from hipHostMalloc (e.g. a pin_memory tensor).
+ *  - The caller owns all tensors, the workspace, the window and both streams
+ *    (hipStream_t passed as void*).  The library owns only the context, a few events
+ *    and a small pinned host mailbox.
+ *  - moe_route, moe_stream_experts and moe_layer_forward enqueue work and return;
+ *    results are valid once the compute stream has been synchronised.
+ *  - Row-major everywhere.  X, Y: [n_tokens, d_model].  W1, W3: [d_ff, d_model].
+ *    W2: [d_model, d_ff].  Wg: [n_experts, d_model].  Element type = config dtype.
+ *  - Assignment a = t*top_k + j sends token t to expert topk_idx[a] (slot j).
+ */
+#ifndef KLOTSKI_MOE_H
+#define KLOTSKI_MOE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx; /* opaque, library-owned */
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = 1, /* null pointer, bad enum, index out of range */
+    MOE_ERR_SHAPE = 2,       /* sizes the kernels do not support, or beyond the configured maxima */
+    MOE_ERR_STATE = 3,       /* call order violated (e.g. forward before route, weights not set) */
+    MOE_ERR_OOM = 4,         /* workspace or window too small */
+    MOE_ERR_NOT_PINNED = 5,  /* a host pointer that must be pinned is not */
+    MOE_ERR_HIP = 6          /* a HIP runtime call failed */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+typedef enum { MOE_RESIDENT = 0, MOE_HOST_PINNED = 1 } moe_residency;
+
+/* flags of moe_stream_experts */
+#define MOE_PREFETCH 1  /* issued before the gate ran: the caller's guess of the hot experts */
+#define MOE_ON_DEMAND 2 /* issued after the gate: experts the gate selected that are not in flight */
+
+#define MOE_MAX_EXPERTS 256 /* routed experts per layer */
+#define MOE_MAX_TOPK 8
+#define MOE_MAX_BATCHES 64
+#define MOE_MAX_SHARED 8
+
+typedef struct {
+    int32_t d_model;       /* d; bf16: multiple of 64, f32: multiple of 4 */
+    int32_t d_ff;          /* f; bf16: multiple of 64, f32: multiple of 4 */
+    int32_t n_experts;     /* E routed experts, 1..MOE_MAX_EXPERTS */
+    int32_t top_k;         /* k, 1..min(E, MOE_MAX_TOPK) */
+    int32_t n_shared;      /* S always-on experts (ids E..E+S-1), 0..MOE_MAX_SHARED */
+    int32_t n_layers;      /* MoE layers handled by one context */
+    int32_t window_layers; /* 0: all routed experts resident; >0: window of window_layers*E slots */
+    int32_t max_tokens;    /* largest batch group (tokens) a call may bring */
+    int32_t max_batches;   /* largest number of batches in a group, <= MOE_MAX_BATCHES */
+    int32_t dtype;         /* moe_dtype of X, Y and all weights */
+    int32_t renormalize;   /* 1: routing weights renormalised over the k winners; 0: full softmax */
+} moe_config;
+
+/* Sizes and first-order time estimates for one configuration (moe_plan). */
+typedef struct {
+    int64_t workspace_bytes; /* device scratch moe_create needs */
+    int64_t expert_bytes;    /* packed size of one expert = size of one window slot */
+    int64_t window_bytes;    /* n_slots * expert_bytes (0 when window_layers == 0) */
+    int32_t n_slots;         /* window_layers * n_experts */
+    int32_t reserved;
+    double t_io_expert_s;    /* expert_bytes / link_Bps: one expert over the host link */
+    double t_c_expert_s;     /* max(expert_bytes/hbm_Bps, flops/mfma_flops) at n_tokens*k/E rows */
+    double t_c_gate_s;       /* gate: bytes of X over hbm_Bps */
+} moe_plan_t;
+
+/* Counters of the streamed pipeline, cumulative since moe_create or moe_reset_stats. */
+typedef struct {
+    int64_t tokens;          /* tokens routed */
+    int64_t bytes_h2d;       /* expert bytes copied host -> device */
+    int64_t n_copies;        /* expert copies issued */
+    int64_t n_prefetch_hits; /* experts needed by a layer that were already in flight or resident */
+    int64_t n_prefetch_unused; /* prefetched experts that the gate then did not select */
+    int64_t n_forward;       /* moe_layer_forward calls */
+    int64_t n_active_sum;    /* sum over forwards of activated routed experts */
+} moe_stats;
+
+/*
+ * moe_plan -- host only, pure.  Sizes the workspace and the window for `cfg`, and prices one
+ * expert's transfer and compute at the given rates (bytes/s, bytes/s, flop/s) for a batch
+ * group of n_tokens tokens: the per-shape quantities the paper's planner measures
+ * (Section 7, stage "measurement"; t_IO_E and t_c_E of the inequality group).
+ * Errors: MOE_ERR_INVALID_ARG (null), MOE_ERR_SHAPE (unsupported sizes).
+ */
+moe_status moe_plan(const moe_config* cfg, int32_t n_tokens, double hbm_Bps, double link_Bps,
+                    double mfma_flops, moe_plan_t* out);
+
+/*
+ * moe_plan_batches -- host only, pure.  Smallest integer n (batches per batch group) that
+ * satisfies the four overlap inequalities of the paper's planner (Section 7, inequality
+ * group; the legend's t_c_topk-E is the formulas' t_c_hot-E; the sum runs over the queue Q
+ * of activated non-hot experts).  All times in seconds; t_c_E has len_q entries.
+ * Returns n >= 1 in *n_out; MOE_ERR_INVALID_ARG when t_c_A + t_c_G <= 0 while I/O is not.
+ */
+moe_status moe_plan_batches(double t_c_A, double t_c_G, double t_c_hotE, const double* t_c_E,
+                            int32_t len_q, double t_io_A, double t_io_G, double t_io_E, int32_t K,
+                            int32_t* n_out);
+
+/*
+ * moe_create -- build a context.  workspace_dev: device scratch of at least
+ * moe_plan().workspace_bytes, 256-byte aligned.  window_dev: device memory of at least
+ * window_bytes when cfg->window_layers > 0, else ignored (may be null).  Streams are
+ * hipStream_t; the copy stream must differ from the compute stream when a window is used.
+ * The buffers and streams must outlive the context.
+ */
+moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_stream,
+                      void* workspace_dev, int64_t workspace_bytes, void* window_dev,
+                      int64_t window_bytes, moe_ctx** out);
+
+/* moe_destroy -- synchronises both streams, releases events and the mailbox. */
+moe_status moe_destroy(moe_ctx* ctx);
+
+/* moe_set_gate -- register the gate matrix Wg [E, d] (device) of a layer.  Not copied. */
+moe_status moe_set_gate(moe_ctx* ctx, int32_t layer, const void* wg_dev);
+
+/*
+ * moe_set_expert -- offline placement of one expert (paper Section 4: placement happens in
+ * an offline phase before inference).  Reads W1, W3, W2 (device, row-major) and writes the
+ * expert's packed blob (moe_plan().expert_bytes bytes, a layout private to the library) to
+ * packed_dst: device memory when where == MOE_RESIDENT, pinned host memory when
+ * where == MOE_HOST_PINNED (requires a window; shared experts must be resident).
+ * Synchronous.  packed_dst must stay valid while the context lives; the sources need not.
+ * expert in [0, E) routed, [E, E+S) shared.
+ */
+moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const void* w1_dev,
+                          const void* w3_dev, const void* w2_dev, int32_t where, void* packed_dst);
+
+/*
+ * moe_route -- gate + dispatch plan of one layer for a batch group (Section 2.1: softmax gate,
+ * top-k; Section 5: expert layer divided by experts, hot experts first).
+ *   x_dev [n_tokens, d]; batch_offsets_host[n_batches+1], non-decreasing, starts at 0,
+ *   n_tokens = batch_offsets_host[n_batches] <= max_tokens (0 is allowed: no work).
+ * Optional device outputs (null = not wanted), all valid after the compute stream syncs:
+ *   logits_dev [n_tokens, E] f32      fp32 gate logits (fixed summation order)
+ *   topk_idx_dev [n_tokens, k] i32    winners by (logit desc, index asc)
+ *   topk_w_dev [n_tokens, k] f32      routing weights
+ *   counts_dev [E], offsets_dev [E+1] tokens per expert and their exclusive scan
+ *   perm_dev, inv_perm_dev [n_tokens*k] stable grouping of assignments by expert
+ *   exec_order_dev [E]                activated experts by (batches touching desc, tokens desc,
+ *                                     index asc); -1 beyond the activated ones
+ * counts and exec_order are also mailed to the host (see moe_route_wait).
+ */
+moe_status moe_route(moe_ctx* ctx, int32_t layer, const void* x_dev,
+                     const int32_t* batch_offsets_host, int32_t n_batches, float* logits_dev,
+                     int32_t* topk_idx_dev, float* topk_w_dev, int32_t* counts_dev,
+                     int32_t* offsets_dev, int32_t* perm_dev, int32_t* inv_perm_dev,
+                     int32_t* exec_order_dev);
+
+/*
+ * moe_route_wait -- block until the last moe_route's counts reached the host, then copy them
+ * out: counts_host[E], exec_order_host[E] (-1 padded), *n_active (any may be null).
+ * This is the point where the paper's pipeline learns which experts the gate selected and
+ * starts their on-demand transfers (Section 5).
+ */
+moe_status moe_route_wait(moe_ctx* ctx, int32_t* counts_host, int32_t* exec_order_host,
+                          int32_t* n_active);
+
+/*
+ * moe_stream_experts -- enqueue host->device copies of routed experts of `layer` on the copy
+ * stream, in the order given (Section 5: prefetch the hot experts before the gate, transfer
+ * the rest on demand after it, never transfer experts nobody selected).  Each expert goes to
+ * a free window slot; a slot is reused only after the kernels that read it have finished.
+ * Experts already resident or in flight for this layer are skipped.  With MOE_ON_DEMAND the
+ * ids must be among the experts the last moe_route activated.  Returns MOE_ERR_OOM if no
+ * slot can be freed (window smaller than one layer's activated experts plus prefetches).
+ */
+moe_status moe_stream_experts(moe_ctx* ctx, int32_t layer, const int32_t* expert_ids_host,
+                              int32_t n_ids, int32_t flags);
+
+/*
+ * moe_layer_forward -- Y = MoE layer(X) for the batch group of the last moe_route on this
+ * layer: grouped SwiGLU experts over each expert's tokens, in exec_order, then
+ * Y[t] = sum_j w[t,j]*FFN_{idx[t,j]}(X[t]) + sum_s FFN_{E+s}(X[t]) (Section 2.1).
+ * With a window, activated experts not yet in flight are transferred on demand first, each
+ * expert's kernels wait for its copy, and its slot is released right after its last kernel
+ * (Section 5, last sentence of "minimizing intra-layer bubbles").
+ * x_dev must be the tensor given to moe_route.  y_dev [n_tokens, d] in the config dtype.
+ */
+moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, void* y_dev);
+
+moe_status moe_get_stats(const moe_ctx* ctx, moe_stats* out);
+moe_status moe_reset_stats(moe_ctx* ctx);
+
+/*
+ * moe_set_tuning -- knobs, 0 keeps the current value.  split_k: split of the down projection's
+ * reduction (auto by default).  h_planes (bf16 only): 2 (default) carries the intermediate
+ * H = silu(X W1^T) .* (X W3^T) between the two GEMMs as a pair of bf16 numbers (value and
+ * rounding remainder), which keeps the layer inside the 1e-2 absolute tolerance at d_ff = 14336;
+ * 1 stores plain bf16 H (one third fewer MFMA operations, about twice the output error).
+ */
+moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t reserved);
+
+/*
+ * Per-kernel timing of the last moe_route + moe_layer_forward pair (all-resident layers only),
+ * taken with HIP events on the compute stream between the launches.  For the fp32 path up_ms is
+ * 0 and down_ms covers both expert kernels.  moe_get_profile blocks until that forward is done.
+ */
+typedef struct {
+    float router_ms, plan_ms, gather_ms, up_ms, down_ms, combine_ms;
+} moe_profile;
+moe_status moe_set_profiling(moe_ctx* ctx, int32_t enable);
+moe_status moe_get_profile(moe_ctx* ctx, moe_profile* out);
+
+/* Last error text of the context (or of the last failed moe_create/moe_plan when ctx is null). */
+const char* moe_last_error(const moe_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KLOTSKI_MOE_H */

@@ -35,6 +35,19 @@
 
 #define KO_LANES 64
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads the token loop of ko_moe_forward will use (reported beside timings). */
+int ko_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 /* ---- storage helpers ---------------------------------------------------- */
 
 /* bfloat16 bit pattern -> double (exact: bf16 is the top half of an fp32). */

@@ -49,6 +49,10 @@ def _i32(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
+def num_threads() -> int:
+    return int(lib().ko_num_threads())
+
+
 def vector_width(dtype: str) -> int:
     """Elements per 16-byte vector of the storage type (part of the logit order)."""
     return 4 if dtype == "f32" else 8

@@ -1,0 +1,228 @@
+// Dispatch plan: per-expert counts, prefix sums, stable grouping of assignments by expert,
+// execution order of the experts, and the tile tables the grouped FFN walks.
+//
+// The expert layer is evaluated expert by expert over the tokens of all batches of the batch
+// group, experts that serve the most batches / tokens first (paper Section 5).  Everything
+// here is integer work with a unique answer: histograms use LDS atomics (order-free), stable
+// ranks come from wavefront ballots and per-segment prefix sums.
+#include "kernels.h"
+
+namespace kmoe {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRounds = kPlanChunk / kThreads;  // 4
+constexpr int kSegs = kRounds * (kThreads / 64);  // 16 (round, wave) segments per chunk
+
+__device__ __forceinline__ int batch_of(const BatchOffsets& bo, int t) {
+    int lo = 0, hi = bo.n;  // find b with v[b] <= t < v[b+1]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (bo.v[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// P1: per chunk of assignments, tokens per expert and the set of batches touching each expert.
+__global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t* __restrict__ idx,
+                                                              int A, int E, int k, BatchOffsets bo,
+                                                              int32_t* __restrict__ blk_counts,
+                                                              unsigned long long* __restrict__ blk_mask) {
+    __shared__ int32_t cnt[kMaxExperts];
+    __shared__ unsigned long long msk[kMaxExperts];
+    for (int e = threadIdx.x; e < E; e += kThreads) {
+        cnt[e] = 0;
+        msk[e] = 0ull;
+    }
+    __syncthreads();
+    const int base = blockIdx.x * kPlanChunk;
+    for (int r = 0; r < kRounds; ++r) {
+        const int a = base + r * kThreads + threadIdx.x;
+        if (a < A) {
+            const int e = idx[a];
+            atomicAdd(&cnt[e], 1);
+            atomicOr(&msk[e], 1ull << batch_of(bo, a / k));
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kThreads) {
+        blk_counts[(size_t)blockIdx.x * E + e] = cnt[e];
+        blk_mask[(size_t)blockIdx.x * E + e] = msk[e];
+    }
+}
+
+// P2: one block.  Totals, scans, execution order, tile tables, host mail.
+__global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunks, PlanPtrs p,
+                                                             int max_tiles) {
+    __shared__ int32_t cnt[kMaxExperts];
+    __shared__ int32_t nbt[kMaxExperts];
+    __shared__ int32_t off[kMaxExperts + 1];
+    __shared__ int32_t pof[kMaxExperts + 1];
+    __shared__ int32_t ord[kMaxExperts];
+    __shared__ int32_t nact;
+    const int E = s.E, tid = threadIdx.x;
+    if (tid == 0) nact = 0;
+    for (int e = tid; e < E; e += kThreads) {
+        int run = 0;
+        unsigned long long m = 0ull;
+        for (int c = 0; c < nchunks; ++c) {
+            p.blk_base[(size_t)c * E + e] = run;
+            run += p.blk_counts[(size_t)c * E + e];
+            m |= p.blk_mask[(size_t)c * E + e];
+        }
+        cnt[e] = run;
+        nbt[e] = __popcll(m);
+        ord[e] = -1;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int o = 0, po = 0;
+        for (int e = 0; e < E; ++e) {
+            off[e] = o;
+            pof[e] = po;
+            o += cnt[e];
+            po += (cnt[e] + kRowBlk - 1) / kRowBlk * kRowBlk;
+        }
+        off[E] = o;
+        pof[E] = po;
+    }
+    __syncthreads();
+    // execution order: rank of e among the activated experts by (nbatch desc, count desc, e asc)
+    for (int e = tid; e < E; e += kThreads) {
+        if (cnt[e] > 0) {
+            int rank = 0;
+            for (int q = 0; q < E; ++q) {
+                if (q == e || cnt[q] == 0) continue;
+                const bool q_first = nbt[q] > nbt[e] ||
+                                     (nbt[q] == nbt[e] && (cnt[q] > cnt[e] || (cnt[q] == cnt[e] && q < e)));
+                rank += q_first ? 1 : 0;
+            }
+            ord[rank] = e;
+            atomicAdd(&nact, 1);
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += kThreads) {
+        p.counts[e] = cnt[e];
+        p.offsets[e] = off[e];
+        p.poff[e] = pof[e];
+        p.nbatch[e] = nbt[e];
+        p.exec_order[e] = ord[e];
+        p.mail[e] = cnt[e];
+        p.mail[E + e] = ord[e];
+        p.exp_tile0[e] = 0;
+        p.exp_ntiles[e] = 0;
+        const int b0 = pof[e] / kRowBlk, nb = (cnt[e] + kRowBlk - 1) / kRowBlk;
+        for (int b = 0; b < nb; ++b) p.blk_expert[b0 + b] = e;
+    }
+    if (tid == 0) {
+        p.offsets[E] = off[E];
+        p.poff[E] = pof[E];
+        p.mail[2 * E] = nact;
+        // tiles: shared experts first (they serve every batch), then routed in execution order
+        int nt = 0;
+        const int routed_blks = pof[E] / kRowBlk;
+        const int nblk_tok = (s.N + kRowBlk - 1) / kRowBlk;
+        for (int sh = 0; sh < s.S; ++sh) {
+            p.exp_tile0[E + sh] = nt;
+            for (int b = 0; b < nblk_tok && nt < max_tiles; b += kTileBlks) {
+                p.tile_expert[nt] = E + sh;
+                p.tile_xblk[nt] = routed_blks + b;
+                p.tile_hblk[nt] = routed_blks + sh * nblk_tok + b;
+                p.tile_nblk[nt] = min(kTileBlks, nblk_tok - b);
+                ++nt;
+            }
+            p.exp_ntiles[E + sh] = nt - p.exp_tile0[E + sh];
+        }
+        for (int i = 0; i < nact; ++i) {
+            const int e = ord[i];
+            const int b0 = pof[e] / kRowBlk, nb = (cnt[e] + kRowBlk - 1) / kRowBlk;
+            p.exp_tile0[e] = nt;
+            for (int b = 0; b < nb && nt < max_tiles; b += kTileBlks) {
+                p.tile_expert[nt] = e;
+                p.tile_xblk[nt] = b0 + b;
+                p.tile_hblk[nt] = b0 + b;
+                p.tile_nblk[nt] = min(kTileBlks, nb - b);
+                ++nt;
+            }
+            p.exp_ntiles[e] = nt - p.exp_tile0[e];
+        }
+        p.meta[0] = nact;
+        p.meta[1] = nt;
+        p.meta[2] = routed_blks;
+        p.meta[3] = s.N;
+    }
+}
+
+// P3: stable position of every assignment inside its expert's group.
+__global__ __launch_bounds__(kThreads) void plan_rank_kernel(const int32_t* __restrict__ idx, int A,
+                                                             int E, PlanPtrs p) {
+    __shared__ int32_t seg[kSegs][kMaxExperts];  // tokens of expert e in (round, wave) segment
+    for (int i = threadIdx.x; i < kSegs * kMaxExperts; i += kThreads) (&seg[0][0])[i] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int base = blockIdx.x * kPlanChunk;
+    int my_e[kRounds], my_rank[kRounds];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int a = base + r * kThreads + threadIdx.x;
+        const int e = a < A ? idx[a] : -1;
+        my_e[r] = e;
+        my_rank[r] = 0;
+        bool done = e < 0;
+        // group the wavefront's lanes by expert; every pass retires the leader's group
+        while (true) {
+            const unsigned long long pending = __ballot(!done);
+            if (pending == 0ull) break;
+            const int leader = __ffsll((long long)pending) - 1;
+            const int ev = __shfl(e, leader, 64);
+            const unsigned long long same = __ballot(e == ev);
+            if (e == ev) {
+                my_rank[r] = __popcll(same & ((1ull << lane) - 1ull));
+                if (lane == leader) seg[r * (kThreads / 64) + wave][ev] = __popcll(same);
+                done = true;
+            }
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kThreads) {  // exclusive scan over the 16 segments
+        int run = 0;
+#pragma unroll
+        for (int sg = 0; sg < kSegs; ++sg) {
+            const int c = seg[sg][e];
+            seg[sg][e] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int a = base + r * kThreads + threadIdx.x;
+        const int e = my_e[r];
+        if (e >= 0) {
+            const int pos = p.offsets[e] + p.blk_base[(size_t)blockIdx.x * E + e] +
+                            seg[r * (kThreads / 64) + wave][e] + my_rank[r];
+            p.inv_perm[a] = pos;
+            p.perm[pos] = a;
+        }
+    }
+}
+
+}  // namespace
+
+void launch_plan(hipStream_t st, const Shape& s, const BatchOffsets& bo, const PlanPtrs& p,
+                 int max_tiles) {
+    const int A = s.N * s.k;
+    const int nchunks = (A + kPlanChunk - 1) / kPlanChunk;
+    if (nchunks > 0) {
+        hipLaunchKernelGGL(plan_count_kernel, dim3(nchunks), dim3(kThreads), 0, st, p.topk_idx, A,
+                           s.E, s.k, bo, p.blk_counts, p.blk_mask);
+    }
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(kThreads), 0, st, s, nchunks, p, max_tiles);
+    if (nchunks > 0) {
+        hipLaunchKernelGGL(plan_rank_kernel, dim3(nchunks), dim3(kThreads), 0, st, p.topk_idx, A,
+                           s.E, p);
+    }
+}
+
+}  // namespace kmoe

@@ -1,0 +1,179 @@
+// Router: gate logits in a fixed fp32 summation order, wavefront top-k, routing weights.
+//
+// The gating network scores every expert for every token and the k best are activated
+// (paper Section 2.1).  One 64-lane wavefront serves one token.  The logit of (token, expert)
+// is accumulated in an order that a scalar program can reproduce exactly: the row is cut into
+// 16-byte vectors, vector c belongs to lane c mod 64, a lane folds its elements in increasing
+// index with fused multiply-adds, and the 64 partial sums meet in an xor butterfly
+// (32,16,...,1).  IEEE addition is commutative, so every lane ends with the same value.
+#include "kernels.h"
+
+namespace kmoe {
+namespace {
+
+constexpr int kRouterWaves = 4;
+constexpr int kEG = 8;  // experts accumulated together
+
+template <typename T>
+struct Chunk;
+
+template <>
+struct Chunk<float> {
+    static constexpr int V = 4;
+    static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+        float4 q = *reinterpret_cast<const float4*>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    }
+};
+
+struct bf16raw {
+    uint16_t bits;
+};
+
+template <>
+struct Chunk<bf16raw> {
+    static constexpr int V = 8;
+    static __device__ __forceinline__ void load(const bf16raw* p, float (&v)[8]) {
+        uint4 q = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);            // low half = lower index
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
+struct Cand {
+    float v;
+    int e;  // -1: none
+};
+
+__device__ __forceinline__ bool better(const Cand& a, const Cand& b) {
+    if (a.e < 0) return false;
+    if (b.e < 0) return true;
+    return a.v > b.v || (a.v == b.v && a.e < b.e);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kRouterWaves * 64) void router_kernel(
+    const T* __restrict__ X, const T* __restrict__ Wg, int N, int d, int E, int k, int renorm,
+    float* __restrict__ logits_out, int32_t* __restrict__ idx_out, float* __restrict__ w_out) {
+    constexpr int V = Chunk<T>::V;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * kRouterWaves + (threadIdx.x >> 6);
+    if (t >= N) return;  // whole wavefront leaves; no block-wide synchronisation below
+    const int nchunk = d / V;
+    const T* xrow = X + (size_t)t * d;
+
+    float mine[4];  // logits of experts lane, lane+64, lane+128, lane+192
+#pragma unroll
+    for (int s = 0; s < 4; ++s) mine[s] = 0.f;
+
+    for (int e0 = 0; e0 < E; e0 += kEG) {
+        float acc[kEG];
+#pragma unroll
+        for (int j = 0; j < kEG; ++j) acc[j] = 0.f;
+        for (int c = lane; c < nchunk; c += 64) {
+            float xv[V];
+            Chunk<T>::load(xrow + (size_t)c * V, xv);
+#pragma unroll
+            for (int j = 0; j < kEG; ++j) {
+                if (e0 + j < E) {
+                    float wv[V];
+                    Chunk<T>::load(Wg + (size_t)(e0 + j) * d + (size_t)c * V, wv);
+#pragma unroll
+                    for (int i = 0; i < V; ++i) acc[j] = __builtin_fmaf(xv[i], wv[i], acc[j]);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kEG; ++j) {
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) acc[j] = acc[j] + __shfl_xor(acc[j], m, 64);
+            const int e = e0 + j;
+            if (e < E) {
+                if (logits_out != nullptr && lane == 0) logits_out[(size_t)t * E + e] = acc[j];
+                if ((e & 63) == lane) {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+                        if ((e >> 6) == s) mine[s] = acc[j];
+                }
+            }
+        }
+    }
+
+    // top-k by (logit desc, index asc): k rounds of a wavefront arg-max
+    bool taken[4] = {false, false, false, false};
+    float selv[kMaxTopK];
+    int sele[kMaxTopK];
+#pragma unroll
+    for (int j = 0; j < kMaxTopK; ++j) {
+        selv[j] = 0.f;
+        sele[j] = 0;
+        if (j < k) {
+            Cand best{0.f, -1};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int e = lane + 64 * s;
+                Cand c{mine[s], (e < E && !taken[s]) ? e : -1};
+                if (better(c, best)) best = c;
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) {
+                Cand o{__shfl_xor(best.v, m, 64), __shfl_xor(best.e, m, 64)};
+                if (better(o, best)) best = o;
+            }
+            best.v = __shfl(best.v, 0, 64);
+            best.e = __shfl(best.e, 0, 64);
+            selv[j] = best.v;
+            sele[j] = best.e;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                if (best.e == lane + 64 * s) taken[s] = true;
+        }
+    }
+
+    // routing weights: softmax over all experts, renormalised over the winners (or not)
+    const float mx = selv[0];
+    float den = 0.f;
+    if (renorm) {
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j)
+            if (j < k) den += expf(selv[j] - mx);
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            if (lane + 64 * s < E) den += expf(mine[s] - mx);
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) den += __shfl_xor(den, m, 64);
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j) {
+            if (j < k) {
+                idx_out[(size_t)t * k + j] = sele[j];
+                w_out[(size_t)t * k + j] = expf(selv[j] - mx) / den;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+void launch_router(hipStream_t st, int dtype, const void* x, const void* wg, const Shape& s,
+                   float* logits_out, int32_t* idx_out, float* w_out) {
+    if (s.N <= 0) return;
+    dim3 grid((s.N + kRouterWaves - 1) / kRouterWaves), block(kRouterWaves * 64);
+    if (dtype == 0) {
+        hipLaunchKernelGGL(router_kernel<float>, grid, block, 0, st, (const float*)x,
+                           (const float*)wg, s.N, s.d, s.E, s.k, s.renorm, logits_out, idx_out,
+                           w_out);
+    } else {
+        hipLaunchKernelGGL(router_kernel<bf16raw>, grid, block, 0, st, (const bf16raw*)x,
+                           (const bf16raw*)wg, s.N, s.d, s.E, s.k, s.renorm, logits_out, idx_out,
+                           w_out);
+    }
+}
+
+}  // namespace kmoe

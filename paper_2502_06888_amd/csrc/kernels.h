@@ -1,0 +1,106 @@
+// Internal interface between the C-ABI host code and the HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kmoe {
+
+constexpr int kLanes = 64;
+constexpr int kRowBlk = 16;        // rows (tokens) per MFMA block
+constexpr int kTileBlks = 16;      // row blocks per tile (256 rows)
+constexpr int kPlanChunk = 1024;   // assignments per block of the dispatch kernels
+constexpr int kMaxExperts = 256;
+constexpr int kMaxTopK = 8;
+constexpr int kMaxBatches = 64;
+
+// Capacity of the tile tables for a context.
+inline int max_tiles_for(int max_rows16, int E, int S, int max_tokens) {
+    return max_rows16 / kTileBlks + E + S * ((max_tokens + 255) / 256 + 1) + 1;
+}
+
+struct BatchOffsets {
+    int32_t n;
+    int32_t v[kMaxBatches + 1];
+};
+
+// Device pointers of one context's dispatch plan (all inside the caller's workspace).
+struct PlanPtrs {
+    int32_t* topk_idx;    // [A]
+    float* topk_w;        // [A]
+    int32_t* counts;      // [E]
+    int32_t* offsets;     // [E+1]
+    int32_t* poff;        // [E+1]  16-padded row offsets by expert id
+    int32_t* nbatch;      // [E]
+    int32_t* exec_order;  // [E]
+    int32_t* meta;        // [0] n_active  [1] n_tiles  [2] n_blk16 (routed)  [3] n_tokens
+    int32_t* perm;        // [A]
+    int32_t* inv_perm;    // [A]
+    int32_t* blk_counts;  // [nchunks][E]
+    int32_t* blk_base;    // [nchunks][E]
+    unsigned long long* blk_mask;  // [nchunks][E]
+    int32_t* tile_expert; // [max_tiles]   expert id (E+s for shared)
+    int32_t* tile_xblk;   // [max_tiles]   first 16-row block in the packed activations
+    int32_t* tile_hblk;   // [max_tiles]   first 16-row block in H / O
+    int32_t* tile_nblk;   // [max_tiles]   row blocks in this tile (1..16)
+    int32_t* exp_tile0;   // [E+S] first tile of an expert
+    int32_t* exp_ntiles;  // [E+S]
+    int32_t* blk_expert;  // [max_blk16]   routed expert owning a 16-row block
+    int32_t* mail;        // [2E+1] counts, exec_order, n_active (copied to the host mailbox)
+};
+
+struct Shape {
+    int32_t N, d, f, E, k, S;
+    int32_t renorm;
+    int32_t max_rows16;   // capacity of the routed padded-row space, in 16-row blocks
+};
+
+// ---- router -------------------------------------------------------------------------------
+void launch_router(hipStream_t st, int dtype, const void* x, const void* wg, const Shape& s,
+                   float* logits_out, int32_t* idx_out, float* w_out);
+
+// ---- dispatch plan ------------------------------------------------------------------------
+void launch_plan(hipStream_t st, const Shape& s, const BatchOffsets& bo, const PlanPtrs& p,
+                 int max_tiles);
+
+// ---- bf16 path ----------------------------------------------------------------------------
+// Offline packing of one expert (W1,W3 [f,d]; W2 [d,f]) into the fragment-ordered blob.
+void launch_pack_expert_bf16(hipStream_t st, const void* w1, const void* w3, const void* w2,
+                             int d, int f, void* blob);
+// Gather token rows per expert (and the plain rows for shared experts) into fragment order.
+void launch_gather_bf16(hipStream_t st, const void* x, const Shape& s, const PlanPtrs& p,
+                        void* xp);
+
+struct FfnArgs {
+    const uint8_t* const* wtab;  // device table: blob of expert id e (may hold nulls for streamed)
+    const uint8_t* w_single;     // non-null: use this blob for every tile of the launch
+    const void* act;             // packed activations (Xp for up, Hp for down)
+    void* out;                   // Hp (up) or O partials (down)
+    const int32_t* tile_expert;
+    const int32_t* tile_xblk;
+    const int32_t* tile_hblk;
+    const int32_t* tile_nblk;
+    const int32_t* tile_first;   // device: index of the first tile of this launch (null = 0)
+    const int32_t* tile_count;   // device: number of tiles of this launch
+    int32_t max_tiles;           // tiles the grid was sized for
+    int32_t d, f;
+    int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder)
+    int64_t h_plane_units;       // 16-byte units between the two planes of H
+    int32_t split_k;             // down projection only
+    int64_t o_split_stride;      // elements between split-K partials of O
+};
+void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a);
+void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a);
+int ffn_configure();  // one-time function attributes (dynamic LDS); returns hipError_t
+
+// Y[t] = sum_j w[t,j] * sum_s O[s][row(t,j)] + shared rows; one rounding to the output type.
+void launch_combine(hipStream_t st, int out_dtype, const Shape& s, const PlanPtrs& p,
+                    const float* o, int split_k, int64_t o_split_stride, void* y);
+
+// ---- f32 path (plain row-major blobs: W1 | W3 | W2) ------------------------------------------
+void launch_pack_expert_f32(hipStream_t st, const void* w1, const void* w3, const void* w2, int d,
+                            int f, void* blob);
+void launch_ffn_f32(hipStream_t st, const float* x, const Shape& s, const PlanPtrs& p,
+                    const uint8_t* const* wtab, const uint8_t* w_single, int32_t only_expert,
+                    float* h, float* o);
+
+}  // namespace kmoe

@@ -1,0 +1,834 @@
+// C-ABI of the MoE-layer hot path: context, offline placement, routing, expert streaming and
+// the layer forward.  Host logic only; the kernels live in the k_*.hip files.
+//
+// Pipeline (paper Section 5 / Algorithm 1, expert-layer branch): prefetch the experts the
+// caller expects to be hot before the gate runs; run the gate for all batches of the group at
+// once; start on-demand transfers for the activated experts that are not in flight; run the
+// experts in execution order, each one as soon as its weights have landed; release an
+// expert's slot right after its last kernel.  Copies run on a dedicated stream and are tied
+// to the compute stream by per-slot events (Section 8, "Overlapping Computation and I/O").
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/moe.h"
+#include "kernels.h"
+
+using namespace kmoe;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+struct Layout {
+    int64_t A = 0, max_rows16 = 0, tok_rows16 = 0, x_rows16 = 0, h_rows16 = 0;
+    int32_t nchunks = 0, max_tiles = 0, split_cap = 1;
+    int64_t expert_bytes = 0;
+    // byte offsets into the workspace
+    int64_t topk_idx, topk_w, counts, offsets, poff, nbatch, exec_order, meta, perm, inv_perm,
+        blk_counts, blk_base, blk_mask, tile_expert, tile_xblk, tile_hblk, tile_nblk, exp_tile0,
+        exp_ntiles, blk_expert, mail, wtab, xp, h, o;
+    int64_t o_split_stride = 0;  // elements
+    int64_t h_plane_units = 0;   // 16-byte units between the two bf16 planes of H
+    int64_t total = 0;
+};
+
+int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+moe_status check_config(const moe_config* c, std::string& err) {
+    auto bad = [&](const char* m, moe_status s) {
+        err = m;
+        return s;
+    };
+    if (!c) return bad("config is null", MOE_ERR_INVALID_ARG);
+    if (c->dtype != MOE_F32 && c->dtype != MOE_BF16) return bad("dtype must be MOE_F32 or MOE_BF16", MOE_ERR_INVALID_ARG);
+    if (c->d_model <= 0 || c->d_ff <= 0) return bad("d_model and d_ff must be positive", MOE_ERR_SHAPE);
+    const int mult = c->dtype == MOE_BF16 ? 64 : 4;
+    if (c->d_model % mult || c->d_ff % mult)
+        return bad(c->dtype == MOE_BF16 ? "bf16 needs d_model and d_ff to be multiples of 64"
+                                        : "f32 needs d_model and d_ff to be multiples of 4",
+                   MOE_ERR_SHAPE);
+    if (c->n_experts < 1 || c->n_experts > MOE_MAX_EXPERTS) return bad("n_experts out of range", MOE_ERR_SHAPE);
+    if (c->top_k < 1 || c->top_k > MOE_MAX_TOPK || c->top_k > c->n_experts) return bad("top_k out of range", MOE_ERR_SHAPE);
+    if (c->n_shared < 0 || c->n_shared > MOE_MAX_SHARED) return bad("n_shared out of range", MOE_ERR_SHAPE);
+    if (c->n_layers < 1) return bad("n_layers must be >= 1", MOE_ERR_SHAPE);
+    if (c->window_layers < 0 || c->window_layers > c->n_layers) return bad("window_layers out of range", MOE_ERR_SHAPE);
+    if (c->max_tokens < 1 || (int64_t)c->max_tokens * c->top_k > (1 << 28)) return bad("max_tokens out of range", MOE_ERR_SHAPE);
+    if (c->max_batches < 1 || c->max_batches > MOE_MAX_BATCHES) return bad("max_batches out of range", MOE_ERR_SHAPE);
+    return MOE_OK;
+}
+
+void compute_layout(const moe_config& c, Layout& L) {
+    const int64_t E = c.n_experts, S = c.n_shared, k = c.top_k, d = c.d_model, f = c.d_ff;
+    const int64_t elt = c.dtype == MOE_BF16 ? 2 : 4;
+    L.A = (int64_t)c.max_tokens * k;
+    L.max_rows16 = (L.A + kRowBlk - 1) / kRowBlk + E;
+    L.tok_rows16 = ((int64_t)c.max_tokens + kRowBlk - 1) / kRowBlk;
+    L.x_rows16 = L.max_rows16 + (S > 0 ? L.tok_rows16 : 0);
+    L.h_rows16 = L.max_rows16 + S * L.tok_rows16;
+    L.nchunks = (int32_t)((L.A + kPlanChunk - 1) / kPlanChunk);
+    L.max_tiles = max_tiles_for((int)L.max_rows16, (int)E, (int)S, c.max_tokens);
+    L.split_cap = (c.dtype == MOE_BF16 && L.A <= 8192) ? 8 : 1;
+    L.expert_bytes = 3 * d * f * elt;
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        int64_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    L.topk_idx = take(L.A * 4);
+    L.topk_w = take(L.A * 4);
+    L.counts = take(E * 4);
+    L.offsets = take((E + 1) * 4);
+    L.poff = take((E + 1) * 4);
+    L.nbatch = take(E * 4);
+    L.exec_order = take(E * 4);
+    L.meta = take(16 * 4);
+    L.perm = take(L.A * 4);
+    L.inv_perm = take(L.A * 4);
+    L.blk_counts = take((int64_t)L.nchunks * E * 4);
+    L.blk_base = take((int64_t)L.nchunks * E * 4);
+    L.blk_mask = take((int64_t)L.nchunks * E * 8);
+    L.tile_expert = take((int64_t)L.max_tiles * 4);
+    L.tile_xblk = take((int64_t)L.max_tiles * 4);
+    L.tile_hblk = take((int64_t)L.max_tiles * 4);
+    L.tile_nblk = take((int64_t)L.max_tiles * 4);
+    L.exp_tile0 = take((E + S) * 4);
+    L.exp_ntiles = take((E + S) * 4);
+    L.blk_expert = take(L.max_rows16 * 4);
+    L.mail = take((2 * E + 1) * 4);
+    L.wtab = take((int64_t)c.n_layers * (E + S) * 8);
+    const int64_t h_rows = L.h_rows16 * kRowBlk;
+    if (c.dtype == MOE_BF16) {
+        L.xp = take(L.x_rows16 * kRowBlk * d * 2);
+        L.h_plane_units = h_rows * f * 2 / 16;
+        L.h = take(2 * h_rows * f * 2);  // H as a bf16 pair: value plane + remainder plane
+    } else {
+        L.xp = off;
+        L.h = take(h_rows * f * 4);
+    }
+    L.o_split_stride = h_rows * d;
+    L.o = take((int64_t)L.split_cap * L.o_split_stride * 4);
+    L.total = off;
+}
+
+enum SlotState { SLOT_FREE = 0, SLOT_LOADED = 1 };
+
+struct Slot {
+    uint8_t* ptr = nullptr;
+    int layer = -1, expert = -1;
+    SlotState state = SLOT_FREE;
+    bool prefetched = false;
+    hipEvent_t ready = nullptr;  // copy landed (recorded on the copy stream)
+    hipEvent_t done = nullptr;   // last reader finished (recorded on the compute stream)
+    bool done_pending = false;
+};
+
+struct LayerState {
+    const void* wg = nullptr;
+    std::vector<const uint8_t*> resident;  // E+S device blobs (null if not resident)
+    std::vector<const uint8_t*> host;      // E pinned host blobs (null if resident)
+    std::vector<int> slot_of;              // E: window slot holding the expert, or -1
+};
+
+struct HostTile {
+    int first = 0, count = 0;
+};
+
+}  // namespace
+
+struct moe_ctx {
+    moe_config cfg{};
+    Layout L;
+    hipStream_t compute = nullptr, copy = nullptr;
+    uint8_t* ws = nullptr;
+    uint8_t* window = nullptr;
+    PlanPtrs plan{};
+    const uint8_t** wtab_dev = nullptr;  // [n_layers][E+S]
+    std::vector<LayerState> layers;
+    std::vector<Slot> slots;
+    int32_t* mailbox = nullptr;  // pinned host, 2E+1
+    hipEvent_t route_ev = nullptr;
+    // state of the last moe_route
+    int routed_layer = -1;
+    int routed_tokens = 0;
+    const void* routed_x = nullptr;
+    bool route_pending = false;  // mailbox not read yet
+    bool host_plan_valid = false;
+    std::vector<int32_t> h_counts, h_order;
+    int h_nactive = 0;
+    std::vector<HostTile> h_tiles;  // per expert id (E+S)
+    int split_k_user = 0;
+    int h_planes = 2;  // bf16 path: carry H as value + rounding remainder (2) or as plain bf16 (1)
+    moe_stats stats{};
+    bool profiling = false;
+    hipEvent_t pev[8] = {};  // router start, router end, plan end, fwd start, gather, up, down, combine
+    bool prof_route = false, prof_fwd = false;
+    mutable std::string err;
+};
+
+namespace {
+
+moe_status fail(const moe_ctx* ctx, moe_status s, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf;
+    g_last_error = buf;
+    return s;
+}
+
+#define HIP_TRY(ctx, expr)                                                                   \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fail(ctx, MOE_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));    \
+    } while (0)
+
+bool is_pinned_host(const void* p) {
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();  // clear the sticky error of an unregistered pointer
+        return false;
+    }
+    return at.type == hipMemoryTypeHost;
+}
+
+Shape make_shape(const moe_ctx* c, int n_tokens) {
+    Shape s;
+    s.N = n_tokens;
+    s.d = c->cfg.d_model;
+    s.f = c->cfg.d_ff;
+    s.E = c->cfg.n_experts;
+    s.k = c->cfg.top_k;
+    s.S = c->cfg.n_shared;
+    s.renorm = c->cfg.renormalize;
+    s.max_rows16 = (int32_t)c->L.max_rows16;
+    return s;
+}
+
+bool all_resident_layer(const moe_ctx* c, int layer) {
+    for (const uint8_t* p : c->layers[layer].resident)
+        if (!p) return false;
+    return true;
+}
+
+int auto_split_k(const moe_ctx* c, int n_tokens) {
+    if (c->cfg.dtype != MOE_BF16) return 1;
+    int cap = c->L.split_cap;
+    const int nstage = c->cfg.d_ff / 64;
+    cap = std::min(cap, nstage);
+    if (c->split_k_user > 0) return std::min(c->split_k_user, cap);
+    const int64_t A = (int64_t)n_tokens * c->cfg.top_k;
+    const int64_t tiles = std::max<int64_t>(std::min<int64_t>(c->cfg.n_experts, A), (A + 255) / 256) +
+                          (int64_t)c->cfg.n_shared * ((n_tokens + 255) / 256);
+    const int64_t groups = (c->cfg.d_model / 32 + 7) / 8;
+    const int64_t wgs = std::max<int64_t>(1, tiles * groups);
+    int64_t want = (512 + wgs - 1) / wgs;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(want, cap));
+}
+
+// Host mirror of the device tile enumeration (plan_scan_kernel): shared experts first, then the
+// routed experts in execution order, 16 row blocks per tile.
+void build_host_tiles(moe_ctx* c) {
+    const int E = c->cfg.n_experts, S = c->cfg.n_shared;
+    c->h_tiles.assign(E + S, HostTile{});
+    int nt = 0;
+    const int nblk_tok = (c->routed_tokens + kRowBlk - 1) / kRowBlk;
+    for (int sh = 0; sh < S; ++sh) {
+        c->h_tiles[E + sh].first = nt;
+        nt += (nblk_tok + kTileBlks - 1) / kTileBlks;
+        c->h_tiles[E + sh].count = nt - c->h_tiles[E + sh].first;
+    }
+    for (int i = 0; i < c->h_nactive; ++i) {
+        const int e = c->h_order[i];
+        const int nb = (c->h_counts[e] + kRowBlk - 1) / kRowBlk;
+        c->h_tiles[e].first = nt;
+        nt += (nb + kTileBlks - 1) / kTileBlks;
+        c->h_tiles[e].count = nt - c->h_tiles[e].first;
+    }
+}
+
+moe_status wait_route(moe_ctx* ctx) {
+    if (ctx->routed_layer < 0) return fail(ctx, MOE_ERR_STATE, "moe_route has not been called");
+    if (ctx->route_pending) {
+        HIP_TRY(ctx, hipEventSynchronize(ctx->route_ev));
+        const int E = ctx->cfg.n_experts;
+        ctx->h_counts.assign(ctx->mailbox, ctx->mailbox + E);
+        ctx->h_order.assign(ctx->mailbox + E, ctx->mailbox + 2 * E);
+        ctx->h_nactive = ctx->mailbox[2 * E];
+        ctx->route_pending = false;
+        ctx->host_plan_valid = true;
+        ctx->stats.n_active_sum += ctx->h_nactive;
+        build_host_tiles(ctx);
+    }
+    return MOE_OK;
+}
+
+void release_slot(moe_ctx* ctx, Slot& s, bool record_done) {
+    if (s.layer >= 0 && s.expert >= 0) ctx->layers[s.layer].slot_of[s.expert] = -1;
+    if (record_done) {
+        (void)hipEventRecord(s.done, ctx->compute);
+        s.done_pending = true;
+    }
+    s.layer = -1;
+    s.expert = -1;
+    s.state = SLOT_FREE;
+    s.prefetched = false;
+}
+
+moe_status stream_one(moe_ctx* ctx, int layer, int e, bool prefetch) {
+    LayerState& ls = ctx->layers[layer];
+    if (ls.resident[e]) return MOE_OK;  // nothing to move
+    if (!ls.host[e]) return fail(ctx, MOE_ERR_STATE, "layer %d expert %d has no weights", layer, e);
+    if (ls.slot_of[e] >= 0) return MOE_OK;  // already in flight or loaded
+    int pick = -1;
+    for (size_t i = 0; i < ctx->slots.size(); ++i)
+        if (ctx->slots[i].state == SLOT_FREE) {
+            pick = (int)i;
+            break;
+        }
+    if (pick < 0) return fail(ctx, MOE_ERR_OOM, "no free window slot for layer %d expert %d", layer, e);
+    Slot& s = ctx->slots[pick];
+    if (s.done_pending) {  // the slot's previous readers must finish before it is overwritten
+        HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, s.done, 0));
+        s.done_pending = false;
+    }
+    HIP_TRY(ctx, hipMemcpyAsync(s.ptr, ls.host[e], (size_t)ctx->L.expert_bytes, hipMemcpyHostToDevice,
+                                ctx->copy));
+    HIP_TRY(ctx, hipEventRecord(s.ready, ctx->copy));
+    s.layer = layer;
+    s.expert = e;
+    s.state = SLOT_LOADED;
+    s.prefetched = prefetch;
+    ls.slot_of[e] = pick;
+    ctx->stats.bytes_h2d += ctx->L.expert_bytes;
+    ctx->stats.n_copies += 1;
+    return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_last_error(const moe_ctx* ctx) { return ctx ? ctx->err.c_str() : g_last_error.c_str(); }
+
+moe_status moe_plan(const moe_config* cfg, int32_t n_tokens, double hbm_Bps, double link_Bps,
+                    double mfma_flops, moe_plan_t* out) {
+    std::string err;
+    moe_status st = check_config(cfg, err);
+    if (st != MOE_OK) return fail(nullptr, st, "%s", err.c_str());
+    if (!out) return fail(nullptr, MOE_ERR_INVALID_ARG, "out is null");
+    if (n_tokens < 0 || n_tokens > cfg->max_tokens)
+        return fail(nullptr, MOE_ERR_SHAPE, "n_tokens %d outside [0, max_tokens]", n_tokens);
+    Layout L;
+    compute_layout(*cfg, L);
+    memset(out, 0, sizeof *out);
+    out->workspace_bytes = L.total;
+    out->expert_bytes = L.expert_bytes;
+    out->n_slots = cfg->window_layers * cfg->n_experts;
+    out->window_bytes = (int64_t)out->n_slots * L.expert_bytes;
+    const double elt = cfg->dtype == MOE_BF16 ? 2.0 : 4.0;
+    const double rows = (double)n_tokens * cfg->top_k / cfg->n_experts;
+    const double flops = 6.0 * cfg->d_model * (double)cfg->d_ff * rows;
+    out->t_io_expert_s = link_Bps > 0 ? (double)L.expert_bytes / link_Bps : 0.0;
+    const double t_mem = hbm_Bps > 0 ? (double)L.expert_bytes / hbm_Bps : 0.0;
+    const double t_alu = mfma_flops > 0 ? flops / mfma_flops : 0.0;
+    out->t_c_expert_s = std::max(t_mem, t_alu);
+    out->t_c_gate_s = hbm_Bps > 0 ? (double)n_tokens * cfg->d_model * elt / hbm_Bps : 0.0;
+    return MOE_OK;
+}
+
+moe_status moe_plan_batches(double t_c_A, double t_c_G, double t_c_hotE, const double* t_c_E,
+                            int32_t len_q, double t_io_A, double t_io_G, double t_io_E, int32_t K,
+                            int32_t* n_out) {
+    if (!n_out || len_q < 0 || K < 0 || (len_q > 0 && !t_c_E))
+        return fail(nullptr, MOE_ERR_INVALID_ARG, "bad argument to moe_plan_batches");
+    const double vals[] = {t_c_A, t_c_G, t_c_hotE, t_io_A, t_io_G, t_io_E};
+    for (double v : vals)
+        if (!(v >= 0.0)) return fail(nullptr, MOE_ERR_INVALID_ARG, "times must be >= 0");
+    double sum_q = 0.0;
+    for (int i = 0; i < len_q; ++i) {
+        if (!(t_c_E[i] >= 0.0)) return fail(nullptr, MOE_ERR_INVALID_ARG, "times must be >= 0");
+        sum_q += t_c_E[i];
+    }
+    // n * lhs_rate + lhs_const >= rhs, one row per arrow of the pipeline figure (I..IV)
+    struct Row {
+        double rate, lhs_const, rhs;
+    };
+    std::vector<Row> rows;
+    rows.push_back({t_c_A, 0.0, t_io_G});
+    rows.push_back({t_c_A + t_c_G, 0.0, t_io_G + K * t_io_E});
+    if (len_q > 0) {  // with no cold expert queued the last two conditions do not apply
+        rows.push_back({t_c_A + t_c_G, t_c_hotE, t_io_G + (K + 1) * t_io_E});
+        rows.push_back({t_c_A + t_c_G, t_c_hotE + sum_q, t_io_G + (K + len_q) * t_io_E + t_io_A});
+    }
+    long long n = 1;
+    for (const Row& r : rows) {
+        const double need = r.rhs - r.lhs_const;
+        if (need <= 0.0) continue;
+        if (!(r.rate > 0.0))
+            return fail(nullptr, MOE_ERR_INVALID_ARG, "no compute time to overlap the I/O with");
+        const double x = need / r.rate;
+        long long c = (long long)x;
+        if ((double)c < x) ++c;
+        n = std::max(n, c);
+    }
+    if (n > INT32_MAX) n = INT32_MAX;
+    *n_out = (int32_t)n;
+    return MOE_OK;
+}
+
+moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_stream,
+                      void* workspace_dev, int64_t workspace_bytes, void* window_dev,
+                      int64_t window_bytes, moe_ctx** out) {
+    std::string err;
+    moe_status st = check_config(cfg, err);
+    if (st != MOE_OK) return fail(nullptr, st, "%s", err.c_str());
+    if (!out) return fail(nullptr, MOE_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (!workspace_dev) return fail(nullptr, MOE_ERR_INVALID_ARG, "workspace is null");
+    if (((uintptr_t)workspace_dev & 255u) != 0) return fail(nullptr, MOE_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    Layout L;
+    compute_layout(*cfg, L);
+    if (workspace_bytes < L.total)
+        return fail(nullptr, MOE_ERR_OOM, "workspace of %lld bytes, need %lld", (long long)workspace_bytes, (long long)L.total);
+    const int n_slots = cfg->window_layers * cfg->n_experts;
+    if (n_slots > 0) {
+        if (!window_dev) return fail(nullptr, MOE_ERR_INVALID_ARG, "window is null");
+        if (((uintptr_t)window_dev & 255u) != 0) return fail(nullptr, MOE_ERR_INVALID_ARG, "window must be 256-byte aligned");
+        if (window_bytes < (int64_t)n_slots * L.expert_bytes)
+            return fail(nullptr, MOE_ERR_OOM, "window of %lld bytes, need %lld", (long long)window_bytes, (long long)n_slots * L.expert_bytes);
+        if (compute_stream == copy_stream)
+            return fail(nullptr, MOE_ERR_INVALID_ARG, "streaming needs a copy stream distinct from the compute stream");
+    }
+    moe_ctx* c = new (std::nothrow) moe_ctx();
+    if (!c) return fail(nullptr, MOE_ERR_OOM, "out of host memory");
+    c->cfg = *cfg;
+    c->L = L;
+    c->compute = (hipStream_t)compute_stream;
+    c->copy = (hipStream_t)copy_stream;
+    c->ws = (uint8_t*)workspace_dev;
+    c->window = (uint8_t*)window_dev;
+    uint8_t* w = c->ws;
+    PlanPtrs& p = c->plan;
+    p.topk_idx = (int32_t*)(w + L.topk_idx);
+    p.topk_w = (float*)(w + L.topk_w);
+    p.counts = (int32_t*)(w + L.counts);
+    p.offsets = (int32_t*)(w + L.offsets);
+    p.poff = (int32_t*)(w + L.poff);
+    p.nbatch = (int32_t*)(w + L.nbatch);
+    p.exec_order = (int32_t*)(w + L.exec_order);
+    p.meta = (int32_t*)(w + L.meta);
+    p.perm = (int32_t*)(w + L.perm);
+    p.inv_perm = (int32_t*)(w + L.inv_perm);
+    p.blk_counts = (int32_t*)(w + L.blk_counts);
+    p.blk_base = (int32_t*)(w + L.blk_base);
+    p.blk_mask = (unsigned long long*)(w + L.blk_mask);
+    p.tile_expert = (int32_t*)(w + L.tile_expert);
+    p.tile_xblk = (int32_t*)(w + L.tile_xblk);
+    p.tile_hblk = (int32_t*)(w + L.tile_hblk);
+    p.tile_nblk = (int32_t*)(w + L.tile_nblk);
+    p.exp_tile0 = (int32_t*)(w + L.exp_tile0);
+    p.exp_ntiles = (int32_t*)(w + L.exp_ntiles);
+    p.blk_expert = (int32_t*)(w + L.blk_expert);
+    p.mail = (int32_t*)(w + L.mail);
+    c->wtab_dev = (const uint8_t**)(w + L.wtab);
+    const int E = cfg->n_experts, S = cfg->n_shared;
+    c->layers.resize(cfg->n_layers);
+    for (auto& ls : c->layers) {
+        ls.resident.assign(E + S, nullptr);
+        ls.host.assign(E, nullptr);
+        ls.slot_of.assign(E, -1);
+    }
+    auto cleanup = [&](moe_status s, const char* what, hipError_t e) {
+        moe_status r = fail(nullptr, s, "%s failed: %s", what, hipGetErrorString(e));
+        moe_destroy(c);
+        return r;
+    };
+    hipError_t e;
+    e = hipMemsetAsync(w + L.wtab, 0, (size_t)cfg->n_layers * (E + S) * 8, c->compute);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
+    e = hipMemsetAsync(w + L.meta, 0, 64, c->compute);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
+    e = hipStreamSynchronize(c->compute);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipStreamSynchronize", e);
+    e = hipHostMalloc((void**)&c->mailbox, (size_t)(2 * E + 1) * 4, hipHostMallocDefault);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipHostMalloc", e);
+    e = hipEventCreateWithFlags(&c->route_ev, hipEventDisableTiming);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipEventCreate", e);
+    for (auto& ev : c->pev) {
+        e = hipEventCreate(&ev);
+        if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipEventCreate", e);
+    }
+    c->slots.resize(n_slots);
+    for (int i = 0; i < n_slots; ++i) {
+        Slot& s = c->slots[i];
+        s.ptr = c->window + (size_t)i * L.expert_bytes;
+        e = hipEventCreateWithFlags(&s.ready, hipEventDisableTiming);
+        if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipEventCreate", e);
+        e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming);
+        if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipEventCreate", e);
+    }
+    if (cfg->dtype == MOE_BF16) {
+        int r = ffn_configure();
+        if (r != 0) return cleanup(MOE_ERR_HIP, "hipFuncSetAttribute", (hipError_t)r);
+    }
+    *out = c;
+    return MOE_OK;
+}
+
+moe_status moe_destroy(moe_ctx* ctx) {
+    if (!ctx) return MOE_OK;
+    if (ctx->compute || true) (void)hipStreamSynchronize(ctx->compute);
+    if (ctx->copy != ctx->compute) (void)hipStreamSynchronize(ctx->copy);
+    for (Slot& s : ctx->slots) {
+        if (s.ready) (void)hipEventDestroy(s.ready);
+        if (s.done) (void)hipEventDestroy(s.done);
+    }
+    if (ctx->route_ev) (void)hipEventDestroy(ctx->route_ev);
+    for (auto& ev : ctx->pev)
+        if (ev) (void)hipEventDestroy(ev);
+    if (ctx->mailbox) (void)hipHostFree(ctx->mailbox);
+    delete ctx;
+    return MOE_OK;
+}
+
+moe_status moe_set_gate(moe_ctx* ctx, int32_t layer, const void* wg_dev) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (!wg_dev) return fail(ctx, MOE_ERR_INVALID_ARG, "gate matrix is null");
+    ctx->layers[layer].wg = wg_dev;
+    return MOE_OK;
+}
+
+moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const void* w1_dev,
+                          const void* w3_dev, const void* w2_dev, int32_t where, void* packed_dst) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    const int E = ctx->cfg.n_experts, S = ctx->cfg.n_shared;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (expert < 0 || expert >= E + S) return fail(ctx, MOE_ERR_INVALID_ARG, "expert %d out of range", expert);
+    if (!w1_dev || !w3_dev || !w2_dev || !packed_dst) return fail(ctx, MOE_ERR_INVALID_ARG, "null weight pointer");
+    if (where != MOE_RESIDENT && where != MOE_HOST_PINNED) return fail(ctx, MOE_ERR_INVALID_ARG, "bad residency");
+    if (((uintptr_t)packed_dst & 15u) != 0) return fail(ctx, MOE_ERR_INVALID_ARG, "packed_dst must be 16-byte aligned");
+    const int d = ctx->cfg.d_model, f = ctx->cfg.d_ff;
+    LayerState& ls = ctx->layers[layer];
+    void* pack_to = packed_dst;
+    if (where == MOE_HOST_PINNED) {
+        if (expert >= E) return fail(ctx, MOE_ERR_INVALID_ARG, "shared experts must be resident");
+        if (ctx->slots.empty()) return fail(ctx, MOE_ERR_STATE, "host-resident experts need a window (window_layers > 0)");
+        if (!is_pinned_host(packed_dst)) return fail(ctx, MOE_ERR_NOT_PINNED, "packed_dst is not pinned host memory");
+        for (const Slot& s : ctx->slots)
+            if (s.state != SLOT_FREE) return fail(ctx, MOE_ERR_STATE, "placement while experts are in the window");
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->copy));
+        pack_to = ctx->slots[0].ptr;  // staging: slot 0 is idle during the offline phase
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+    if (ctx->cfg.dtype == MOE_BF16)
+        launch_pack_expert_bf16(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, pack_to);
+    else
+        launch_pack_expert_f32(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, pack_to);
+    HIP_TRY(ctx, hipGetLastError());
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+    if (where == MOE_HOST_PINNED) {
+        HIP_TRY(ctx, hipMemcpy(packed_dst, pack_to, (size_t)ctx->L.expert_bytes, hipMemcpyDeviceToHost));
+        ctx->slots[0].done_pending = false;
+        ls.host[expert] = (const uint8_t*)packed_dst;
+        ls.resident[expert] = nullptr;
+        const uint8_t* nul = nullptr;
+        HIP_TRY(ctx, hipMemcpy((void*)(ctx->wtab_dev + (size_t)layer * (E + S) + expert), &nul, 8, hipMemcpyHostToDevice));
+    } else {
+        ls.resident[expert] = (const uint8_t*)packed_dst;
+        if (expert < E) ls.host[expert] = nullptr;
+        const uint8_t* ptr = (const uint8_t*)packed_dst;
+        HIP_TRY(ctx, hipMemcpy((void*)(ctx->wtab_dev + (size_t)layer * (E + S) + expert), &ptr, 8, hipMemcpyHostToDevice));
+    }
+    return MOE_OK;
+}
+
+moe_status moe_route(moe_ctx* ctx, int32_t layer, const void* x_dev,
+                     const int32_t* batch_offsets_host, int32_t n_batches, float* logits_dev,
+                     int32_t* topk_idx_dev, float* topk_w_dev, int32_t* counts_dev,
+                     int32_t* offsets_dev, int32_t* perm_dev, int32_t* inv_perm_dev,
+                     int32_t* exec_order_dev) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (!batch_offsets_host) return fail(ctx, MOE_ERR_INVALID_ARG, "batch_offsets is null");
+    if (n_batches < 1 || n_batches > ctx->cfg.max_batches) return fail(ctx, MOE_ERR_SHAPE, "n_batches %d outside [1, %d]", n_batches, ctx->cfg.max_batches);
+    if (batch_offsets_host[0] != 0) return fail(ctx, MOE_ERR_INVALID_ARG, "batch_offsets must start at 0");
+    BatchOffsets bo;
+    bo.n = n_batches;
+    for (int b = 0; b <= n_batches; ++b) {
+        if (b > 0 && batch_offsets_host[b] < batch_offsets_host[b - 1])
+            return fail(ctx, MOE_ERR_INVALID_ARG, "batch_offsets must be non-decreasing");
+        bo.v[b] = batch_offsets_host[b];
+    }
+    for (int b = n_batches + 1; b <= kMaxBatches; ++b) bo.v[b] = batch_offsets_host[n_batches];
+    const int N = batch_offsets_host[n_batches];
+    if (N > ctx->cfg.max_tokens) return fail(ctx, MOE_ERR_SHAPE, "%d tokens exceed max_tokens %d", N, ctx->cfg.max_tokens);
+    if (N > 0 && !x_dev) return fail(ctx, MOE_ERR_INVALID_ARG, "x is null");
+    LayerState& ls = ctx->layers[layer];
+    if (!ls.wg) return fail(ctx, MOE_ERR_STATE, "gate of layer %d not set", layer);
+    const int E = ctx->cfg.n_experts, k = ctx->cfg.top_k;
+    const Shape s = make_shape(ctx, N);
+    hipStream_t st = ctx->compute;
+    const bool prof = ctx->profiling;
+    if (prof) (void)hipEventRecord(ctx->pev[0], st);
+    launch_router(st, ctx->cfg.dtype, x_dev, ls.wg, s, logits_dev, ctx->plan.topk_idx, ctx->plan.topk_w);
+    if (prof) (void)hipEventRecord(ctx->pev[1], st);
+    launch_plan(st, s, bo, ctx->plan, ctx->L.max_tiles);
+    if (prof) (void)hipEventRecord(ctx->pev[2], st);
+    ctx->prof_route = prof;
+    HIP_TRY(ctx, hipGetLastError());
+    const size_t A = (size_t)N * k;
+    auto out = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
+        if (!dst || bytes == 0) return hipSuccess;
+        return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st);
+    };
+    HIP_TRY(ctx, out(topk_idx_dev, ctx->plan.topk_idx, A * 4));
+    HIP_TRY(ctx, out(topk_w_dev, ctx->plan.topk_w, A * 4));
+    HIP_TRY(ctx, out(counts_dev, ctx->plan.counts, (size_t)E * 4));
+    HIP_TRY(ctx, out(offsets_dev, ctx->plan.offsets, (size_t)(E + 1) * 4));
+    HIP_TRY(ctx, out(perm_dev, ctx->plan.perm, A * 4));
+    HIP_TRY(ctx, out(inv_perm_dev, ctx->plan.inv_perm, A * 4));
+    HIP_TRY(ctx, out(exec_order_dev, ctx->plan.exec_order, (size_t)E * 4));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->mailbox, ctx->plan.mail, (size_t)(2 * E + 1) * 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipEventRecord(ctx->route_ev, st));
+    ctx->routed_layer = layer;
+    ctx->routed_tokens = N;
+    ctx->routed_x = x_dev;
+    ctx->route_pending = true;
+    ctx->host_plan_valid = false;
+    ctx->stats.tokens += N;
+    return MOE_OK;
+}
+
+moe_status moe_route_wait(moe_ctx* ctx, int32_t* counts_host, int32_t* exec_order_host,
+                          int32_t* n_active) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    moe_status st = wait_route(ctx);
+    if (st != MOE_OK) return st;
+    const int E = ctx->cfg.n_experts;
+    if (counts_host) memcpy(counts_host, ctx->h_counts.data(), (size_t)E * 4);
+    if (exec_order_host) memcpy(exec_order_host, ctx->h_order.data(), (size_t)E * 4);
+    if (n_active) *n_active = ctx->h_nactive;
+    return MOE_OK;
+}
+
+moe_status moe_stream_experts(moe_ctx* ctx, int32_t layer, const int32_t* expert_ids_host,
+                              int32_t n_ids, int32_t flags) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (n_ids < 0 || (n_ids > 0 && !expert_ids_host)) return fail(ctx, MOE_ERR_INVALID_ARG, "bad expert id list");
+    if (flags != MOE_PREFETCH && flags != MOE_ON_DEMAND) return fail(ctx, MOE_ERR_INVALID_ARG, "flags must be MOE_PREFETCH or MOE_ON_DEMAND");
+    if (ctx->slots.empty()) return fail(ctx, MOE_ERR_STATE, "context has no window (window_layers == 0)");
+    const int E = ctx->cfg.n_experts;
+    for (int i = 0; i < n_ids; ++i)
+        if (expert_ids_host[i] < 0 || expert_ids_host[i] >= E)
+            return fail(ctx, MOE_ERR_INVALID_ARG, "expert id %d out of range", expert_ids_host[i]);
+    if (flags == MOE_ON_DEMAND) {
+        if (ctx->routed_layer != layer) return fail(ctx, MOE_ERR_STATE, "on-demand transfer for layer %d, but the last moe_route was for layer %d", layer, ctx->routed_layer);
+        moe_status st = wait_route(ctx);
+        if (st != MOE_OK) return st;
+        for (int i = 0; i < n_ids; ++i)
+            if (ctx->h_counts[expert_ids_host[i]] == 0)
+                return fail(ctx, MOE_ERR_INVALID_ARG, "expert %d was not activated: it is never transferred", expert_ids_host[i]);
+    }
+    for (int i = 0; i < n_ids; ++i) {
+        moe_status st = stream_one(ctx, layer, expert_ids_host[i], flags == MOE_PREFETCH);
+        if (st != MOE_OK) return st;
+    }
+    return MOE_OK;
+}
+
+moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, void* y_dev) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (ctx->routed_layer != layer) return fail(ctx, MOE_ERR_STATE, "moe_route(layer %d) must precede moe_layer_forward", layer);
+    if (x_dev != ctx->routed_x) return fail(ctx, MOE_ERR_STATE, "x differs from the tensor given to moe_route");
+    const int N = ctx->routed_tokens;
+    ctx->stats.n_forward += 1;
+    if (N == 0) return MOE_OK;
+    if (!y_dev) return fail(ctx, MOE_ERR_INVALID_ARG, "y is null");
+    const int E = ctx->cfg.n_experts, S = ctx->cfg.n_shared;
+    LayerState& ls = ctx->layers[layer];
+    bool all_resident = true;
+    for (int e = 0; e < E + S; ++e) {
+        if (!ls.resident[e]) {
+            all_resident = false;
+            if (e >= E || !ls.host[e]) return fail(ctx, MOE_ERR_STATE, "weights of layer %d expert %d not set", layer, e);
+        }
+    }
+    const Shape s = make_shape(ctx, N);
+    const PlanPtrs& p = ctx->plan;
+    hipStream_t st = ctx->compute;
+    const uint8_t* const* wtab = ctx->wtab_dev + (size_t)layer * (E + S);
+    uint8_t* w = ctx->ws;
+    const bool bf16 = ctx->cfg.dtype == MOE_BF16;
+    const int split = auto_split_k(ctx, N);
+    float* o = (float*)(w + ctx->L.o);
+
+    FfnArgs a{};
+    a.wtab = wtab;
+    a.tile_expert = p.tile_expert;
+    a.tile_xblk = p.tile_xblk;
+    a.tile_hblk = p.tile_hblk;
+    a.tile_nblk = p.tile_nblk;
+    a.d = s.d;
+    a.f = s.f;
+    a.o_split_stride = ctx->L.o_split_stride;
+    a.h_planes = ctx->h_planes;
+    a.h_plane_units = ctx->L.h_plane_units;
+
+    const bool prof = ctx->profiling && all_resident_layer(ctx, layer);
+    ctx->prof_fwd = false;
+    if (prof) (void)hipEventRecord(ctx->pev[3], st);
+    if (bf16) launch_gather_bf16(st, x_dev, s, p, w + ctx->L.xp);
+    if (prof) (void)hipEventRecord(ctx->pev[4], st);
+
+    if (all_resident) {
+        if (bf16) {
+            a.w_single = nullptr;
+            a.tile_first = nullptr;
+            a.tile_count = p.meta + 1;
+            const int64_t A = (int64_t)N * s.k;
+            a.max_tiles = (int)std::min<int64_t>(ctx->L.max_tiles,
+                                                 (A / kRowBlk + E) / kTileBlks + std::min<int64_t>(E, A) +
+                                                     (int64_t)S * ((N + 255) / 256) + 1);
+            a.act = w + ctx->L.xp;
+            a.out = w + ctx->L.h;
+            a.split_k = 1;
+            launch_ffn_up_bf16(st, a);
+            if (prof) (void)hipEventRecord(ctx->pev[5], st);
+            a.act = w + ctx->L.h;
+            a.out = o;
+            a.split_k = split;
+            launch_ffn_down_bf16(st, a);
+        } else {
+            if (prof) (void)hipEventRecord(ctx->pev[5], st);
+            launch_ffn_f32(st, (const float*)x_dev, s, p, wtab, nullptr, -1, (float*)(w + ctx->L.h), o);
+        }
+        if (prof) (void)hipEventRecord(ctx->pev[6], st);
+    } else {
+        moe_status rs = wait_route(ctx);
+        if (rs != MOE_OK) return rs;
+        // experts of this layer in the window that the gate did not select are dropped
+        for (Slot& sl : ctx->slots) {
+            if (sl.state == SLOT_LOADED && sl.layer == layer && ctx->h_counts[sl.expert] == 0) {
+                ctx->stats.n_prefetch_unused += 1;
+                release_slot(ctx, sl, false);
+            }
+        }
+        // on-demand transfers for activated experts that are neither resident nor in flight
+        for (int i = 0; i < ctx->h_nactive; ++i) {
+            const int e = ctx->h_order[i];
+            if (ls.resident[e]) continue;
+            if (ls.slot_of[e] >= 0) {
+                ctx->stats.n_prefetch_hits += 1;
+                continue;
+            }
+            moe_status ss = stream_one(ctx, layer, e, false);
+            if (ss != MOE_OK) return ss;
+        }
+        // device-side tile ranges are addressed through exp_tile0 / exp_ntiles
+        auto run_expert = [&](int e, const uint8_t* blob) {
+            if (bf16) {
+                a.w_single = blob;
+                a.tile_first = p.exp_tile0 + e;
+                a.tile_count = p.exp_ntiles + e;
+                a.max_tiles = ctx->h_tiles[e].count;
+                if (a.max_tiles == 0) return;
+                a.act = w + ctx->L.xp;
+                a.out = w + ctx->L.h;
+                a.split_k = 1;
+                launch_ffn_up_bf16(st, a);
+                a.act = w + ctx->L.h;
+                a.out = o;
+                a.split_k = split;
+                launch_ffn_down_bf16(st, a);
+            } else {
+                launch_ffn_f32(st, (const float*)x_dev, s, p, wtab, blob, e, (float*)(w + ctx->L.h), o);
+            }
+        };
+        for (int sh = 0; sh < S; ++sh) run_expert(E + sh, ls.resident[E + sh]);
+        // experts already loaded go first, then the rest in execution order (= copy order)
+        for (int pass = 0; pass < 2; ++pass) {
+            for (int i = 0; i < ctx->h_nactive; ++i) {
+                const int e = ctx->h_order[i];
+                const bool res = ls.resident[e] != nullptr;
+                const bool early = res || (ls.slot_of[e] >= 0 && ctx->slots[ls.slot_of[e]].prefetched);
+                if ((pass == 0) != early) continue;
+                if (res) {
+                    run_expert(e, ls.resident[e]);
+                } else {
+                    Slot& sl = ctx->slots[ls.slot_of[e]];
+                    HIP_TRY(ctx, hipStreamWaitEvent(st, sl.ready, 0));
+                    run_expert(e, sl.ptr);
+                    release_slot(ctx, sl, true);  // freed as soon as its last kernel is queued
+                }
+            }
+        }
+    }
+    launch_combine(st, bf16 ? 1 : 0, s, p, o, bf16 ? split : 1, ctx->L.o_split_stride, y_dev);
+    if (prof) {
+        (void)hipEventRecord(ctx->pev[7], st);
+        ctx->prof_fwd = true;
+    }
+    HIP_TRY(ctx, hipGetLastError());
+    return MOE_OK;
+}
+
+moe_status moe_get_stats(const moe_ctx* ctx, moe_stats* out) {
+    if (!ctx || !out) return fail(ctx, MOE_ERR_INVALID_ARG, "null argument");
+    *out = ctx->stats;
+    return MOE_OK;
+}
+
+moe_status moe_reset_stats(moe_ctx* ctx) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    ctx->stats = moe_stats{};
+    return MOE_OK;
+}
+
+moe_status moe_set_profiling(moe_ctx* ctx, int32_t enable) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    ctx->profiling = enable != 0;
+    ctx->prof_route = ctx->prof_fwd = false;
+    return MOE_OK;
+}
+
+moe_status moe_get_profile(moe_ctx* ctx, moe_profile* out) {
+    if (!ctx || !out) return fail(ctx, MOE_ERR_INVALID_ARG, "null argument");
+    memset(out, 0, sizeof *out);
+    if (!ctx->prof_route || !ctx->prof_fwd)
+        return fail(ctx, MOE_ERR_STATE, "no profiled moe_route + resident moe_layer_forward pair yet");
+    HIP_TRY(ctx, hipEventSynchronize(ctx->pev[7]));
+    float* dst[7] = {&out->router_ms, &out->plan_ms, nullptr, &out->gather_ms, &out->up_ms,
+                     &out->down_ms, &out->combine_ms};
+    for (int i = 0; i < 7; ++i) {
+        if (!dst[i]) continue;
+        HIP_TRY(ctx, hipEventElapsedTime(dst[i], ctx->pev[i], ctx->pev[i + 1]));
+    }
+    return MOE_OK;
+}
+
+moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t reserved) {
+    (void)reserved;
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (split_k < 0 || split_k > 64) return fail(ctx, MOE_ERR_INVALID_ARG, "split_k out of range");
+    if (h_planes < 0 || h_planes > 2) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1 or 2");
+    ctx->split_k_user = split_k;
+    if (h_planes > 0) ctx->h_planes = h_planes;
+    return MOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,128 @@
+"""The C-ABI library: loads, exports every symbol include/moe.h declares, and its host-only
+entry points (sizing, the planner's inequality group, argument validation) behave.
+No GPU needed, no compute call made."""
+import ctypes as C
+import math
+import os
+import re
+
+import pytest
+
+from paper_2502_06888_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = declared_symbols()
+    assert {"moe_plan", "moe_route", "moe_layer_forward", "moe_stream_experts"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in moe.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def test_struct_sizes_match_header():
+    assert C.sizeof(B.MoeConfig) == 11 * 4
+    assert C.sizeof(B.MoePlan) == 3 * 8 + 2 * 4 + 3 * 8
+    assert C.sizeof(B.MoeStats) == 7 * 8
+
+
+def test_plan_sizes_for_the_named_workloads():
+    cfg = B.make_config(4096, 14336, 8, 2, max_tokens=512)
+    p = B.moe_plan(cfg, 512, 8e12, 64e9, 2.5e15)
+    assert p.expert_bytes == 3 * 4096 * 14336 * 2 == 352321536
+    assert p.n_slots == 0 and p.window_bytes == 0
+    assert p.workspace_bytes > 0 and p.workspace_bytes % 256 == 0
+    assert math.isclose(p.t_io_expert_s, 352321536 / 64e9)
+    # 128 rows per expert: memory time (44 us) dominates MFMA time (18 us)
+    assert math.isclose(p.t_c_expert_s, 352321536 / 8e12)
+    cfg = B.make_config(6144, 16384, 8, 2, n_layers=8, window_layers=2, max_tokens=512)
+    p = B.moe_plan(cfg, 512)
+    assert p.expert_bytes == 603979776 and p.n_slots == 16
+    assert p.window_bytes == 16 * 603979776
+    cfg = B.make_config(256, 512, 8, 2, max_tokens=64, dtype=B.MOE_F32)
+    assert B.moe_plan(cfg, 64).expert_bytes == 1572864
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(d_model=4100), B.MOE_ERR_SHAPE), (dict(d_ff=100), B.MOE_ERR_SHAPE),
+    (dict(n_experts=0), B.MOE_ERR_SHAPE), (dict(n_experts=257), B.MOE_ERR_SHAPE),
+    (dict(top_k=9), B.MOE_ERR_SHAPE), (dict(top_k=3, n_experts=2), B.MOE_ERR_SHAPE),
+    (dict(n_shared=9), B.MOE_ERR_SHAPE), (dict(window_layers=2, n_layers=1), B.MOE_ERR_SHAPE),
+    (dict(max_batches=65), B.MOE_ERR_SHAPE), (dict(dtype=7), B.MOE_ERR_INVALID_ARG),
+    (dict(max_tokens=0), B.MOE_ERR_SHAPE),
+])
+def test_plan_rejects_bad_configs(kw, status):
+    base = dict(d_model=4096, d_ff=14336, n_experts=8, top_k=2)
+    base.update(kw)
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_plan(B.make_config(**base), 1)
+    assert ei.value.status == status and ei.value.message
+
+
+def test_plan_null_and_range_arguments():
+    lib = B.load_library()
+    cfg = B.make_config(256, 512, 8, 2, max_tokens=64)
+    out = B.MoePlan()
+    assert lib.moe_plan(None, 1, 1.0, 1.0, 1.0, C.byref(out)) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_plan(C.byref(cfg), 1, 1.0, 1.0, 1.0, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_plan(C.byref(cfg), 65, 1.0, 1.0, 1.0, C.byref(out)) == B.MOE_ERR_SHAPE
+    assert b"max_tokens" in lib.moe_last_error(None)
+
+
+def test_create_validates_before_touching_the_gpu():
+    lib = B.load_library()
+    cfg = B.make_config(256, 512, 8, 2, max_tokens=64)
+    h = C.c_void_p()
+    assert lib.moe_create(C.byref(cfg), None, None, None, 0, None, 0, C.byref(h)) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_create(C.byref(cfg), None, None, 256, 1 << 30, None, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_create(C.byref(cfg), None, None, 257, 1 << 30, None, 0, C.byref(h)) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_create(C.byref(cfg), None, None, 256, 16, None, 0, C.byref(h)) == B.MOE_ERR_OOM
+    cfgw = B.make_config(256, 512, 8, 2, n_layers=2, window_layers=1, max_tokens=64)
+    assert lib.moe_create(C.byref(cfgw), None, None, 256, 1 << 30, None, 0, C.byref(h)) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_create(C.byref(cfgw), None, None, 256, 1 << 30, 256, 16, C.byref(h)) == B.MOE_ERR_OOM
+    assert lib.moe_create(C.byref(cfgw), None, None, 256, 1 << 30, 256, 1 << 40, C.byref(h)) == B.MOE_ERR_INVALID_ARG
+    assert not h.value
+    for fn in (lib.moe_destroy,):
+        assert fn(None) == B.MOE_OK
+    assert lib.moe_set_gate(None, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_layer_forward(None, 0, None, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_stream_experts(None, 0, None, 0, 1) == B.MOE_ERR_INVALID_ARG
+
+
+# ---- planner inequality group (paper Section 7): closed forms -------------------------------
+
+def test_plan_batches_closed_forms():
+    # only the gate transfer matters: n * tA >= tG_io
+    assert B.moe_plan_batches(2.0, 0.0, 0.0, [], 0.0, 7.0, 0.0, 0) == 4      # ceil(3.5)
+    assert B.moe_plan_batches(2.0, 0.0, 0.0, [], 0.0, 8.0, 0.0, 0) == 4      # exact -> no round up
+    assert B.moe_plan_batches(2.0, 0.0, 0.0, [], 0.0, 0.0, 0.0, 0) == 1      # nothing to hide
+    # second inequality: n (tA+tG) >= tG_io + K tE_io  ->  n >= (1 + 2*21)/2.7
+    assert B.moe_plan_batches(2.6, 0.1, 0.0, [], 0.0, 1.0, 21.0, 2) == math.ceil(43 / 2.7)
+    # best case (no cold expert queued): hot-expert compute does not enter
+    assert B.moe_plan_batches(2.6, 0.1, 100.0, [], 50.0, 1.0, 21.0, 2) == math.ceil(43 / 2.7)
+    # third: n(tA+tG) + t_hot >= tG_io + (K+1) tE_io ; fourth adds the queue and the next attention
+    n3 = math.ceil((1 + 3 * 21 - 5.0) / 2.7)
+    n4 = math.ceil((1 + (2 + 3) * 21 + 4.0 - 5.0 - 3 * 2.0) / 2.7)
+    assert B.moe_plan_batches(2.6, 0.1, 5.0, [2.0, 2.0, 2.0], 4.0, 1.0, 21.0, 2) == max(n3, n4)
+    # worst case of the paper: nobody picked a hot expert (t_hot = 0) needs a larger n
+    assert B.moe_plan_batches(2.6, 0.1, 0.0, [2.0] * 3, 4.0, 1.0, 21.0, 2) >= max(n3, n4)
+    # monotone: more compute per batch never needs more batches
+    ns = [B.moe_plan_batches(t, 0.1, 1.0, [1.0] * 6, 5.0, 0.1, 21.0, 2) for t in (1.0, 2.0, 4.0, 8.0)]
+    assert ns == sorted(ns, reverse=True)
+
+
+def test_plan_batches_errors():
+    with pytest.raises(B.MoeError):
+        B.moe_plan_batches(0.0, 0.0, 0.0, [], 0.0, 1.0, 0.0, 0)              # nothing to overlap with
+    with pytest.raises(B.MoeError):
+        B.moe_plan_batches(-1.0, 0.0, 0.0, [], 0.0, 1.0, 0.0, 0)
+    lib = B.load_library()
+    assert lib.moe_plan_batches(1.0, 0.0, 0.0, None, 2, 0.0, 1.0, 0.0, 0, C.byref(C.c_int32())) == B.MOE_ERR_INVALID_ARG
