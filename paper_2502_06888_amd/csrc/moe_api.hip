@@ -733,7 +733,7 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
             const int e = ctx->h_order[i];
             if (ls.resident[e]) continue;
             if (ls.slot_of[e] >= 0) {
-                ctx->stats.n_prefetch_hits += 1;
+                if (ctx->slots[ls.slot_of[e]].prefetched) ctx->stats.n_prefetch_hits += 1;
                 continue;
             }
             moe_status ss = stream_one(ctx, layer, e, false);
@@ -760,16 +760,23 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
             }
         };
         for (int sh = 0; sh < S; ++sh) run_expert(E + sh, ls.resident[E + sh]);
-        // experts already loaded go first, then the rest in execution order (= copy order)
+        // experts whose weights were on the device before the gate ran (resident or prefetched)
+        // go first, then the rest in execution order, which is also their copy order
+        std::vector<char> early(ctx->h_nactive, 0);
+        for (int i = 0; i < ctx->h_nactive; ++i) {
+            const int e = ctx->h_order[i];
+            early[i] = ls.resident[e] != nullptr ||
+                       (ls.slot_of[e] >= 0 && ctx->slots[ls.slot_of[e]].prefetched);
+        }
         for (int pass = 0; pass < 2; ++pass) {
             for (int i = 0; i < ctx->h_nactive; ++i) {
+                if ((pass == 0) != (early[i] != 0)) continue;
                 const int e = ctx->h_order[i];
-                const bool res = ls.resident[e] != nullptr;
-                const bool early = res || (ls.slot_of[e] >= 0 && ctx->slots[ls.slot_of[e]].prefetched);
-                if ((pass == 0) != early) continue;
-                if (res) {
+                if (ls.resident[e]) {
                     run_expert(e, ls.resident[e]);
                 } else {
+                    if (ls.slot_of[e] < 0)
+                        return fail(ctx, MOE_ERR_STATE, "layer %d expert %d is not in the window", layer, e);
                     Slot& sl = ctx->slots[ls.slot_of[e]];
                     HIP_TRY(ctx, hipStreamWaitEvent(st, sl.ready, 0));
                     run_expert(e, sl.ptr);

@@ -54,9 +54,9 @@ def streamed_pass(ctx, w, layers, prefetch_k, delay_compute=False, explicit_on_d
                 torch.cuda._sleep(20_000_000)               # compute lags, copies run ahead
             ctx.layer_forward(l, x, y)
         prev_counts = counts
-        outs.append((y, counts, n_active))
+        outs.append((y, counts, n_active, x))   # x must stay allocated until its forward has run
     ctx.compute_stream.synchronize()
-    return [(y.to(torch.float32).cpu().numpy(), c, n) for y, c, n in outs]
+    return [(y.to(torch.float32).cpu().numpy(), c, n) for y, c, n, _ in outs]
 
 
 @pytest.mark.parametrize("prefetch_k,delay,explicit", [(0, False, False), (2, False, True),
