@@ -229,8 +229,8 @@ class MoeContext:
     def reset_stats(self):
         _check(self.lib.moe_reset_stats(self.h), self.h)
 
-    def set_tuning(self, split_k: int = 0, h_planes: int = 0):
-        _check(self.lib.moe_set_tuning(self.h, split_k, h_planes, 0), self.h)
+    def set_tuning(self, split_k: int = 0, h_planes: int = 0, variant: int = 0):
+        _check(self.lib.moe_set_tuning(self.h, split_k, h_planes, variant), self.h)
 
     def set_profiling(self, enable: bool):
         _check(self.lib.moe_set_profiling(self.h, int(enable)), self.h)

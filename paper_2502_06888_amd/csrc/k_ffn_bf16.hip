@@ -25,9 +25,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte unit
 typedef const __attribute__((address_space(1))) u32x4* gptr;  // global (HBM) address space
 
 constexpr int kXcd = 8;
-constexpr int kBlkStageUnits = 128;  // 16-byte units of one row block per LDS stage (SK * PL = 2)
-constexpr int kLdsUnits = 2 * kTileBlks * kBlkStageUnits;
-constexpr int kLdsBytes = kLdsUnits * 16;  // 64 KiB, double buffered
+constexpr int kFragsPerBlk = 4;  // fragments of one row block in one LDS stage
+constexpr int kBlkStageUnits = kFragsPerBlk * 64;  // 16-byte units of one row block per stage
+constexpr int kBufUnits = kTileBlks * kBlkStageUnits;
+constexpr int kLdsBytes = 2 * kBufUnits * 16;  // 128 KiB, double buffered
 
 __device__ __forceinline__ gptr as_global(const void* p) { return (gptr)(uintptr_t)p; }
 
@@ -39,64 +40,100 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float v) {
     return a >> 16;
 }
 
-// A stage of the reduction loop covers SK steps of 32 for PL planes of the activations
-// (SK * PL == 2): SK = 2, PL = 1 normally; SK = 1, PL = 2 when H is carried as a bf16 pair
-// (high part + rounding remainder) through the down projection.
+// One LDS stage holds, per row block, SX reduction steps of 32 for PL planes of the activations
+// (SX * PL == 4): SX = 4, PL = 1 normally; SX = 2, PL = 2 when H is carried as a bf16 pair
+// (value + rounding remainder) through the down projection.  The weight ring in registers is
+// SX steps deep, one slot per step of the stage.  The activation loads of the next stage are
+// issued before any weight load of this stage, so by the time they are waited for (end of the
+// stage) every older load in the in-order memory counter has long been consumed: waiting for
+// the activations never forces a weight prefetch to complete early.
 struct TileCtx {
     gptr wbase;     // this wavefront's weight stream (+lane), 128 units per reduction step
     gptr actbase;   // packed activations at the tile's first row block (plane 0)
     size_t plane;   // units between activation planes
     u32x4* lds;
-    int nks;        // reduction steps of 32
-    int s0, s1;     // stage range of this workgroup
+    int nks;        // reduction steps of 32 in the whole reduction
+    int k0, k1;     // reduction steps of this workgroup: [k0, k1), k0 a multiple of SX
     int nblk;       // live row blocks of the tile
     bool active;    // wavefront owns a real unit
 };
 
-template <int SK>
-__device__ __forceinline__ void load_w(const TileCtx& c, u32x4 (&dst)[SK][2], int stage) {
-#pragma unroll
-    for (int ks = 0; ks < SK; ++ks) {
-        gptr q = c.wbase + (size_t)(stage * SK + ks) * 128;
-        dst[ks][0] = q[0];
-        dst[ks][1] = q[64];
-    }
+__device__ __forceinline__ void load_w(const TileCtx& c, u32x4 (&dst)[2], int kstep) {
+    gptr q = c.wbase + (size_t)kstep * 128;
+    dst[0] = q[0];
+    dst[1] = q[64];
 }
 
-// Unit u of a stage is (row block b, plane pl, step ks, lane): u = ((b*PL + pl)*SK + ks)*64 + lane.
-template <int PASSES, int T, int SK, int PL>
-__device__ __forceinline__ void load_x(const TileCtx& c, u32x4 (&xr)[PASSES], int stage) {
+// Unit u of a stage is (row block b, plane pl, step j, lane): u = ((b*PL + pl)*SX + j)*64 + lane.
+// Lanes past the live part of the tile re-read unit 0, steps past the end of the reduction
+// re-read the last step: both in bounds, and what is then stored lands in LDS slots that no
+// live MFMA reads.
+template <int PASSES, int T, int SX, int PL>
+__device__ __forceinline__ void load_x(const TileCtx& c, u32x4 (&xr)[PASSES], int kbase) {
     const int live_units = c.nblk * kBlkStageUnits;
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         int u = (int)threadIdx.x + p * T;
-        u = u < live_units ? u : 0;  // out-of-tile lanes re-read unit 0 (in bounds, not stored)
+        u = u < live_units ? u : 0;
         const int b = u / kBlkStageUnits, r = u % kBlkStageUnits;
-        const int pl = PL == 1 ? 0 : r / (SK * 64);
-        const int w = r % (SK * 64);  // ks*64 + lane
-        xr[p] = c.actbase[(size_t)pl * c.plane + ((size_t)b * c.nks + (size_t)stage * SK) * 64 + w];
+        const int pl = r / (SX * 64);
+        const int j = (r / 64) % SX;
+        const int ks = min(kbase + j, c.nks - 1);
+        xr[p] = c.actbase[(size_t)pl * c.plane + ((size_t)b * c.nks + ks) * 64 + (r & 63)];
     }
 }
 
+// PASSES * T <= kBufUnits (one LDS buffer), so the stores need no guard.
 template <int PASSES, int T>
 __device__ __forceinline__ void store_x(const TileCtx& c, const u32x4 (&xr)[PASSES], int buf) {
-    const int live_units = c.nblk * kBlkStageUnits;
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-        const int u = (int)threadIdx.x + p * T;
-        if (u < live_units) c.lds[buf * (kLdsUnits / 2) + u] = xr[p];
-    }
+    for (int p = 0; p < PASSES; ++p) c.lds[buf * kBufUnits + (int)threadIdx.x + p * T] = xr[p];
 }
 
-template <int MODE, int NB, int WAVES, int PD, int SK, int PL>
+// MFMAs of one reduction step: NB*PL fragments read from LDS through a rolling window of D
+// registers, so that D reads are in flight ahead of the matrix core; the interleaving is
+// pinned with scheduling groups (D reads, then one read per two MFMAs).
+template <int MODE, int NB, int SX, int PL, int D>
+__device__ __forceinline__ void step_mfma(const u32x4* L, int j, const u32x4 (&w)[2],
+                                          f32x4 (&acc0)[NB], f32x4 (&acc1)[NB]) {
+    constexpr int NF = NB * PL;
+    constexpr int DD = D < NF ? D : NF;
+    u32x4 win[DD];
+    const bf16x8 wa = as_bf16x8(w[0]), wb = as_bf16x8(w[1]);
+#pragma unroll
+    for (int i = 0; i < DD; ++i) win[i] = L[(i * SX + j) * 64];  // fragment i = (b, pl) = i/PL, i%PL
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+        const int b = i / PL;
+        const bf16x8 xa = as_bf16x8(win[i % DD]);
+        if (MODE == 0) {  // rows = features, cols = tokens
+            acc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, xa, acc0[b], 0, 0, 0);
+            acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, xa, acc1[b], 0, 0, 0);
+        } else {  // rows = tokens, cols = output columns
+            acc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, wa, acc0[b], 0, 0, 0);
+            acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, wb, acc1[b], 0, 0, 0);
+        }
+        if (i + DD < NF) win[i % DD] = L[((i + DD) * SX + j) * 64];
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
+#pragma unroll
+    for (int i = 0; i < NF - DD; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * DD, 0);
+}
+
+template <int MODE, int NB, int WAVES, int SX, int PL>
 __device__ __forceinline__ void ffn_tile(const TileCtx& c, f32x4 (&acc0)[NB], f32x4 (&acc1)[NB]) {
-    static_assert(SK * PL == 2 && PD % 2 == 0, "stage geometry");
+    static_assert(SX * PL == kFragsPerBlk, "stage geometry");
     constexpr int T = WAVES * 64;
     constexpr int UNITS = NB * kBlkStageUnits;
     constexpr int PASSES = (UNITS + T - 1) / T;
+    constexpr int D = 4;
     const int lane = threadIdx.x & 63;
 
-    u32x4 wr[PD][SK][2];
+    u32x4 wr[SX][2];
     u32x4 xr[PASSES];
 
 #pragma unroll
@@ -105,51 +142,43 @@ __device__ __forceinline__ void ffn_tile(const TileCtx& c, f32x4 (&acc0)[NB], f3
         acc1[b] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // prologue: fill the weight ring, stage the first activations
-    if (c.active) {
+    // prologue: stage the first activations, fill the weight ring
+    load_x<PASSES, T, SX, PL>(c, xr, c.k0);
 #pragma unroll
-        for (int u = 0; u < PD; ++u)
-            if (c.s0 + u < c.s1) load_w<SK>(c, wr[u], c.s0 + u);
-    }
-    load_x<PASSES, T, SK, PL>(c, xr, c.s0);
+    for (int j = 0; j < SX; ++j)
+        if (c.k0 + j < c.k1) load_w(c, wr[j], c.k0 + j);
     store_x<PASSES, T>(c, xr, 0);
     __syncthreads();
 
-    for (int s = c.s0; s < c.s1; s += PD) {
+    int k = c.k0, buf = 0;
+    // steady state: this stage and the next are complete, so the body is branch-free
+    for (; k + 2 * SX <= c.k1; k += SX, buf ^= 1) {
+        load_x<PASSES, T, SX, PL>(c, xr, k + SX);
+        __builtin_amdgcn_sched_barrier(0);
+        const u32x4* L = c.lds + buf * kBufUnits + lane;
 #pragma unroll
-        for (int u = 0; u < PD; ++u) {
-            const int cur = s + u;
-            if (cur < c.s1) {  // uniform over the workgroup
-                const int buf = u & 1;  // PD is even and s - s0 is a multiple of PD
-                const bool more = cur + 1 < c.s1;
-                if (more) load_x<PASSES, T, SK, PL>(c, xr, cur + 1);
-                if (c.active) {
-                    const u32x4* L = c.lds + buf * (kLdsUnits / 2) + lane;
+        for (int j = 0; j < SX; ++j) {
+            step_mfma<MODE, NB, SX, PL, D>(L, j, wr[j], acc0, acc1);
+            load_w(c, wr[j], k + SX + j);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        store_x<PASSES, T>(c, xr, buf ^ 1);
+        __syncthreads();
+    }
+    // drain: the last one or two stages, guarded step by step
+    for (; k < c.k1; k += SX, buf ^= 1) {
+        const bool more = k + SX < c.k1;
+        if (more) load_x<PASSES, T, SX, PL>(c, xr, k + SX);
+        const u32x4* L = c.lds + buf * kBufUnits + lane;
 #pragma unroll
-                    for (int ks = 0; ks < SK; ++ks) {
-                        const bf16x8 wa = as_bf16x8(wr[u][ks][0]);
-                        const bf16x8 wb = as_bf16x8(wr[u][ks][1]);
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) {
-#pragma unroll
-                            for (int pl = 0; pl < PL; ++pl) {
-                                const bf16x8 xa = as_bf16x8(L[((b * PL + pl) * SK + ks) * 64]);
-                                if (MODE == 0) {  // rows = features, cols = tokens
-                                    acc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, xa, acc0[b], 0, 0, 0);
-                                    acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, xa, acc1[b], 0, 0, 0);
-                                } else {  // rows = tokens, cols = output columns
-                                    acc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, wa, acc0[b], 0, 0, 0);
-                                    acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, wb, acc1[b], 0, 0, 0);
-                                }
-                            }
-                        }
-                    }
-                    if (cur + PD < c.s1) load_w<SK>(c, wr[u], cur + PD);
-                }
-                if (more) store_x<PASSES, T>(c, xr, buf ^ 1);
-                __syncthreads();
+        for (int j = 0; j < SX; ++j) {
+            if (k + j < c.k1) {  // uniform over the workgroup
+                step_mfma<MODE, NB, SX, PL, D>(L, j, wr[j], acc0, acc1);
+                if (k + SX + j < c.k1) load_w(c, wr[j], k + SX + j);
             }
         }
+        if (more) store_x<PASSES, T>(c, xr, buf ^ 1);
+        __syncthreads();
     }
 }
 
@@ -180,10 +209,10 @@ __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) 
 // Up projections + SwiGLU.  The accumulator of lane (token j = lane & 15, group g = lane >> 4)
 // holds features 16*unit + 4g + r, r = 0..3: exactly half of the lane's 16-byte unit in the
 // fragment order of the down projection, so H is written with one 8-byte store per row block.
-template <int NB, int WAVES, int PD>
+template <int NB, int WAVES>
 __device__ __forceinline__ void up_tile(const FfnArgs& a, const TileCtx& c, int unit, int hblk0) {
     f32x4 g[NB], u[NB];
-    ffn_tile<0, NB, WAVES, PD, 2, 1>(c, g, u);
+    ffn_tile<0, NB, WAVES, 4, 1>(c, g, u);
     if (!c.active) return;
     const int lane = threadIdx.x & 63;
     uint2* hp = reinterpret_cast<uint2*>(a.out);
@@ -208,11 +237,11 @@ __device__ __forceinline__ void up_tile(const FfnArgs& a, const TileCtx& c, int 
     }
 }
 
-template <int NB, int WAVES, int PD, int PL>
+template <int NB, int WAVES, int PL>
 __device__ __forceinline__ void down_tile(const FfnArgs& a, const TileCtx& c, int unit, int hblk0,
                                           int sp) {
     f32x4 p0[NB], p1[NB];
-    ffn_tile<1, NB, WAVES, PD, 2 / PL, PL>(c, p0, p1);
+    ffn_tile<1, NB, WAVES, 4 / PL, PL>(c, p0, p1);
     if (!c.active) return;
     const int lane = threadIdx.x & 63;
     float* o = reinterpret_cast<float*>(a.out) + (size_t)sp * a.o_split_stride;
@@ -231,8 +260,7 @@ __device__ __forceinline__ void down_tile(const FfnArgs& a, const TileCtx& c, in
 }
 
 #define NB_SWITCH(CALL)                       \
-    if (nblk <= 1) { CALL(1); }               \
-    else if (nblk <= 2) { CALL(2); }          \
+    if (nblk <= 2) { CALL(2); }               \
     else if (nblk <= 4) { CALL(4); }          \
     else if (nblk <= 6) { CALL(6); }          \
     else if (nblk <= 8) { CALL(8); }          \
@@ -240,7 +268,7 @@ __device__ __forceinline__ void down_tile(const FfnArgs& a, const TileCtx& c, in
     else if (nblk <= 12) { CALL(12); }        \
     else { CALL(16); }
 
-template <int WAVES, int PD>
+template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_groups) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, 1);
@@ -254,19 +282,20 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
     TileCtx c;
     c.nks = a.d / 32;
     c.active = unit < a.f / 16;
-    c.wbase = as_global(blob) + (size_t)unit * c.nks * 128 + lane;
+    const int wunit = c.active ? unit : a.f / 16 - 1;  // idle wavefronts shadow the last unit
+    c.wbase = as_global(blob) + (size_t)wunit * c.nks * 128 + lane;
     c.actbase = as_global(a.act) + (size_t)a.tile_xblk[w.tile] * c.nks * 64;
     c.plane = 0;
     c.lds = lds;
-    c.s0 = 0;
-    c.s1 = c.nks / 2;
+    c.k0 = 0;
+    c.k1 = c.nks;
     c.nblk = nblk;
-#define CALL(NB) up_tile<NB, WAVES, PD>(a, c, unit, hblk0)
+#define CALL(NB) up_tile<NB, WAVES>(a, c, unit, hblk0)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
-template <int WAVES, int PD, int PL>
+template <int WAVES, int PL>
 __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, a.split_k);
@@ -280,33 +309,35 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     TileCtx c;
     c.nks = a.f / 32;
     c.active = unit < a.d / 32;
-    c.wbase = as_global(blob + (size_t)a.d * a.f * 4) + (size_t)unit * c.nks * 128 + lane;
+    const int wunit = c.active ? unit : a.d / 32 - 1;  // idle wavefronts shadow the last unit
+    c.wbase = as_global(blob + (size_t)a.d * a.f * 4) + (size_t)wunit * c.nks * 128 + lane;
     c.actbase = as_global(a.act) + (size_t)hblk0 * c.nks * 64;
     c.plane = (size_t)a.h_plane_units;
     c.lds = lds;
-    const int nstage = c.nks / (2 / PL);
-    c.s0 = (int)((long long)w.sp * nstage / a.split_k);
-    c.s1 = (int)((long long)(w.sp + 1) * nstage / a.split_k);
+    constexpr int SX = 4 / PL;
+    const int nstage = (c.nks + SX - 1) / SX;
+    c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
+    c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
     c.nblk = nblk;
-#define CALL(NB) down_tile<NB, WAVES, PD, PL>(a, c, unit, hblk0, w.sp)
+#define CALL(NB) down_tile<NB, WAVES, PL>(a, c, unit, hblk0, w.sp)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
-template <int WAVES, int PD>
+template <int WAVES>
 void launch_up(hipStream_t st, const FfnArgs& a) {
     const int n_groups = (a.f / 16 + WAVES - 1) / WAVES;
     const int grid = (a.max_tiles * n_groups + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((ffn_up_kernel<WAVES, PD>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st, a,
+    hipLaunchKernelGGL((ffn_up_kernel<WAVES>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st, a,
                        n_groups);
 }
 
-template <int WAVES, int PD, int PL>
+template <int WAVES, int PL>
 void launch_down(hipStream_t st, const FfnArgs& a) {
     const int n_groups = (a.d / 32 + WAVES - 1) / WAVES;
     const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((ffn_down_kernel<WAVES, PD, PL>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
-                       st, a, n_groups);
+    hipLaunchKernelGGL((ffn_down_kernel<WAVES, PL>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st,
+                       a, n_groups);
 }
 
 template <typename K>
@@ -318,19 +349,19 @@ hipError_t allow_lds(K kernel) {
 }  // namespace
 
 int ffn_configure() {
-    hipError_t e = allow_lds(&ffn_up_kernel<8, 2>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 2, 1>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 4, 2>);
+    hipError_t e = allow_lds(&ffn_up_kernel<8>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 2>);
     return (int)e;
 }
 
-void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) { launch_up<8, 2>(st, a); }
+void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) { launch_up<8>(st, a); }
 
 void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
     if (a.h_planes == 2)
-        launch_down<8, 4, 2>(st, a);
+        launch_down<8, 2>(st, a);
     else
-        launch_down<8, 2, 1>(st, a);
+        launch_down<8, 1>(st, a);
 }
 
 }  // namespace kmoe

@@ -165,6 +165,7 @@ struct moe_ctx {
     int h_nactive = 0;
     std::vector<HostTile> h_tiles;  // per expert id (E+S)
     int split_k_user = 0;
+    int variant = 0;   // kernel shape selector of the bf16 FFN (0 = default)
     int h_planes = 2;  // bf16 path: carry H as value + rounding remainder (2) or as plain bf16 (1)
     moe_stats stats{};
     bool profiling = false;
@@ -686,6 +687,7 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
     a.d = s.d;
     a.f = s.f;
     a.o_split_stride = ctx->L.o_split_stride;
+    a.variant = ctx->variant;
     a.h_planes = ctx->h_planes;
     a.h_plane_units = ctx->L.h_plane_units;
 
@@ -828,13 +830,14 @@ moe_status moe_get_profile(moe_ctx* ctx, moe_profile* out) {
     return MOE_OK;
 }
 
-moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t reserved) {
-    (void)reserved;
+moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant) {
+    if (variant < -1 || variant > 8) return fail(ctx, MOE_ERR_INVALID_ARG, "variant out of range");
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
     if (split_k < 0 || split_k > 64) return fail(ctx, MOE_ERR_INVALID_ARG, "split_k out of range");
     if (h_planes < 0 || h_planes > 2) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1 or 2");
     ctx->split_k_user = split_k;
     if (h_planes > 0) ctx->h_planes = h_planes;
+    if (variant != 0) ctx->variant = variant < 0 ? 0 : variant;
     return MOE_OK;
 }
 
