@@ -92,7 +92,7 @@ void launch_ffn_f32(hipStream_t st, const float* x, const Shape& s, const PlanPt
                     const uint8_t* const* wtab, const uint8_t* w_single, int32_t only_expert,
                     float* h, float* o) {
     if (s.N <= 0) return;
-    const int rows = s.max_rows16 * kRowBlk + s.S * ((s.N + kRowBlk - 1) / kRowBlk * kRowBlk);
+    const int rows = s.max_rowblks * kRowBlk + s.S * ((s.N + kRowBlk - 1) / kRowBlk * kRowBlk);
     // rows beyond the routed padded space of this call shift the shared rows down; bound by the
     // capacity and let row_owner() reject what is not there.
     hipLaunchKernelGGL(ffn_up_f32_kernel, dim3(rows, (s.f + kSlab - 1) / kSlab), dim3(kWaves * 64),

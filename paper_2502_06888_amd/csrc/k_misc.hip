@@ -2,12 +2,14 @@
 // MFMA fragment order, and the weighted combine (paper Section 2.1: the layer output of a
 // token is the weighted sum of its selected experts' outputs).
 //
-// Fragment order (bf16).  A 16x32 operand fragment of the 16x16x32 MFMA is stored as 64
-// consecutive 16-byte units, one per lane: lane l holds row (l & 15) and the eight reduction
-// positions of group g = l >> 4.  For the up projections (reduction over d) position i of
-// group g is element 32*ks + 8*g + i.  For the down projection (reduction over f) it is
-// 32*ks + 4*g + i for i < 4 and 32*ks + 16 + 4*g + (i-4) otherwise, which is exactly how the
-// up kernel's accumulator registers fall, so H never needs a shuffle between the two GEMMs.
+// Fragment order (bf16).  A 32x16 operand fragment of the 32x32x16 MFMA is stored as 64
+// consecutive 16-byte units, one per lane: lane l holds row (l & 31) and the eight reduction
+// positions of half hi = l >> 5.  For the up projections (reduction over d) position i is
+// element 16*ks + 8*hi + i, and the 32 rows of a weight fragment are 16 rows of W1 followed by
+// the same 16 rows of W3, so that one MFMA yields gate and up values of the same features in
+// the same lane.  For the down projection (reduction over f) position i is feature
+// 16*ks + 8*(i/4) + 4*hi + i%4, which is exactly how those values fall in the up kernel's
+// accumulator registers, so H never needs a shuffle between the two GEMMs.
 #include "kernels.h"
 
 namespace kmoe {
@@ -16,23 +18,22 @@ namespace {
 constexpr int kThreads = 256;
 
 // ---- offline packing of expert weights ----------------------------------------------------
-// W13p: [rb = f/16][ks = d/32][mat 2][lane 64] x 16 B   (mat 0 = W1, 1 = W3)
-// W2p : [nb = d/32][ks = f/32][sub 2][lane 64] x 16 B   (sub = which 16 of the 32 columns)
+// W13p: [unit = f/16][ks = d/16][lane 64] x 16 B   rows 0..15 = W1, rows 16..31 = W3 of the unit
+// W2p : [unit = d/32][ks = f/16][lane 64] x 16 B   rows = 32 output columns
 __global__ __launch_bounds__(kThreads) void pack_up_kernel(const uint16_t* __restrict__ w1,
                                                            const uint16_t* __restrict__ w3, int d,
                                                            int f, uint4* __restrict__ out) {
     const size_t units = (size_t)f * d * 2 / 8;
-    const int nks = d / 32;
+    const int nks = d / 16;
     for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
          u += (size_t)gridDim.x * kThreads) {
         const int lane = (int)(u & 63);
-        const int mat = (int)((u >> 6) & 1);
-        const size_t q = u >> 7;
+        const size_t q = u >> 6;
         const int ks = (int)(q % nks);
-        const int rb = (int)(q / nks);
-        const int row = rb * 16 + (lane & 15);
-        const int col = ks * 32 + (lane >> 4) * 8;
-        const uint16_t* src = (mat == 0 ? w1 : w3) + (size_t)row * d + col;
+        const int unit = (int)(q / nks);
+        const int r = lane & 31, hi = lane >> 5;
+        const uint16_t* src = (r < 16 ? w1 + (size_t)(unit * 16 + r) * d
+                                      : w3 + (size_t)(unit * 16 + r - 16) * d) + ks * 16 + hi * 8;
         out[u] = *reinterpret_cast<const uint4*>(src);
     }
 }
@@ -40,20 +41,19 @@ __global__ __launch_bounds__(kThreads) void pack_up_kernel(const uint16_t* __res
 __global__ __launch_bounds__(kThreads) void pack_down_kernel(const uint16_t* __restrict__ w2, int d,
                                                              int f, uint4* __restrict__ out) {
     const size_t units = (size_t)f * d / 8;
-    const int nks = f / 32;
+    const int nks = f / 16;
     for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
          u += (size_t)gridDim.x * kThreads) {
         const int lane = (int)(u & 63);
-        const int sub = (int)((u >> 6) & 1);
-        const size_t q = u >> 7;
+        const size_t q = u >> 6;
         const int ks = (int)(q % nks);
-        const int nb = (int)(q / nks);
-        const int row = nb * 32 + sub * 16 + (lane & 15);  // output feature (row of W2)
-        const int g = lane >> 4;
-        const uint16_t* src = w2 + (size_t)row * f + ks * 32 + 4 * g;
-        const uint2 lo = *reinterpret_cast<const uint2*>(src);       // f = 32ks + 4g + 0..3
-        const uint2 hi = *reinterpret_cast<const uint2*>(src + 16);  // f = 32ks + 16 + 4g + 0..3
-        out[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        const int unit = (int)(q / nks);
+        const int col = unit * 32 + (lane & 31);  // output feature (row of W2)
+        const int hi = lane >> 5;
+        const uint16_t* src = w2 + (size_t)col * f + ks * 16 + 4 * hi;
+        const uint2 lo = *reinterpret_cast<const uint2*>(src);      // f = 16ks + 4hi + 0..3
+        const uint2 up = *reinterpret_cast<const uint2*>(src + 8);  // f = 16ks + 8 + 4hi + 0..3
+        out[u] = make_uint4(lo.x, lo.y, up.x, up.y);
     }
 }
 
@@ -65,11 +65,11 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict_
 }
 
 // ---- per-call gather of token rows into fragment order -------------------------------------
-// Xp: [blk16][ks = d/32][lane 64] x 16 B.  Routed blocks follow the padded per-expert row
+// Xp: [row block][ks = d/16][lane 64] x 16 B.  Routed blocks follow the padded per-expert row
 // space; the rows of shared experts (all tokens, natural order) follow them.
 __global__ __launch_bounds__(kThreads) void gather_kernel(const uint16_t* __restrict__ x, Shape s,
                                                           PlanPtrs p, uint4* __restrict__ xp) {
-    const int nks = s.d / 32;
+    const int nks = s.d / 16;
     const int routed_blks = p.meta[2];
     const int shared_blks = s.S > 0 ? (s.N + kRowBlk - 1) / kRowBlk : 0;
     const size_t units = (size_t)(routed_blks + shared_blks) * nks * 64;
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(const uint16_t* __rest
         const size_t q = u >> 6;
         const int ks = (int)(q % nks);
         const int blk = (int)(q / nks);
-        const int j = lane & 15, g = lane >> 4;
+        const int j = lane & 31, hi = lane >> 5;
         int token = -1;
         if (blk < routed_blks) {
             const int e = p.blk_expert[blk];
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(const uint16_t* __rest
         }
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (token >= 0)
-            v = *reinterpret_cast<const uint4*>(x + (size_t)token * s.d + ks * 32 + g * 8);
+            v = *reinterpret_cast<const uint4*>(x + (size_t)token * s.d + ks * 16 + hi * 8);
         xp[u] = v;
     }
 }
@@ -184,7 +184,8 @@ void launch_pack_expert_f32(hipStream_t st, const void* w1, const void* w3, cons
 void launch_gather_bf16(hipStream_t st, const void* x, const Shape& s, const PlanPtrs& p,
                         void* xp) {
     if (s.N <= 0) return;
-    const size_t max_units = ((size_t)s.max_rows16 + (s.S > 0 ? (s.N + 15) / 16 : 0)) * (s.d / 32) * 64;
+    const size_t max_units =
+        ((size_t)s.max_rowblks + (s.S > 0 ? (s.N + kRowBlk - 1) / kRowBlk : 0)) * (s.d / 16) * 64;
     hipLaunchKernelGGL(gather_kernel, dim3(grid_for(max_units, 2048)), dim3(kThreads), 0, st,
                        (const uint16_t*)x, s, p, (uint4*)xp);
 }

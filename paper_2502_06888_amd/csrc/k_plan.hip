@@ -51,31 +51,14 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t* __r
     }
 }
 
-// P2: one block.  Totals, scans, execution order, tile tables, host mail.
-__global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunks, PlanPtrs p,
-                                                             int max_tiles) {
-    __shared__ int32_t cnt[kMaxExperts];
-    __shared__ int32_t nbt[kMaxExperts];
-    __shared__ int32_t off[kMaxExperts + 1];
-    __shared__ int32_t pof[kMaxExperts + 1];
-    __shared__ int32_t ord[kMaxExperts];
-    __shared__ int32_t nact;
+// Totals -> scans, execution order, tile tables, host mail.  cnt[] and nbt[] hold the tokens
+// and the batches of every expert on entry; off[], pof[], ord[] and nact are LDS scratch.
+__device__ __forceinline__ void scan_body(const Shape& s, const PlanPtrs& p, int max_tiles,
+                                          int32_t* cnt, int32_t* nbt, int32_t* off, int32_t* pof,
+                                          int32_t* ord, int32_t* nact_p) {
     const int E = s.E, tid = threadIdx.x;
-    if (tid == 0) nact = 0;
-    for (int e = tid; e < E; e += kThreads) {
-        int run = 0;
-        unsigned long long m = 0ull;
-        for (int c = 0; c < nchunks; ++c) {
-            p.blk_base[(size_t)c * E + e] = run;
-            run += p.blk_counts[(size_t)c * E + e];
-            m |= p.blk_mask[(size_t)c * E + e];
-        }
-        cnt[e] = run;
-        nbt[e] = __popcll(m);
-        ord[e] = -1;
-    }
-    __syncthreads();
     if (tid == 0) {
+        *nact_p = 0;
         int o = 0, po = 0;
         for (int e = 0; e < E; ++e) {
             off[e] = o;
@@ -86,6 +69,7 @@ __global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunk
         off[E] = o;
         pof[E] = po;
     }
+    for (int e = tid; e < E; e += kThreads) ord[e] = -1;
     __syncthreads();
     // execution order: rank of e among the activated experts by (nbatch desc, count desc, e asc)
     for (int e = tid; e < E; e += kThreads) {
@@ -98,10 +82,11 @@ __global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunk
                 rank += q_first ? 1 : 0;
             }
             ord[rank] = e;
-            atomicAdd(&nact, 1);
+            atomicAdd(nact_p, 1);
         }
     }
     __syncthreads();
+    const int nact = *nact_p;
     for (int e = tid; e < E; e += kThreads) {
         p.counts[e] = cnt[e];
         p.offsets[e] = off[e];
@@ -115,6 +100,7 @@ __global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunk
         const int b0 = pof[e] / kRowBlk, nb = (cnt[e] + kRowBlk - 1) / kRowBlk;
         for (int b = 0; b < nb; ++b) p.blk_expert[b0 + b] = e;
     }
+    __syncthreads();  // exp_tile0 / exp_ntiles are zeroed before thread 0 fills them
     if (tid == 0) {
         p.offsets[E] = off[E];
         p.poff[E] = pof[E];
@@ -154,14 +140,39 @@ __global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunk
     }
 }
 
-// P3: stable position of every assignment inside its expert's group.
-__global__ __launch_bounds__(kThreads) void plan_rank_kernel(const int32_t* __restrict__ idx, int A,
-                                                             int E, PlanPtrs p) {
-    __shared__ int32_t seg[kSegs][kMaxExperts];  // tokens of expert e in (round, wave) segment
+// P2: one block.  Sums the per-chunk histograms, then scan_body.
+__global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunks, PlanPtrs p,
+                                                             int max_tiles) {
+    __shared__ int32_t cnt[kMaxExperts];
+    __shared__ int32_t nbt[kMaxExperts];
+    __shared__ int32_t off[kMaxExperts + 1];
+    __shared__ int32_t pof[kMaxExperts + 1];
+    __shared__ int32_t ord[kMaxExperts];
+    __shared__ int32_t nact;
+    for (int e = threadIdx.x; e < s.E; e += kThreads) {
+        int run = 0;
+        unsigned long long m = 0ull;
+        for (int c = 0; c < nchunks; ++c) {
+            p.blk_base[(size_t)c * s.E + e] = run;
+            run += p.blk_counts[(size_t)c * s.E + e];
+            m |= p.blk_mask[(size_t)c * s.E + e];
+        }
+        cnt[e] = run;
+        nbt[e] = __popcll(m);
+    }
+    __syncthreads();
+    scan_body(s, p, max_tiles, cnt, nbt, off, pof, ord, &nact);
+}
+
+// Stable position of every assignment of one chunk inside its expert's group.  off[] are the
+// exclusive expert offsets, base[] (may be null = zeros) the tokens of earlier chunks.
+__device__ __forceinline__ void rank_body(const int32_t* __restrict__ idx, int A, int E,
+                                          const PlanPtrs& p, int chunk, int32_t (*seg)[kMaxExperts],
+                                          const int32_t* off, const int32_t* base_of_chunk) {
     for (int i = threadIdx.x; i < kSegs * kMaxExperts; i += kThreads) (&seg[0][0])[i] = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int base = blockIdx.x * kPlanChunk;
+    const int base = chunk * kPlanChunk;
     int my_e[kRounds], my_rank[kRounds];
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
@@ -200,12 +211,53 @@ __global__ __launch_bounds__(kThreads) void plan_rank_kernel(const int32_t* __re
         const int a = base + r * kThreads + threadIdx.x;
         const int e = my_e[r];
         if (e >= 0) {
-            const int pos = p.offsets[e] + p.blk_base[(size_t)blockIdx.x * E + e] +
+            const int pos = off[e] + (base_of_chunk ? base_of_chunk[e] : 0) +
                             seg[r * (kThreads / 64) + wave][e] + my_rank[r];
             p.inv_perm[a] = pos;
             p.perm[pos] = a;
         }
     }
+}
+
+// P3: one block per chunk.
+__global__ __launch_bounds__(kThreads) void plan_rank_kernel(const int32_t* __restrict__ idx, int A,
+                                                             int E, PlanPtrs p) {
+    __shared__ int32_t seg[kSegs][kMaxExperts];  // tokens of expert e in (round, wave) segment
+    rank_body(idx, A, E, p, blockIdx.x, seg, p.offsets, p.blk_base + (size_t)blockIdx.x * E);
+}
+
+// All three phases in one block, for batch groups of at most one chunk of assignments.
+__global__ __launch_bounds__(kThreads) void plan_fused_kernel(const int32_t* __restrict__ idx,
+                                                              Shape s, BatchOffsets bo, PlanPtrs p,
+                                                              int max_tiles) {
+    __shared__ int32_t cnt[kMaxExperts];
+    __shared__ unsigned long long msk[kMaxExperts];
+    __shared__ int32_t nbt[kMaxExperts];
+    __shared__ int32_t off[kMaxExperts + 1];
+    __shared__ int32_t pof[kMaxExperts + 1];
+    __shared__ int32_t ord[kMaxExperts];
+    __shared__ int32_t nact;
+    __shared__ int32_t seg[kSegs][kMaxExperts];
+    const int A = s.N * s.k;
+    for (int e = threadIdx.x; e < s.E; e += kThreads) {
+        cnt[e] = 0;
+        msk[e] = 0ull;
+    }
+    __syncthreads();
+    for (int r = 0; r < kRounds; ++r) {
+        const int a = r * kThreads + threadIdx.x;
+        if (a < A) {
+            const int e = idx[a];
+            atomicAdd(&cnt[e], 1);
+            atomicOr(&msk[e], 1ull << batch_of(bo, a / s.k));
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < s.E; e += kThreads) nbt[e] = __popcll(msk[e]);
+    __syncthreads();
+    scan_body(s, p, max_tiles, cnt, nbt, off, pof, ord, &nact);
+    __syncthreads();
+    rank_body(idx, A, s.E, p, 0, seg, off, nullptr);
 }
 
 }  // namespace
@@ -214,6 +266,11 @@ void launch_plan(hipStream_t st, const Shape& s, const BatchOffsets& bo, const P
                  int max_tiles) {
     const int A = s.N * s.k;
     const int nchunks = (A + kPlanChunk - 1) / kPlanChunk;
+    if (nchunks <= 1) {
+        hipLaunchKernelGGL(plan_fused_kernel, dim3(1), dim3(kThreads), 0, st, p.topk_idx, s, bo, p,
+                           max_tiles);
+        return;
+    }
     if (nchunks > 0) {
         hipLaunchKernelGGL(plan_count_kernel, dim3(nchunks), dim3(kThreads), 0, st, p.topk_idx, A,
                            s.E, s.k, bo, p.blk_counts, p.blk_mask);

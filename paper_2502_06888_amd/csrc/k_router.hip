@@ -11,7 +11,8 @@
 namespace kmoe {
 namespace {
 
-constexpr int kRouterWaves = 4;
+constexpr int kRouterWaves = 2;
+constexpr int kCB = 4;  // vectors per lane loaded together
 constexpr int kEG = 8;  // experts accumulated together
 
 template <typename T>
@@ -70,20 +71,42 @@ __global__ __launch_bounds__(kRouterWaves * 64) void router_kernel(
 #pragma unroll
     for (int s = 0; s < 4; ++s) mine[s] = 0.f;
 
+    const int cpl = (nchunk + 63) / 64;  // vectors per lane
     for (int e0 = 0; e0 < E; e0 += kEG) {
         float acc[kEG];
 #pragma unroll
         for (int j = 0; j < kEG; ++j) acc[j] = 0.f;
-        for (int c = lane; c < nchunk; c += 64) {
-            float xv[V];
-            Chunk<T>::load(xrow + (size_t)c * V, xv);
+        // kCB vectors per lane at a time: all their loads are independent and issued together,
+        // the fused multiply-adds then run in increasing element index per (expert, lane)
+        for (int c0 = 0; c0 < cpl; c0 += kCB) {
+            float xv[kCB][V];
+#pragma unroll
+            for (int q = 0; q < kCB; ++q) {
+                const int c = (c0 + q) * 64 + lane;
+                if (c < nchunk) {
+                    Chunk<T>::load(xrow + (size_t)c * V, xv[q]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < V; ++i) xv[q][i] = 0.f;
+                }
+            }
 #pragma unroll
             for (int j = 0; j < kEG; ++j) {
                 if (e0 + j < E) {
-                    float wv[V];
-                    Chunk<T>::load(Wg + (size_t)(e0 + j) * d + (size_t)c * V, wv);
+                    float wv[kCB][V];
 #pragma unroll
-                    for (int i = 0; i < V; ++i) acc[j] = __builtin_fmaf(xv[i], wv[i], acc[j]);
+                    for (int q = 0; q < kCB; ++q) {
+                        const int c = min((c0 + q) * 64 + lane, nchunk - 1);  // clamped: x is 0 there
+                        Chunk<T>::load(Wg + (size_t)(e0 + j) * d + (size_t)c * V, wv[q]);
+                    }
+#pragma unroll
+                    for (int q = 0; q < kCB; ++q) {
+                        if ((c0 + q) * 64 + lane < nchunk) {
+#pragma unroll
+                            for (int i = 0; i < V; ++i)
+                                acc[j] = __builtin_fmaf(xv[q][i], wv[q][i], acc[j]);
+                        }
+                    }
                 }
             }
         }

@@ -6,16 +6,16 @@
 namespace kmoe {
 
 constexpr int kLanes = 64;
-constexpr int kRowBlk = 16;        // rows (tokens) per MFMA block
-constexpr int kTileBlks = 16;      // row blocks per tile (256 rows)
+constexpr int kRowBlk = 32;        // rows (tokens) per MFMA block
+constexpr int kTileBlks = 8;       // row blocks per tile (256 rows)
 constexpr int kPlanChunk = 1024;   // assignments per block of the dispatch kernels
 constexpr int kMaxExperts = 256;
 constexpr int kMaxTopK = 8;
 constexpr int kMaxBatches = 64;
 
 // Capacity of the tile tables for a context.
-inline int max_tiles_for(int max_rows16, int E, int S, int max_tokens) {
-    return max_rows16 / kTileBlks + E + S * ((max_tokens + 255) / 256 + 1) + 1;
+inline int max_tiles_for(int max_rowblks, int E, int S, int max_tokens) {
+    return max_rowblks / kTileBlks + E + S * ((max_tokens + 255) / 256 + 1) + 1;
 }
 
 struct BatchOffsets {
@@ -29,29 +29,29 @@ struct PlanPtrs {
     float* topk_w;        // [A]
     int32_t* counts;      // [E]
     int32_t* offsets;     // [E+1]
-    int32_t* poff;        // [E+1]  16-padded row offsets by expert id
+    int32_t* poff;        // [E+1]  32-padded row offsets by expert id
     int32_t* nbatch;      // [E]
     int32_t* exec_order;  // [E]
-    int32_t* meta;        // [0] n_active  [1] n_tiles  [2] n_blk16 (routed)  [3] n_tokens
+    int32_t* meta;        // [0] n_active  [1] n_tiles  [2] routed row blocks  [3] n_tokens
     int32_t* perm;        // [A]
     int32_t* inv_perm;    // [A]
     int32_t* blk_counts;  // [nchunks][E]
     int32_t* blk_base;    // [nchunks][E]
     unsigned long long* blk_mask;  // [nchunks][E]
     int32_t* tile_expert; // [max_tiles]   expert id (E+s for shared)
-    int32_t* tile_xblk;   // [max_tiles]   first 16-row block in the packed activations
-    int32_t* tile_hblk;   // [max_tiles]   first 16-row block in H / O
-    int32_t* tile_nblk;   // [max_tiles]   row blocks in this tile (1..16)
+    int32_t* tile_xblk;   // [max_tiles]   first row block in the packed activations
+    int32_t* tile_hblk;   // [max_tiles]   first row block in H / O
+    int32_t* tile_nblk;   // [max_tiles]   row blocks in this tile (1..8)
     int32_t* exp_tile0;   // [E+S] first tile of an expert
     int32_t* exp_ntiles;  // [E+S]
-    int32_t* blk_expert;  // [max_blk16]   routed expert owning a 16-row block
+    int32_t* blk_expert;  // [max_rowblks] routed expert owning a row block
     int32_t* mail;        // [2E+1] counts, exec_order, n_active (copied to the host mailbox)
 };
 
 struct Shape {
     int32_t N, d, f, E, k, S;
     int32_t renorm;
-    int32_t max_rows16;   // capacity of the routed padded-row space, in 16-row blocks
+    int32_t max_rowblks;   // capacity of the routed padded-row space, in row blocks
 };
 
 // ---- router -------------------------------------------------------------------------------
@@ -82,6 +82,7 @@ struct FfnArgs {
     const int32_t* tile_first;   // device: index of the first tile of this launch (null = 0)
     const int32_t* tile_count;   // device: number of tiles of this launch
     int32_t max_tiles;           // tiles the grid was sized for
+    int32_t est_tiles;           // tiles the host expects to be live (launch-shape heuristic)
     int32_t d, f;
     int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder)
     int64_t h_plane_units;       // 16-byte units between the two planes of H

@@ -27,7 +27,7 @@ namespace {
 thread_local std::string g_last_error;
 
 struct Layout {
-    int64_t A = 0, max_rows16 = 0, tok_rows16 = 0, x_rows16 = 0, h_rows16 = 0;
+    int64_t A = 0, max_rowblks = 0, tok_rows16 = 0, x_rows16 = 0, h_rows16 = 0;
     int32_t nchunks = 0, max_tiles = 0, split_cap = 1;
     int64_t expert_bytes = 0;
     // byte offsets into the workspace
@@ -68,12 +68,12 @@ void compute_layout(const moe_config& c, Layout& L) {
     const int64_t E = c.n_experts, S = c.n_shared, k = c.top_k, d = c.d_model, f = c.d_ff;
     const int64_t elt = c.dtype == MOE_BF16 ? 2 : 4;
     L.A = (int64_t)c.max_tokens * k;
-    L.max_rows16 = (L.A + kRowBlk - 1) / kRowBlk + E;
+    L.max_rowblks = (L.A + kRowBlk - 1) / kRowBlk + E;
     L.tok_rows16 = ((int64_t)c.max_tokens + kRowBlk - 1) / kRowBlk;
-    L.x_rows16 = L.max_rows16 + (S > 0 ? L.tok_rows16 : 0);
-    L.h_rows16 = L.max_rows16 + S * L.tok_rows16;
+    L.x_rows16 = L.max_rowblks + (S > 0 ? L.tok_rows16 : 0);
+    L.h_rows16 = L.max_rowblks + S * L.tok_rows16;
     L.nchunks = (int32_t)((L.A + kPlanChunk - 1) / kPlanChunk);
-    L.max_tiles = max_tiles_for((int)L.max_rows16, (int)E, (int)S, c.max_tokens);
+    L.max_tiles = max_tiles_for((int)L.max_rowblks, (int)E, (int)S, c.max_tokens);
     L.split_cap = (c.dtype == MOE_BF16 && L.A <= 8192) ? 8 : 1;
     L.expert_bytes = 3 * d * f * elt;
     int64_t off = 0;
@@ -101,7 +101,7 @@ void compute_layout(const moe_config& c, Layout& L) {
     L.tile_nblk = take((int64_t)L.max_tiles * 4);
     L.exp_tile0 = take((E + S) * 4);
     L.exp_ntiles = take((E + S) * 4);
-    L.blk_expert = take(L.max_rows16 * 4);
+    L.blk_expert = take(L.max_rowblks * 4);
     L.mail = take((2 * E + 1) * 4);
     L.wtab = take((int64_t)c.n_layers * (E + S) * 8);
     const int64_t h_rows = L.h_rows16 * kRowBlk;
@@ -213,7 +213,7 @@ Shape make_shape(const moe_ctx* c, int n_tokens) {
     s.k = c->cfg.top_k;
     s.S = c->cfg.n_shared;
     s.renorm = c->cfg.renormalize;
-    s.max_rows16 = (int32_t)c->L.max_rows16;
+    s.max_rowblks = (int32_t)c->L.max_rowblks;
     return s;
 }
 
@@ -706,6 +706,8 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
             a.max_tiles = (int)std::min<int64_t>(ctx->L.max_tiles,
                                                  (A / kRowBlk + E) / kTileBlks + std::min<int64_t>(E, A) +
                                                      (int64_t)S * ((N + 255) / 256) + 1);
+            a.est_tiles = (int)(std::max<int64_t>(std::min<int64_t>(E, A), (A + 255) / 256) +
+                                (int64_t)S * ((N + 255) / 256));
             a.act = w + ctx->L.xp;
             a.out = w + ctx->L.h;
             a.split_k = 1;
@@ -748,6 +750,7 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
                 a.tile_first = p.exp_tile0 + e;
                 a.tile_count = p.exp_ntiles + e;
                 a.max_tiles = ctx->h_tiles[e].count;
+                a.est_tiles = a.max_tiles;
                 if (a.max_tiles == 0) return;
                 a.act = w + ctx->L.xp;
                 a.out = w + ctx->L.h;
