@@ -52,6 +52,104 @@ def cpu_baseline(w, data, budget_s: float = 15.0):
                       f"(gate, top-k, dispatch and fp64 SwiGLU experts), {t:.1f} s"}
 
 
+def measure_link_peak(torch, nbytes: int = 1 << 30, reps: int = 5) -> float:
+    """Best host->device rate of one large copy from pinned memory on this machine, GB/s."""
+    src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    st = torch.cuda.Stream()
+    best = 0.0
+    with torch.cuda.stream(st):
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            dst.copy_(src, non_blocking=True)
+            e1.record(st)
+            e1.synchronize()
+            best = max(best, nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return best
+
+
+def bench_streamed(w, args):
+    """Streamed stack: all routed experts in pinned host memory, a window of device slots, the
+    next layer's hot experts prefetched while the current layer computes.  A step is one pass
+    over all layers for one batch group (one decode step of the stack)."""
+    import torch
+    from paper_2502_06888_amd import binding as B
+    from paper_2502_06888_amd import inputs as I
+    dev = torch.device("cuda:0")
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, w.n_layers,
+                        w.window_layers, w.n_tokens, w.n_batches, B.MOE_BF16, 1)
+    ctx = B.MoeContext(cfg, compute, copy)
+    link_peak = measure_link_peak(torch)
+    t_setup = time.perf_counter()
+    xs, noise = [], None
+    for l in range(w.n_layers):                      # placement: generate, pack, park in pinned memory
+        data, noise = I.gen_layer(w, l, noise, threads=16)
+        ctx.set_gate(l, data.wg.to(dev))
+        for e in range(w.n_experts + w.n_shared):
+            where = B.MOE_HOST_PINNED if e < w.n_experts else B.MOE_RESIDENT
+            ctx.set_expert(l, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev), where)
+        xs.append(data.x.to(dev))
+        del data
+    t_setup = time.perf_counter() - t_setup
+    ys = [torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev) for _ in xs]
+    bo = [int(v) for v in w.batch_offsets]
+    K = args.prefetch if args.prefetch >= 0 else w.top_k
+    state = {"hot": []}
+
+    def one_pass():
+        n_active = []
+        for l in range(w.n_layers):
+            ctx.route(l, xs[l], bo)
+            counts, order, na = ctx.route_wait()
+            ctx.stream_experts(l, order[:na], B.MOE_ON_DEMAND)          # what the gate selected
+            nxt = (l + 1) % w.n_layers
+            hot = list(np.argsort(-np.asarray(counts), kind="stable")[:K])
+            if K > 0:
+                ctx.stream_experts(nxt, hot, B.MOE_PREFETCH)            # guess for the next layer
+            ctx.layer_forward(l, xs[l], ys[l])
+            n_active.append(na)
+        return n_active
+
+    with torch.cuda.stream(compute):
+        for _ in range(max(1, args.warmup if args.warmup < 5 else 1)):
+            one_pass()
+    torch.cuda.synchronize()
+    ctx.reset_stats()
+    steps = args.steps if args.steps <= 20 else 5
+    with torch.cuda.stream(compute):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            n_active = one_pass()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    st = ctx.stats()
+    gbs = st["bytes_h2d"] / wall / 1e9
+    out = {
+        "metric": "moe_stack_tokens_per_s", "value": w.n_tokens * steps / wall, "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": 1, "ms_per_step": wall / steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "d_model": w.d_model, "d_ff": w.d_ff, "n_experts": w.n_experts,
+                   "top_k": w.top_k, "n_shared": w.n_shared, "n_layers": w.n_layers,
+                   "tokens": w.n_tokens, "n_batches": w.n_batches, "window_layers": w.window_layers,
+                   "prefetch_per_layer": K, "experts": "pinned host memory",
+                   "n_active_per_layer": n_active},
+        "token_layers_per_s": w.n_tokens * w.n_layers * steps / wall,
+        "host_link": {"achieved_GBps": gbs, "measured_peak_GBps": link_peak, "nominal_peak_GBps": 64.0,
+                      "frac_of_nominal": gbs / 64.0, "frac_of_measured": gbs / link_peak,
+                      "bubble_link_idle": max(0.0, 1.0 - gbs / link_peak),
+                      "bytes_h2d_per_step": st["bytes_h2d"] / steps, "copies_per_step": st["n_copies"] / steps,
+                      "prefetch_hits_per_step": st["n_prefetch_hits"] / steps,
+                      "prefetch_unused_per_step": st["n_prefetch_unused"] / steps},
+        "setup_s": t_setup,
+    }
+    ctx.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +159,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--h-planes", type=int, default=0, help="0 = library default")
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
+    ap.add_argument("--prefetch", type=int, default=-1,
+                    help="streamed stacks: experts prefetched per layer (-1 = top_k)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -78,8 +178,8 @@ def main():
 
     w = I.WORKLOADS[args.workload]
     if w.streamed:
-        print("bench.py: streamed stacks are measured by bench_stream.py", file=sys.stderr)
-        sys.exit(2)
+        print(json.dumps(bench_streamed(w, args)))
+        return
     dev = torch.device("cuda:0")
     data, _ = I.gen_layer(w, 0, threads=16)
     compute = torch.cuda.Stream()
