@@ -52,6 +52,22 @@ def cpu_baseline(w, data, budget_s: float = 15.0):
                       f"(gate, top-k, dispatch and fp64 SwiGLU experts), {t:.1f} s"}
 
 
+def recorded_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE +
+    WRITE_SIZE, each scaled by the copy-kernel calibration); None when no summary covers it.
+    Counters cannot be read from inside a timed run, so this figure is the recorded one."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        f"{kernel}_{workload}_hbm_traffic.md")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(float(line.split(":", 1)[1]))
+    except OSError:
+        pass
+    return None
+
+
 def measure_link_peak(torch, nbytes: int = 1 << 30, reps: int = 5) -> float:
     """Best host->device rate of one large copy from pinned memory on this machine, GB/s."""
     src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
@@ -161,6 +177,9 @@ def main():
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
     ap.add_argument("--prefetch", type=int, default=-1,
                     help="streamed stacks: experts prefetched per layer (-1 = top_k)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel before the "
+                         "timed region, so that a counter run has a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -194,6 +213,12 @@ def main():
     x = data.x.to(dev)
     y = torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
     bo = [int(v) for v in w.batch_offsets]
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB read
+        dst = torch.empty_like(src)                                     # 1 GiB written
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        del src, dst
     torch.cuda.synchronize()
 
     def step():
@@ -251,7 +276,8 @@ def main():
                    "tokens_per_expert": counts},
         "roofline": {"bound": "hbm", "kernel": "ffn_up_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes": up_bytes},
+                     "traffic": recorded_traffic(w.name, "ffn_up_kernel"),
+                     "algorithmic_bytes": up_bytes},
         "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()},
         "layer": {"algorithmic_bytes": layer_bytes,
                   "hbm_frac_of_peak": layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
