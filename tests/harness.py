@@ -12,14 +12,15 @@ from paper_2502_06888_amd import inputs as I
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-5, 1e-5)}   # (rtol, atol): |gpu-ref| <= atol + rtol*|ref|
 
 
-def make_ctx(w: I.Workload, compute=None, copy=None, max_tokens=None, window_layers=None):
+def make_ctx(w: I.Workload, compute=None, copy=None, max_tokens=None, window_layers=None,
+             renorm: bool = True):
     compute = compute or torch.cuda.Stream()
     wl = w.window_layers if window_layers is None else window_layers
     if wl > 0 and copy is None:
         copy = torch.cuda.Stream()
     cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, w.n_layers, wl,
                         max_tokens or max(1, w.n_tokens), max(1, w.n_batches),
-                        B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1)
+                        B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1 if renorm else 0)
     return B.MoeContext(cfg, compute, copy)
 
 
@@ -74,11 +75,12 @@ def gpu_layer(ctx, w: I.Workload, layer: int, x_cpu: torch.Tensor, batch_offsets
 
 
 def oracle_layer(w: I.Workload, data: I.LayerData, batch_offsets, tokens=None,
-                 with_output=True) -> ref.LayerRef:
+                 with_output=True, renorm: bool = True) -> ref.LayerRef:
     return ref.moe_layer(I.as_f32(data.x), I.as_f32(data.wg),
                          [I.as_raw(t) for t in data.w1], [I.as_raw(t) for t in data.w3],
                          [I.as_raw(t) for t in data.w2], w.top_k, batch_offsets, w.dtype,
-                         n_shared=w.n_shared, tokens=tokens, with_output=with_output)
+                         n_shared=w.n_shared, tokens=tokens, with_output=with_output,
+                         renorm=renorm)
 
 
 def check_routing(got: dict, want: ref.LayerRef, n_experts: int):

@@ -57,6 +57,20 @@ def test_bf16_small_shapes(w):
     run_case(w)
 
 
+@pytest.mark.parametrize("w", [I.WORKLOADS["tiny_f32"], SMALL], ids=lambda w: w.name)
+def test_full_softmax_weights_without_renormalisation(w):
+    """renormalize = 0: routing weights are the full-softmax probabilities of the winners."""
+    data, _ = I.gen_layer(w, 0)
+    ctx = H.make_ctx(w, renorm=False)
+    H.place_layer(ctx, w, 0, data)
+    got = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
+    want = H.oracle_layer(w, data, w.batch_offsets, renorm=False)
+    H.check_routing(got, want, w.n_experts)
+    assert np.all(got["w"].sum(axis=1) < 1.0)
+    H.check_output(got["y"], want.y, w.dtype)
+    ctx.close()
+
+
 def test_bf16_fine_grained_with_shared_experts_and_skewed_routing():
     w = I.Workload("fine_small", "bf16", 256, 192, 64, 6, n_shared=2, batch_tokens=(16,) * 12,
                    zipf_s=1.1, corr=0.6, w_std=0.08)
