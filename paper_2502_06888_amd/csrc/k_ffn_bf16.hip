@@ -6,8 +6,10 @@
 //   down: O = H W2^T                      reduction over f, fp32, optional split-K partials
 //
 // Work split.  A tile is one expert x up to 8 row blocks of 32 tokens.  A workgroup takes a tile
-// and WAVES output units; a wavefront owns one unit for all rows of the tile, so every weight
-// byte is fetched from HBM once per tile.  An up unit is 16 features: its weight fragment
+// and WAVES * U output units; a wavefront owns U units for all rows of the tile, so every weight
+// byte is fetched from HBM once per tile and every activation fragment read from LDS feeds U
+// MFMAs (with one unit per wavefront the LDS read port, one KiB per MFMA, is what bounds the
+// matrix cores).  An up unit is 16 features: its weight fragment
 // stacks the 16 rows of W1 on the 16 rows of W3, so one 32x32x16 MFMA yields the gate and the up
 // value of the same feature in the same lane and SwiGLU needs no data movement.  A down unit is
 // 32 output columns of W2.  Weights are pre-packed so that a wavefront's stream is one
@@ -44,20 +46,16 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float v) {
 
 // One LDS stage holds, per row block, SX reduction steps of 16 for PL planes of the activations
 // (SX * PL == 8): SX = 8, PL = 1 normally; SX = 4, PL = 2 when H is carried as a bf16 pair
-// (value + rounding remainder) through the down projection.  The weight ring in registers is
-// SX steps deep, one slot per step of the stage.  The activation loads of the next stage are
-// issued before any weight load of this stage, so by the time they are waited for (end of the
-// stage) every older load in the in-order memory counter has long been consumed: waiting for
-// the activations never forces a weight prefetch to complete early.
+// (value + rounding remainder) through the down projection.
 struct TileCtx {
-    gptr wbase;     // this wavefront's weight stream (+lane), 64 units per reduction step
-    gptr actbase;   // packed activations at the tile's first row block (plane 0)
-    size_t plane;   // units between activation planes
+    gptr wbase;      // weight stream of this wavefront's first unit (+lane), 64 units per step
+    size_t ustride;  // 16-byte units between the streams of consecutive output units
+    gptr actbase;    // packed activations at the tile's first row block (plane 0)
+    size_t plane;    // units between activation planes
     u32x4* lds;
-    int nks;        // reduction steps of 16 in the whole reduction
-    int k0, k1;     // reduction steps of this workgroup: [k0, k1), k0 a multiple of SX
-    int nblk;       // live row blocks of the tile
-    bool active;    // wavefront owns a real unit
+    int nks;         // reduction steps of 16 in the whole reduction
+    int k0, k1;      // reduction steps of this workgroup: [k0, k1), k0 a multiple of SX
+    int nblk;        // live row blocks of the tile
 };
 
 // Unit u of a stage is (row block b, plane pl, step j, lane): u = ((b*PL + pl)*SX + j)*64 + lane.
@@ -89,105 +87,175 @@ __device__ __forceinline__ void store_x(const TileCtx& c, const u32x4 (&xr)[PASS
     }
 }
 
-// MFMAs of one reduction step: NB*PL fragments read from LDS through a rolling window of D
-// registers, so that D reads are in flight ahead of the matrix core; the interleaving is
-// pinned with scheduling groups (D reads, then one read per MFMA).
-template <int MODE, int NB, int SX, int PL, int D>
-__device__ __forceinline__ void step_mfma(const u32x4* L, int j, const u32x4 w, f32x16 (&acc)[NB]) {
+template <int MODE>
+__device__ __forceinline__ f32x16 mfma(const bf16x8 wf, const bf16x8 xa, const f32x16 acc) {
+    if (MODE == 0)  // rows = 16 gate + 16 up features, cols = tokens
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xa, acc, 0, 0, 0);
+    // rows = tokens, cols = output columns
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, wf, acc, 0, 0, 0);
+}
+
+// MFMAs of one reduction step for the U units of a wavefront: NB*PL activation fragments read
+// from LDS through a rolling window of D registers, each fragment feeding U MFMAs.  Used by the
+// guarded drain.
+template <int MODE, int NB, int U, int SX, int PL, int D>
+__device__ __forceinline__ void step_mfma(const u32x4* L, int j, const u32x4 (&w)[U],
+                                          f32x16 (&acc)[U][NB]) {
     constexpr int NF = NB * PL;
     constexpr int DD = D < NF ? D : NF;
     u32x4 win[DD];
-    const bf16x8 wf = as_bf16x8(w);
 #pragma unroll
     for (int i = 0; i < DD; ++i) win[i] = L[(i * SX + j) * 64];  // fragment i = (b, pl) = i/PL, i%PL
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
         const int b = i / PL;
         const bf16x8 xa = as_bf16x8(win[i % DD]);
-        if (MODE == 0)  // rows = 16 gate + 16 up features, cols = tokens
-            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xa, acc[b], 0, 0, 0);
-        else  // rows = tokens, cols = output columns
-            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, wf, acc[b], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u][b] = mfma<MODE>(as_bf16x8(w[u]), xa, acc[u][b]);
         if (i + DD < NF) win[i % DD] = L[((i + DD) * SX + j) * 64];
     }
     __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
 #pragma unroll
-    for (int i = 0; i < NF - DD; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    for (int i = 0; i < NF; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
+        if (i + DD < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, DD, 0);
 }
 
-template <int MODE, int NB, int WAVES, int SX, int PL>
-__device__ __forceinline__ void ffn_tile(const TileCtx& c, f32x16 (&acc)[NB]) {
+// MFMAs of a whole stage (SX steps) with the weight reloads of the next ring turn.  The LDS
+// window rolls across the step boundaries, so only the first D reads of a stage are exposed;
+// each ring slot is reloaded right after the last MFMA that reads it.  Order pinned: D reads,
+// then per fragment U MFMAs and one read (while any are left) and, after the last fragment of a
+// step, the U reloads of that step's slot.
+template <int MODE, int NB, int U, int SX, int PL, int D>
+__device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gptr wnext,
+                                           size_t ustride, f32x16 (&acc)[U][NB]) {
+    constexpr int NS = NB * PL;   // fragments per step
+    constexpr int NF = NS * SX;   // fragments per stage
+    constexpr int DD = D < NF ? D : NF;
+    u32x4 win[DD];
+    // fragment t of the stage: step t / NS, (row block, plane) t % NS
+#define KMOE_FRAG_AT(t) L[(((t) % NS) * SX + (t) / NS) * 64]
+#pragma unroll
+    for (int t = 0; t < DD; ++t) win[t] = KMOE_FRAG_AT(t);
+#pragma unroll
+    for (int t = 0; t < NF; ++t) {
+        const int j = t / NS, b = (t % NS) / PL;
+        const bf16x8 xa = as_bf16x8(win[t % DD]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u][b] = mfma<MODE>(as_bf16x8(w[j][u]), xa, acc[u][b]);
+        if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
+        if (t % NS == NS - 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) w[j][u] = wnext[(size_t)u * ustride + (size_t)j * 64];
+        }
+    }
+#undef KMOE_FRAG_AT
+    __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
+#pragma unroll
+    for (int t = 0; t < NF; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
+        if (t + DD < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (t % NS == NS - 1) __builtin_amdgcn_sched_group_barrier(0x020, U, 0);
+    }
+}
+
+// Register budget of one shape: the weight ring is RING steps deep (U KiB per step in flight
+// per wavefront), the activation look-ahead DX stages.
+template <int NB, int WAVES, int U>
+struct Shape2 {
+    static constexpr int RING = (U == 1) ? (NB <= 5 ? 16 : 8) : 8;
+    static constexpr int DX = (NB <= 5) ? 2 : 1;
+};
+
+template <int MODE, int NB, int WAVES, int U, int SX, int PL>
+__device__ __forceinline__ void ffn_tile(const TileCtx& c, f32x16 (&acc)[U][NB]) {
     static_assert(SX * PL == kFragsPerBlk, "stage geometry");
     constexpr int T = WAVES * 64;
     constexpr int UNITS = NB * kBlkStageUnits;
     constexpr int PASSES = (UNITS + T - 1) / T;
     constexpr int D = 3;
-    // weight ring: RS stages of SX steps.  Small tiles leave registers for a ring of 16 steps
-    // (16 KiB per wavefront in flight), full tiles get 8.
-    constexpr int RS = (NB <= 5 ? 16 : 8) / SX;
+    // weight ring: RS stages of SX steps
+    constexpr int RS = Shape2<NB, WAVES, U>::RING / SX;
+    // Activation look-ahead in stages.  The memory counter retires loads in issue order, so the
+    // wait for a stage's activations (before they are stored to LDS) also waits for every
+    // weight load issued before them.  With a look-ahead of one stage that cuts the useful
+    // depth of the weight ring to one stage whatever its size; with DX stages between the issue
+    // of the activation loads and their wait, all older weight loads have been consumed by
+    // then and the ring keeps its full depth.
+    constexpr int DX = Shape2<NB, WAVES, U>::DX;
+    constexpr int G = RS > DX ? RS : DX;  // stages per unrolled group (RS, DX in {1,2,4})
+    static_assert(RS >= 1 && G % RS == 0 && G % DX == 0, "group must cycle ring and look-ahead");
     const int lane = threadIdx.x & 63;
 
-    u32x4 wr[RS][SX];
-    u32x4 xr[PASSES];
+    u32x4 wr[RS][SX][U];
+    u32x4 xr[DX][PASSES];
 
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[u][b][i] = 0.f;
 
-    // prologue: stage the first activations, fill the weight ring
-    load_x<PASSES, T, SX, PL>(c, xr, c.k0);
+    // prologue: activations of the first DX stages and the weight ring, interleaved in the order
+    // the steady state issues them, so that the wait counts at the loop head are the same on
+    // entry and on the back edge
 #pragma unroll
-    for (int rs = 0; rs < RS; ++rs)
+    for (int i = 0; i < G; ++i) {
+        if (i < DX) load_x<PASSES, T, SX, PL>(c, xr[i], c.k0 + i * SX);
+        if (i < RS) {
 #pragma unroll
-        for (int j = 0; j < SX; ++j)
-            if (c.k0 + rs * SX + j < c.k1) wr[rs][j] = c.wbase[(size_t)(c.k0 + rs * SX + j) * 64];
-    store_x<PASSES, T>(c, xr, 0);
+            for (int j = 0; j < SX; ++j)  // past the end: re-read the last step (in bounds, unused)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    wr[i][j][u] = c.wbase[(size_t)u * c.ustride +
+                                          (size_t)min(c.k0 + i * SX + j, c.k1 - 1) * 64];
+        }
+    }
+    store_x<PASSES, T>(c, xr[0], 0);
     __syncthreads();
 
     int k = c.k0, buf = 0;
     // steady state: every stage of the group is complete, has a successor to stage and a slot to
-    // reload, so the body is branch-free
-    for (; k + 2 * RS * SX <= c.k1; k += RS * SX) {
+    // reload, so the body is branch-free (activation loads past the end re-read the last step)
+    for (; k + (G + RS) * SX <= c.k1; k += G * SX) {
 #pragma unroll
-        for (int rs = 0; rs < RS; ++rs) {
-            const int kk = k + rs * SX;
-            load_x<PASSES, T, SX, PL>(c, xr, kk + SX);
+        for (int g = 0; g < G; ++g) {
+            const int kk = k + g * SX;
+            load_x<PASSES, T, SX, PL>(c, xr[g % DX], kk + DX * SX);
             __builtin_amdgcn_sched_barrier(0);
             const u32x4* L = c.lds + buf * kBufUnits + lane;
-#pragma unroll
-            for (int j = 0; j < SX; ++j) {
-                step_mfma<MODE, NB, SX, PL, D>(L, j, wr[rs][j], acc);
-                wr[rs][j] = c.wbase[(size_t)(kk + RS * SX + j) * 64];
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            store_x<PASSES, T>(c, xr, buf ^ 1);
+            stage_mfma<MODE, NB, U, SX, PL, D>(L, wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64,
+                                               c.ustride, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            store_x<PASSES, T>(c, xr[(g + 1) % DX], buf ^ 1);
             __syncthreads();
             buf ^= 1;
         }
     }
     // drain: the last stages, guarded step by step
-    for (; k < c.k1; k += RS * SX) {
+    for (; k < c.k1; k += G * SX) {
 #pragma unroll
-        for (int rs = 0; rs < RS; ++rs) {
-            const int kk = k + rs * SX;
+        for (int g = 0; g < G; ++g) {
+            const int kk = k + g * SX;
             if (kk < c.k1) {  // uniform over the workgroup
                 const bool more = kk + SX < c.k1;
-                if (more) load_x<PASSES, T, SX, PL>(c, xr, kk + SX);
+                if (kk + DX * SX < c.k1) load_x<PASSES, T, SX, PL>(c, xr[g % DX], kk + DX * SX);
                 const u32x4* L = c.lds + buf * kBufUnits + lane;
 #pragma unroll
                 for (int j = 0; j < SX; ++j) {
                     if (kk + j < c.k1) {
-                        step_mfma<MODE, NB, SX, PL, D>(L, j, wr[rs][j], acc);
-                        if (kk + RS * SX + j < c.k1)
-                            wr[rs][j] = c.wbase[(size_t)(kk + RS * SX + j) * 64];
+                        step_mfma<MODE, NB, U, SX, PL, D>(L, j, wr[g % RS][j], acc);
+                        if (kk + RS * SX + j < c.k1) {
+#pragma unroll
+                            for (int u = 0; u < U; ++u)
+                                wr[g % RS][j][u] = c.wbase[(size_t)u * c.ustride +
+                                                           (size_t)(kk + RS * SX + j) * 64];
+                        }
                     }
                 }
-                if (more) store_x<PASSES, T>(c, xr, buf ^ 1);
+                if (more) store_x<PASSES, T>(c, xr[(g + 1) % DX], buf ^ 1);
                 __syncthreads();
                 buf ^= 1;
             }
@@ -223,59 +291,69 @@ __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) 
 // holds, in register r < 8, the gate value of feature 16*unit + 8*(r/4) + 4*hi + r%4 and in
 // register r + 8 the up value of the same feature: exactly the lane's 16-byte unit in the
 // fragment order of the down projection, so H is written with one 16-byte store per row block.
-template <int NB, int WAVES>
-__device__ __forceinline__ void up_tile(const FfnArgs& a, const TileCtx& c, int unit, int hblk0) {
-    f32x16 acc[NB];
-    ffn_tile<0, NB, WAVES, 8, 1>(c, acc);
-    if (!c.active) return;
+template <int NB, int WAVES, int U>
+__device__ __forceinline__ void up_tile(const FfnArgs& a, const TileCtx& c, int wunit, int unit0,
+                                        int hblk0) {
+    f32x16 acc[U][NB];
+    ffn_tile<0, NB, WAVES, U, 8, 1>(c, acc);
     const int lane = threadIdx.x & 63;
     u32x4* hp = reinterpret_cast<u32x4*>(a.out);
     const size_t ksteps_h = (size_t)a.f / 16;
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if (b < c.nblk) {
-            uint32_t hi[8], lo[8];
+    for (int u = 0; u < U; ++u) {
+        if (wunit + u < unit0) continue;  // streamed only to stay in bounds: another wavefront's
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const float gv = acc[b][r];
-                const float h = gv / (1.f + __expf(-gv)) * acc[b][r + 8];
-                hi[r] = bf16_bits_rne(h);
-                lo[r] = bf16_bits_rne(h - __uint_as_float(hi[r] << 16));
+        for (int b = 0; b < NB; ++b) {
+            if (b < c.nblk) {
+                uint32_t hi[8], lo[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const float gv = acc[u][b][r];
+                    // silu through the hardware reciprocal (1 ulp), far inside the bf16 rounding of H
+                    const float h = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][r + 8];
+                    hi[r] = bf16_bits_rne(h);
+                    lo[r] = bf16_bits_rne(h - __uint_as_float(hi[r] << 16));
+                }
+                const size_t at = ((size_t)(hblk0 + b) * ksteps_h + (size_t)(wunit + u)) * 64 + lane;
+                hp[at] = u32x4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16),
+                               hi[6] | (hi[7] << 16)};
+                if (a.h_planes == 2)
+                    hp[at + (size_t)a.h_plane_units] =
+                        u32x4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16),
+                              lo[6] | (lo[7] << 16)};
             }
-            const size_t at = ((size_t)(hblk0 + b) * ksteps_h + (size_t)unit) * 64 + lane;
-            hp[at] = u32x4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16),
-                           hi[6] | (hi[7] << 16)};
-            if (a.h_planes == 2)
-                hp[at + (size_t)a.h_plane_units] =
-                    u32x4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16),
-                          lo[6] | (lo[7] << 16)};
         }
     }
 }
 
 // Down projection: lane (column n = lane & 31, half hi) holds in register r the token row
 // 8*(r/4) + 4*hi + r%4 of the row block.
-template <int NB, int WAVES, int PL>
-__device__ __forceinline__ void down_tile(const FfnArgs& a, const TileCtx& c, int unit, int hblk0,
-                                          int sp) {
-    f32x16 acc[NB];
-    ffn_tile<1, NB, WAVES, 8 / PL, PL>(c, acc);
-    if (!c.active) return;
+template <int NB, int WAVES, int U, int PL>
+__device__ __forceinline__ void down_tile(const FfnArgs& a, const TileCtx& c, int wunit, int unit0,
+                                          int hblk0, int sp) {
+    f32x16 acc[U][NB];
+    ffn_tile<1, NB, WAVES, U, 8 / PL, PL>(c, acc);
     const int lane = threadIdx.x & 63;
     float* o = reinterpret_cast<float*>(a.out) + (size_t)sp * a.o_split_stride;
-    const int col = unit * 32 + (lane & 31);
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if (b < c.nblk) {
+    for (int u = 0; u < U; ++u) {
+        if (wunit + u < unit0) continue;
+        const int col = (wunit + u) * 32 + (lane & 31);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const size_t row = (size_t)(hblk0 + b) * kRowBlk + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
-                o[row * a.d + col] = acc[b][r];
+        for (int b = 0; b < NB; ++b) {
+            if (b < c.nblk) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const size_t row =
+                        (size_t)(hblk0 + b) * kRowBlk + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
+                    o[row * a.d + col] = acc[u][b][r];
+                }
             }
         }
     }
 }
 
+static_assert(kTileBlks == 8, "row-block classes below cover tiles of up to 8 blocks");
 #define NB_SWITCH(CALL)                       \
     if (nblk <= 2) { CALL(2); }               \
     else if (nblk <= 4) { CALL(4); }          \
@@ -283,7 +361,11 @@ __device__ __forceinline__ void down_tile(const FfnArgs& a, const TileCtx& c, in
     else if (nblk <= 6) { CALL(6); }          \
     else { CALL(8); }
 
-template <int WAVES>
+// A workgroup serves one tile and WAVES * U consecutive output units; wavefront w owns units
+// unit0 = (grp * WAVES + w) * U .. unit0 + U - 1, as far as they exist.  It always streams U
+// real units, wunit = min(unit0, n_units - U) onwards, so that every load stays in bounds, and
+// stores only those it owns (wunit + u >= unit0).
+template <int WAVES, int U>
 __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_groups) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, 1);
@@ -293,24 +375,25 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
     const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
-    const int unit = w.grp * WAVES + wave;
+    const int n_units = a.f / 16;
+    const int unit0 = (w.grp * WAVES + wave) * U;
     TileCtx c;
     c.nks = a.d / 16;
-    c.active = unit < a.f / 16;
-    const int wunit = c.active ? unit : a.f / 16 - 1;  // idle wavefronts shadow the last unit
-    c.wbase = as_global(blob) + (size_t)wunit * c.nks * 64 + lane;
+    const int wunit = min(unit0, n_units - U);  // n_units >= U is checked by the launcher
+    c.ustride = (size_t)c.nks * 64;
+    c.wbase = as_global(blob) + (size_t)wunit * c.ustride + lane;
     c.actbase = as_global(a.act) + (size_t)a.tile_xblk[w.tile] * c.nks * 64;
     c.plane = 0;
     c.lds = lds;
     c.k0 = 0;
     c.k1 = c.nks;
     c.nblk = nblk;
-#define CALL(NB) up_tile<NB, WAVES>(a, c, unit, hblk0)
+#define CALL(NB) up_tile<NB, WAVES, U>(a, c, wunit, unit0, hblk0)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
-template <int WAVES, int PL>
+template <int WAVES, int U, int PL>
 __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, a.split_k);
@@ -320,12 +403,13 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
     const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
-    const int unit = w.grp * WAVES + wave;
+    const int n_units = a.d / 32;
+    const int unit0 = (w.grp * WAVES + wave) * U;
     TileCtx c;
     c.nks = a.f / 16;
-    c.active = unit < a.d / 32;
-    const int wunit = c.active ? unit : a.d / 32 - 1;  // idle wavefronts shadow the last unit
-    c.wbase = as_global(blob + (size_t)a.d * a.f * 4) + (size_t)wunit * c.nks * 64 + lane;
+    const int wunit = min(unit0, n_units - U);
+    c.ustride = (size_t)c.nks * 64;
+    c.wbase = as_global(blob + (size_t)a.d * a.f * 4) + (size_t)wunit * c.ustride + lane;
     c.actbase = as_global(a.act) + (size_t)hblk0 * c.nks * 64;
     c.plane = (size_t)a.h_plane_units;
     c.lds = lds;
@@ -334,25 +418,25 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
     c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
     c.nblk = nblk;
-#define CALL(NB) down_tile<NB, WAVES, PL>(a, c, unit, hblk0, w.sp)
+#define CALL(NB) down_tile<NB, WAVES, U, PL>(a, c, wunit, unit0, hblk0, w.sp)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
-template <int WAVES>
+template <int WAVES, int U>
 void launch_up(hipStream_t st, const FfnArgs& a) {
-    const int n_groups = (a.f / 16 + WAVES - 1) / WAVES;
+    const int n_groups = (a.f / 16 + WAVES * U - 1) / (WAVES * U);
     const int grid = (a.max_tiles * n_groups + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((ffn_up_kernel<WAVES>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st, a,
+    hipLaunchKernelGGL((ffn_up_kernel<WAVES, U>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st, a,
                        n_groups);
 }
 
-template <int WAVES, int PL>
+template <int WAVES, int U, int PL>
 void launch_down(hipStream_t st, const FfnArgs& a) {
-    const int n_groups = (a.d / 32 + WAVES - 1) / WAVES;
+    const int n_groups = (a.d / 32 + WAVES * U - 1) / (WAVES * U);
     const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((ffn_down_kernel<WAVES, PL>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st,
-                       a, n_groups);
+    hipLaunchKernelGGL((ffn_down_kernel<WAVES, U, PL>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
+                       st, a, n_groups);
 }
 
 template <typename K>
@@ -361,11 +445,23 @@ hipError_t allow_lds(K kernel) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
 }
 
+}  // namespace
+
+int ffn_configure() {
+    hipError_t e = allow_lds(&ffn_up_kernel<8, 1>);
+
+    if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<7, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<4, 2>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 2>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 2>);
+    return (int)e;
+}
+
 // 8 or 7 wavefronts per workgroup, whichever leaves the smaller idle tail in the last round
 // of workgroups over the 256 compute units (one workgroup per unit at a time).
-int pick_waves(int units, int64_t tiles_times_split, int variant) {
-    if (variant == 1) return 8;
-    if (variant == 2) return 7;
+static int pick_waves(int units, int64_t tiles_times_split) {
     double best = 0.0;
     int pick = 8;
     for (int w : {8, 7}) {
@@ -380,28 +476,30 @@ int pick_waves(int units, int64_t tiles_times_split, int variant) {
     return pick;
 }
 
-}  // namespace
-
-int ffn_configure() {
-    hipError_t e = allow_lds(&ffn_up_kernel<8>);
-    if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<7>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 2>);
-    return (int)e;
-}
-
+// Launch shapes.  variant 1 / 2: eight / seven wavefronts per workgroup, one output unit each;
+// variant 3: four wavefronts with two units each (every activation fragment read from LDS feeds
+// two MFMAs).  Default: tiles expected to be full (many rows per expert, MFMA-bound) take the
+// two-unit shape, small tiles (weight streaming dominates) take 8 or 7 single-unit wavefronts.
 void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) {
-    if (pick_waves(a.f / 16, a.est_tiles, a.variant) == 7)
-        launch_up<7>(st, a);
+    const int units = a.f / 16;
+    int v = a.variant;
+    if (v == 0) v = a.full_tiles ? 3 : (pick_waves(units, a.est_tiles) == 7 ? 2 : 1);
+    if (v == 3 && units >= 2)
+        launch_up<4, 2>(st, a);
+    else if (v == 2)
+        launch_up<7, 1>(st, a);
     else
-        launch_up<8>(st, a);
+        launch_up<8, 1>(st, a);
 }
 
 void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
-    if (a.h_planes == 2)
-        launch_down<8, 2>(st, a);
-    else
-        launch_down<8, 1>(st, a);
+    const int units = a.d / 32;
+    const bool two = a.variant == 3 && units >= 2;  // measured: one unit per wavefront is faster here
+    if (a.h_planes == 2) {
+        if (two) launch_down<4, 2, 2>(st, a); else launch_down<8, 1, 2>(st, a);
+    } else {
+        if (two) launch_down<4, 2, 1>(st, a); else launch_down<8, 1, 1>(st, a);
+    }
 }
 
 }  // namespace kmoe

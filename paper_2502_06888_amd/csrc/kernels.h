@@ -15,7 +15,7 @@ constexpr int kMaxBatches = 64;
 
 // Capacity of the tile tables for a context.
 inline int max_tiles_for(int max_rowblks, int E, int S, int max_tokens) {
-    return max_rowblks / kTileBlks + E + S * ((max_tokens + 255) / 256 + 1) + 1;
+    return max_rowblks / kTileBlks + E + S * ((max_tokens + kTileBlks * kRowBlk - 1) / (kTileBlks * kRowBlk) + 1) + 1;
 }
 
 struct BatchOffsets {
@@ -86,7 +86,8 @@ struct FfnArgs {
     int32_t d, f;
     int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder)
     int64_t h_plane_units;       // 16-byte units between the two planes of H
-    int32_t variant;             // kernel shape (waves per workgroup, prefetch depth); 0 = default
+    int32_t variant;             // kernel shape (waves per workgroup x units per wave); 0 = default
+    int32_t full_tiles;          // host estimate: most tiles are full (more than 160 rows per expert)
     int32_t split_k;             // down projection only
     int64_t o_split_stride;      // elements between split-K partials of O
 };

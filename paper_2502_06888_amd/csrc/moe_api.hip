@@ -23,6 +23,8 @@
 using namespace kmoe;
 
 namespace {
+constexpr int kTileRows = kRowBlk * kTileBlks;
+
 
 thread_local std::string g_last_error;
 
@@ -230,8 +232,8 @@ int auto_split_k(const moe_ctx* c, int n_tokens) {
     cap = std::min(cap, nstage);
     if (c->split_k_user > 0) return std::min(c->split_k_user, cap);
     const int64_t A = (int64_t)n_tokens * c->cfg.top_k;
-    const int64_t tiles = std::max<int64_t>(std::min<int64_t>(c->cfg.n_experts, A), (A + 255) / 256) +
-                          (int64_t)c->cfg.n_shared * ((n_tokens + 255) / 256);
+    const int64_t tiles = std::max<int64_t>(std::min<int64_t>(c->cfg.n_experts, A), (A + kTileRows - 1) / kTileRows) +
+                          (int64_t)c->cfg.n_shared * ((n_tokens + kTileRows - 1) / kTileRows);
     const int64_t groups = (c->cfg.d_model / 32 + 7) / 8;
     const int64_t wgs = std::max<int64_t>(1, tiles * groups);
     int64_t want = (512 + wgs - 1) / wgs;
@@ -688,6 +690,7 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
     a.f = s.f;
     a.o_split_stride = ctx->L.o_split_stride;
     a.variant = ctx->variant;
+    a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
     a.h_planes = ctx->h_planes;
     a.h_plane_units = ctx->L.h_plane_units;
 
@@ -705,9 +708,9 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
             const int64_t A = (int64_t)N * s.k;
             a.max_tiles = (int)std::min<int64_t>(ctx->L.max_tiles,
                                                  (A / kRowBlk + E) / kTileBlks + std::min<int64_t>(E, A) +
-                                                     (int64_t)S * ((N + 255) / 256) + 1);
-            a.est_tiles = (int)(std::max<int64_t>(std::min<int64_t>(E, A), (A + 255) / 256) +
-                                (int64_t)S * ((N + 255) / 256));
+                                                     (int64_t)S * ((N + kTileRows - 1) / kTileRows) + 1);
+            a.est_tiles = (int)(std::max<int64_t>(std::min<int64_t>(E, A), (A + kTileRows - 1) / kTileRows) +
+                                (int64_t)S * ((N + kTileRows - 1) / kTileRows));
             a.act = w + ctx->L.xp;
             a.out = w + ctx->L.h;
             a.split_k = 1;
