@@ -204,8 +204,9 @@ moe_status moe_reset_stats(moe_ctx* ctx);
  * H = silu(X W1^T) .* (X W3^T) between the two GEMMs as a pair of bf16 numbers (value and
  * rounding remainder), which keeps the layer inside the 1e-2 absolute tolerance at d_ff = 14336;
  * 1 stores plain bf16 H (one third fewer MFMA operations, about twice the output error).
- * variant: launch shape of the bf16 expert kernels (waves per workgroup x prefetch depth);
- * -1 selects the default shape again.
+ * variant: launch shape of the bf16 expert kernels, ones digit: 1 = 8 wavefronts x 1 output unit,
+ * 2 = 7 x 1, 3 = 4 x 2 (0 = chosen by tile size); tens digit: passes per workgroup (0 = default);
+ * -1 selects the defaults again.
  */
 moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant);
 

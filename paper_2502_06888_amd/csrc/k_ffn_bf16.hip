@@ -24,6 +24,7 @@ namespace kmoe {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte unit as a first-class value
 typedef const __attribute__((address_space(1))) u32x4* gptr;  // global (HBM) address space
@@ -35,6 +36,10 @@ constexpr int kBufUnits = kTileBlks * kBlkStageUnits;
 constexpr int kLdsBytes = 2 * kBufUnits * 16;  // 128 KiB, double buffered
 
 __device__ __forceinline__ gptr as_global(const void* p) { return (gptr)(uintptr_t)p; }
+
+// Weights are read exactly once per tile: a streaming (non-temporal) load keeps them from
+// taking cache lines that the re-read activations need, and measurably raises the HBM rate.
+__device__ __forceinline__ u32x4 load_stream(gptr p) { return __builtin_nontemporal_load(p); }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -147,7 +152,7 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
         if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
         if (t % NS == NS - 1) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) w[j][u] = wnext[(size_t)u * ustride + (size_t)j * 64];
+            for (int u = 0; u < U; ++u) w[j][u] = load_stream(wnext + (size_t)u * ustride + (size_t)j * 64);
         }
     }
 #undef KMOE_FRAG_AT
@@ -168,28 +173,58 @@ struct Shape2 {
     static constexpr int DX = (NB <= 5) ? 2 : 1;
 };
 
-template <int MODE, int NB, int WAVES, int U, int SX, int PL>
-__device__ __forceinline__ void ffn_tile(const TileCtx& c, f32x16 (&acc)[U][NB]) {
-    static_assert(SX * PL == kFragsPerBlk, "stage geometry");
-    constexpr int T = WAVES * 64;
-    constexpr int UNITS = NB * kBlkStageUnits;
-    constexpr int PASSES = (UNITS + T - 1) / T;
-    constexpr int D = 3;
-    // weight ring: RS stages of SX steps
-    constexpr int RS = Shape2<NB, WAVES, U>::RING / SX;
+// Registers of the software pipeline of one tile pass: the weight ring (RS stages of SX steps,
+// U units) and the activations in flight to LDS (DX stages ahead).
+template <int NB, int WAVES, int U, int SX>
+struct Pipe {
+    static constexpr int T = WAVES * 64;
+    static constexpr int PASSES = (NB * kBlkStageUnits + T - 1) / T;
+    static constexpr int RS = Shape2<NB, WAVES, U>::RING / SX;
     // Activation look-ahead in stages.  The memory counter retires loads in issue order, so the
     // wait for a stage's activations (before they are stored to LDS) also waits for every
     // weight load issued before them.  With a look-ahead of one stage that cuts the useful
     // depth of the weight ring to one stage whatever its size; with DX stages between the issue
     // of the activation loads and their wait, all older weight loads have been consumed by
     // then and the ring keeps its full depth.
-    constexpr int DX = Shape2<NB, WAVES, U>::DX;
-    constexpr int G = RS > DX ? RS : DX;  // stages per unrolled group (RS, DX in {1,2,4})
+    static constexpr int DX = Shape2<NB, WAVES, U>::DX;
+    static constexpr int G = RS > DX ? RS : DX;  // stages per unrolled group (RS, DX in {1,2,4})
     static_assert(RS >= 1 && G % RS == 0 && G % DX == 0, "group must cycle ring and look-ahead");
-    const int lane = threadIdx.x & 63;
-
     u32x4 wr[RS][SX][U];
     u32x4 xr[DX][PASSES];
+};
+
+// Issue the loads that open a pass: activations of the first DX stages and the whole weight
+// ring, interleaved in the order the steady state issues them, so that the wait counts at the
+// loop head are the same on entry and on the back edge.  Nothing is waited for here: a
+// workgroup calls this for its next pass before the epilogue of the current one, so the
+// memory latency of the ring fill hides behind the epilogue.
+template <int NB, int WAVES, int U, int SX, int PL>
+__device__ __forceinline__ void open_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX>& pp) {
+    using P = Pipe<NB, WAVES, U, SX>;
+#pragma unroll
+    for (int i = 0; i < P::G; ++i) {
+        if (i < P::DX) load_x<P::PASSES, P::T, SX, PL>(c, pp.xr[i], c.k0 + i * SX);
+        if (i < P::RS) {
+#pragma unroll
+            for (int j = 0; j < SX; ++j)  // past the end: re-read the last step (in bounds, unused)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    pp.wr[i][j][u] = load_stream(c.wbase + (size_t)u * c.ustride +
+                                                 (size_t)min(c.k0 + i * SX + j, c.k1 - 1) * 64);
+        }
+    }
+}
+
+// One pass over the reduction range of the tile for the U units of every wavefront; the pass
+// must have been opened.  On return all LDS reads of the pass are behind a barrier.
+template <int MODE, int NB, int WAVES, int U, int SX, int PL>
+__device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX>& pp,
+                                         f32x16 (&acc)[U][NB]) {
+    static_assert(SX * PL == kFragsPerBlk, "stage geometry");
+    using P = Pipe<NB, WAVES, U, SX>;
+    constexpr int T = P::T, PASSES = P::PASSES, RS = P::RS, DX = P::DX, G = P::G;
+    constexpr int D = 3;
+    const int lane = threadIdx.x & 63;
 
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -198,22 +233,7 @@ __device__ __forceinline__ void ffn_tile(const TileCtx& c, f32x16 (&acc)[U][NB])
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[u][b][i] = 0.f;
 
-    // prologue: activations of the first DX stages and the weight ring, interleaved in the order
-    // the steady state issues them, so that the wait counts at the loop head are the same on
-    // entry and on the back edge
-#pragma unroll
-    for (int i = 0; i < G; ++i) {
-        if (i < DX) load_x<PASSES, T, SX, PL>(c, xr[i], c.k0 + i * SX);
-        if (i < RS) {
-#pragma unroll
-            for (int j = 0; j < SX; ++j)  // past the end: re-read the last step (in bounds, unused)
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    wr[i][j][u] = c.wbase[(size_t)u * c.ustride +
-                                          (size_t)min(c.k0 + i * SX + j, c.k1 - 1) * 64];
-        }
-    }
-    store_x<PASSES, T>(c, xr[0], 0);
+    store_x<PASSES, T>(c, pp.xr[0], 0);
     __syncthreads();
 
     int k = c.k0, buf = 0;
@@ -223,13 +243,13 @@ __device__ __forceinline__ void ffn_tile(const TileCtx& c, f32x16 (&acc)[U][NB])
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int kk = k + g * SX;
-            load_x<PASSES, T, SX, PL>(c, xr[g % DX], kk + DX * SX);
+            load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
             __builtin_amdgcn_sched_barrier(0);
             const u32x4* L = c.lds + buf * kBufUnits + lane;
-            stage_mfma<MODE, NB, U, SX, PL, D>(L, wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64,
-                                               c.ustride, acc);
+            stage_mfma<MODE, NB, U, SX, PL, D>(L, pp.wr[g % RS],
+                                               c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc);
             __builtin_amdgcn_sched_barrier(0);
-            store_x<PASSES, T>(c, xr[(g + 1) % DX], buf ^ 1);
+            store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
             __syncthreads();
             buf ^= 1;
         }
@@ -241,21 +261,23 @@ __device__ __forceinline__ void ffn_tile(const TileCtx& c, f32x16 (&acc)[U][NB])
             const int kk = k + g * SX;
             if (kk < c.k1) {  // uniform over the workgroup
                 const bool more = kk + SX < c.k1;
-                if (kk + DX * SX < c.k1) load_x<PASSES, T, SX, PL>(c, xr[g % DX], kk + DX * SX);
+                if (kk + DX * SX < c.k1)
+                    load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
                 const u32x4* L = c.lds + buf * kBufUnits + lane;
 #pragma unroll
                 for (int j = 0; j < SX; ++j) {
                     if (kk + j < c.k1) {
-                        step_mfma<MODE, NB, U, SX, PL, D>(L, j, wr[g % RS][j], acc);
+                        step_mfma<MODE, NB, U, SX, PL, D>(L, j, pp.wr[g % RS][j], acc);
                         if (kk + RS * SX + j < c.k1) {
 #pragma unroll
                             for (int u = 0; u < U; ++u)
-                                wr[g % RS][j][u] = c.wbase[(size_t)u * c.ustride +
-                                                           (size_t)(kk + RS * SX + j) * 64];
+                                pp.wr[g % RS][j][u] =
+                                    load_stream(c.wbase + (size_t)u * c.ustride +
+                                                (size_t)(kk + RS * SX + j) * 64);
                         }
                     }
                 }
-                if (more) store_x<PASSES, T>(c, xr[(g + 1) % DX], buf ^ 1);
+                if (more) store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
                 __syncthreads();
                 buf ^= 1;
             }
@@ -291,11 +313,9 @@ __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) 
 // holds, in register r < 8, the gate value of feature 16*unit + 8*(r/4) + 4*hi + r%4 and in
 // register r + 8 the up value of the same feature: exactly the lane's 16-byte unit in the
 // fragment order of the down projection, so H is written with one 16-byte store per row block.
-template <int NB, int WAVES, int U>
-__device__ __forceinline__ void up_tile(const FfnArgs& a, const TileCtx& c, int wunit, int unit0,
-                                        int hblk0) {
-    f32x16 acc[U][NB];
-    ffn_tile<0, NB, WAVES, U, 8, 1>(c, acc);
+template <int NB, int U>
+__device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U][NB], int nblk,
+                                         int wunit, int unit0, int hblk0) {
     const int lane = threadIdx.x & 63;
     u32x4* hp = reinterpret_cast<u32x4*>(a.out);
     const size_t ksteps_h = (size_t)a.f / 16;
@@ -304,23 +324,30 @@ __device__ __forceinline__ void up_tile(const FfnArgs& a, const TileCtx& c, int 
         if (wunit + u < unit0) continue;  // streamed only to stay in bounds: another wavefront's
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            if (b < c.nblk) {
-                uint32_t hi[8], lo[8];
+            if (b < nblk) {
+                // H = silu(gate) * up, rounded to bf16 (RNE, hardware conversion); the second plane
+                // carries the rounding remainder.  silu through the hardware reciprocal (1 ulp),
+                // far inside the bf16 rounding of H.
+                uint32_t hi[4], lo[4];
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    const float gv = acc[u][b][r];
-                    // silu through the hardware reciprocal (1 ulp), far inside the bf16 rounding of H
-                    const float h = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][r + 8];
-                    hi[r] = bf16_bits_rne(h);
-                    lo[r] = bf16_bits_rne(h - __uint_as_float(hi[r] << 16));
+                for (int q = 0; q < 4; ++q) {
+                    float h[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const float gv = acc[u][b][2 * q + t];
+                        h[t] = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][2 * q + t + 8];
+                    }
+                    const bf16x2 v = {(__bf16)h[0], (__bf16)h[1]};
+                    const bf16x2 l = {(__bf16)(h[0] - (float)v[0]), (__bf16)(h[1] - (float)v[1])};
+                    hi[q] = __builtin_bit_cast(uint32_t, v);
+                    lo[q] = __builtin_bit_cast(uint32_t, l);
                 }
                 const size_t at = ((size_t)(hblk0 + b) * ksteps_h + (size_t)(wunit + u)) * 64 + lane;
-                hp[at] = u32x4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16),
-                               hi[6] | (hi[7] << 16)};
+                // streaming stores: measurably cheaper next to the weight stream than cached ones
+                __builtin_nontemporal_store(u32x4{hi[0], hi[1], hi[2], hi[3]}, hp + at);
                 if (a.h_planes == 2)
-                    hp[at + (size_t)a.h_plane_units] =
-                        u32x4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16),
-                              lo[6] | (lo[7] << 16)};
+                    __builtin_nontemporal_store(u32x4{lo[0], lo[1], lo[2], lo[3]},
+                                                hp + at + (size_t)a.h_plane_units);
             }
         }
     }
@@ -328,11 +355,9 @@ __device__ __forceinline__ void up_tile(const FfnArgs& a, const TileCtx& c, int 
 
 // Down projection: lane (column n = lane & 31, half hi) holds in register r the token row
 // 8*(r/4) + 4*hi + r%4 of the row block.
-template <int NB, int WAVES, int U, int PL>
-__device__ __forceinline__ void down_tile(const FfnArgs& a, const TileCtx& c, int wunit, int unit0,
-                                          int hblk0, int sp) {
-    f32x16 acc[U][NB];
-    ffn_tile<1, NB, WAVES, U, 8 / PL, PL>(c, acc);
+template <int NB, int U>
+__device__ __forceinline__ void store_down(const FfnArgs& a, const f32x16 (&acc)[U][NB], int nblk,
+                                           int wunit, int unit0, int hblk0, int sp) {
     const int lane = threadIdx.x & 63;
     float* o = reinterpret_cast<float*>(a.out) + (size_t)sp * a.o_split_stride;
 #pragma unroll
@@ -341,75 +366,96 @@ __device__ __forceinline__ void down_tile(const FfnArgs& a, const TileCtx& c, in
         const int col = (wunit + u) * 32 + (lane & 31);
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            if (b < c.nblk) {
+            if (b < nblk) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const size_t row =
                         (size_t)(hblk0 + b) * kRowBlk + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
-                    o[row * a.d + col] = acc[u][b][r];
+                    __builtin_nontemporal_store(acc[u][b][r], o + row * a.d + col);
                 }
             }
         }
     }
 }
 
-static_assert(kTileBlks == 8, "row-block classes below cover tiles of up to 8 blocks");
+// All passes of a workgroup over its tile.  A workgroup serves WAVES * U consecutive output
+// units per pass and `passes` consecutive such runs; wavefront w owns, in pass p, the units
+// unit0 = ((grp * passes + p) * WAVES + w) * U .. unit0 + U - 1, as far as they exist.  It always
+// streams U real units, wunit = min(unit0, n_units - U) onwards, so that every load stays in
+// bounds, and stores only those it owns (wunit + u >= unit0).  The loads that open pass p + 1 are
+// issued before the epilogue of pass p.
+template <int MODE, int NB, int WAVES, int U, int PL>
+__device__ __forceinline__ void run_tile(const FfnArgs& a, TileCtx c, gptr wsection, int n_units,
+                                         int grp, int passes, int hblk0, int sp) {
+    constexpr int SX = 8 / PL;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    Pipe<NB, WAVES, U, SX> pp;
+    f32x16 acc[U][NB];
+    auto first_unit = [&](int p) { return ((grp * passes + p) * WAVES + wave) * U; };
+    auto live = [&](int p) { return p < passes && (grp * passes + p) * WAVES * U < n_units; };
+    int unit0 = first_unit(0);
+    int wunit = min(unit0, n_units - U);
+    c.wbase = wsection + (size_t)wunit * c.ustride + lane;
+    open_pass<NB, WAVES, U, SX, PL>(c, pp);
+    for (int p = 0; live(p); ++p) {  // uniform over the workgroup
+        run_pass<MODE, NB, WAVES, U, SX, PL>(c, pp, acc);
+        const int done_wunit = wunit, done_unit0 = unit0;
+        if (live(p + 1)) {
+            unit0 = first_unit(p + 1);
+            wunit = min(unit0, n_units - U);
+            c.wbase = wsection + (size_t)wunit * c.ustride + lane;
+            open_pass<NB, WAVES, U, SX, PL>(c, pp);
+        }
+        if (MODE == 0)
+            store_up<NB, U>(a, acc, c.nblk, done_wunit, done_unit0, hblk0);
+        else
+            store_down<NB, U>(a, acc, c.nblk, done_wunit, done_unit0, hblk0, sp);
+    }
+}
+
 #define NB_SWITCH(CALL)                       \
     if (nblk <= 2) { CALL(2); }               \
     else if (nblk <= 4) { CALL(4); }          \
     else if (nblk <= 5) { CALL(5); }          \
     else if (nblk <= 6) { CALL(6); }          \
     else { CALL(8); }
+static_assert(kTileBlks == 8, "row-block classes above cover tiles of up to 8 blocks");
 
-// A workgroup serves one tile and WAVES * U consecutive output units; wavefront w owns units
-// unit0 = (grp * WAVES + w) * U .. unit0 + U - 1, as far as they exist.  It always streams U
-// real units, wunit = min(unit0, n_units - U) onwards, so that every load stays in bounds, and
-// stores only those it owns (wunit + u >= unit0).
 template <int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_groups) {
+__global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_groups, int passes) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, 1);
     if (!w.live) return;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int e = a.tile_expert[w.tile];
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
     const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
-    const int n_units = a.f / 16;
-    const int unit0 = (w.grp * WAVES + wave) * U;
     TileCtx c;
     c.nks = a.d / 16;
-    const int wunit = min(unit0, n_units - U);  // n_units >= U is checked by the launcher
     c.ustride = (size_t)c.nks * 64;
-    c.wbase = as_global(blob) + (size_t)wunit * c.ustride + lane;
     c.actbase = as_global(a.act) + (size_t)a.tile_xblk[w.tile] * c.nks * 64;
     c.plane = 0;
     c.lds = lds;
     c.k0 = 0;
     c.k1 = c.nks;
     c.nblk = nblk;
-#define CALL(NB) up_tile<NB, WAVES, U>(a, c, wunit, unit0, hblk0)
+#define CALL(NB) run_tile<0, NB, WAVES, U, 1>(a, c, as_global(blob), a.f / 16, w.grp, passes, hblk0, 0)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
 template <int WAVES, int U, int PL>
-__global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups) {
+__global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups, int passes) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, a.split_k);
     if (!w.live) return;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int e = a.tile_expert[w.tile];
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
     const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
-    const int n_units = a.d / 32;
-    const int unit0 = (w.grp * WAVES + wave) * U;
     TileCtx c;
     c.nks = a.f / 16;
-    const int wunit = min(unit0, n_units - U);
     c.ustride = (size_t)c.nks * 64;
-    c.wbase = as_global(blob + (size_t)a.d * a.f * 4) + (size_t)wunit * c.ustride + lane;
     c.actbase = as_global(a.act) + (size_t)hblk0 * c.nks * 64;
     c.plane = (size_t)a.h_plane_units;
     c.lds = lds;
@@ -418,25 +464,35 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
     c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
     c.nblk = nblk;
-#define CALL(NB) down_tile<NB, WAVES, U, PL>(a, c, wunit, unit0, hblk0, w.sp)
+#define CALL(NB) \
+    run_tile<1, NB, WAVES, U, PL>(a, c, as_global(blob + (size_t)a.d * a.f * 4), a.d / 32, w.grp, passes, hblk0, w.sp)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
+// Passes per workgroup.  Measured on the decode layer, more than one pass per workgroup (which
+// hides the ring fill of the next pass behind the epilogue) gains nothing: the kernel is bound
+// chip-wide, not per workgroup.  One pass keeps the most workgroups in flight.
+static int pick_passes(int64_t) { return 1; }
+
 template <int WAVES, int U>
 void launch_up(hipStream_t st, const FfnArgs& a) {
-    const int n_groups = (a.f / 16 + WAVES * U - 1) / (WAVES * U);
+    const int runs = (a.f / 16 + WAVES * U - 1) / (WAVES * U);
+    const int passes = a.passes > 0 ? a.passes : pick_passes((int64_t)a.est_tiles * runs);
+    const int n_groups = (runs + passes - 1) / passes;
     const int grid = (a.max_tiles * n_groups + kXcd - 1) / kXcd * kXcd;
     hipLaunchKernelGGL((ffn_up_kernel<WAVES, U>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st, a,
-                       n_groups);
+                       n_groups, passes);
 }
 
 template <int WAVES, int U, int PL>
 void launch_down(hipStream_t st, const FfnArgs& a) {
-    const int n_groups = (a.d / 32 + WAVES * U - 1) / (WAVES * U);
+    const int runs = (a.d / 32 + WAVES * U - 1) / (WAVES * U);
+    const int passes = a.passes > 0 ? a.passes : pick_passes((int64_t)a.est_tiles * runs * a.split_k);
+    const int n_groups = (runs + passes - 1) / passes;
     const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
     hipLaunchKernelGGL((ffn_down_kernel<WAVES, U, PL>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
-                       st, a, n_groups);
+                       st, a, n_groups, passes);
 }
 
 template <typename K>
@@ -459,31 +515,14 @@ int ffn_configure() {
     return (int)e;
 }
 
-// 8 or 7 wavefronts per workgroup, whichever leaves the smaller idle tail in the last round
-// of workgroups over the 256 compute units (one workgroup per unit at a time).
-static int pick_waves(int units, int64_t tiles_times_split) {
-    double best = 0.0;
-    int pick = 8;
-    for (int w : {8, 7}) {
-        const int64_t wgs = tiles_times_split * ((units + w - 1) / w);
-        const int64_t rounds = (wgs + 255) / 256;
-        const double busy = (double)units * tiles_times_split / ((double)rounds * 256 * w);
-        if (busy > best + 1e-9) {
-            best = busy;
-            pick = w;
-        }
-    }
-    return pick;
-}
-
 // Launch shapes.  variant 1 / 2: eight / seven wavefronts per workgroup, one output unit each;
 // variant 3: four wavefronts with two units each (every activation fragment read from LDS feeds
 // two MFMAs).  Default: tiles expected to be full (many rows per expert, MFMA-bound) take the
-// two-unit shape, small tiles (weight streaming dominates) take 8 or 7 single-unit wavefronts.
+// two-unit shape, small tiles (weight streaming dominates) eight single-unit wavefronts.
 void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) {
     const int units = a.f / 16;
     int v = a.variant;
-    if (v == 0) v = a.full_tiles ? 3 : (pick_waves(units, a.est_tiles) == 7 ? 2 : 1);
+    if (v == 0) v = a.full_tiles ? 3 : 1;
     if (v == 3 && units >= 2)
         launch_up<4, 2>(st, a);
     else if (v == 2)

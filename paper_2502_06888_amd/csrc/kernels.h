@@ -87,6 +87,7 @@ struct FfnArgs {
     int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder)
     int64_t h_plane_units;       // 16-byte units between the two planes of H
     int32_t variant;             // kernel shape (waves per workgroup x units per wave); 0 = default
+    int32_t passes;              // runs of units per workgroup (0 = chosen from the tile estimate)
     int32_t full_tiles;          // host estimate: most tiles are full (more than 160 rows per expert)
     int32_t split_k;             // down projection only
     int64_t o_split_stride;      // elements between split-K partials of O

@@ -236,7 +236,7 @@ int auto_split_k(const moe_ctx* c, int n_tokens) {
                           (int64_t)c->cfg.n_shared * ((n_tokens + kTileRows - 1) / kTileRows);
     const int64_t groups = (c->cfg.d_model / 32 + 7) / 8;
     const int64_t wgs = std::max<int64_t>(1, tiles * groups);
-    int64_t want = (512 + wgs - 1) / wgs;
+    int64_t want = (256 + wgs - 1) / wgs;  // one workgroup per compute unit; partial sums cost the combine
     return (int)std::max<int64_t>(1, std::min<int64_t>(want, cap));
 }
 
@@ -689,7 +689,8 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
     a.d = s.d;
     a.f = s.f;
     a.o_split_stride = ctx->L.o_split_stride;
-    a.variant = ctx->variant;
+    a.variant = ctx->variant % 10;
+    a.passes = ctx->variant / 10;
     a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
     a.h_planes = ctx->h_planes;
     a.h_plane_units = ctx->L.h_plane_units;
@@ -837,7 +838,7 @@ moe_status moe_get_profile(moe_ctx* ctx, moe_profile* out) {
 }
 
 moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant) {
-    if (variant < -1 || variant > 8) return fail(ctx, MOE_ERR_INVALID_ARG, "variant out of range");
+    if (variant < -1 || variant > 49) return fail(ctx, MOE_ERR_INVALID_ARG, "variant out of range");
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
     if (split_k < 0 || split_k > 64) return fail(ctx, MOE_ERR_INVALID_ARG, "split_k out of range");
     if (h_planes < 0 || h_planes > 2) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1 or 2");
