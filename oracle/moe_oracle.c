@@ -278,3 +278,54 @@ void ko_moe_forward(const float *X, const int32_t *idx, const double *w, int d, 
         free(h);
     }
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Expert correlation table, path length l = 1 (paper Section 6.2).
+ *
+ * table[p][e] counts how often a token that activated expert p in the previous expert layer
+ * activated expert e in this one; every (previous slot, current slot) pair of a token counts
+ * once.  Plain loops over tokens and slot pairs.
+ */
+void ko_corr_update(const int32_t *idx_prev, const int32_t *idx_cur, int N, int k, int E,
+                    int64_t *table) {
+    for (int t = 0; t < N; ++t)
+        for (int a = 0; a < k; ++a)
+            for (int b = 0; b < k; ++b)
+                table[(size_t)idx_prev[(size_t)t * k + a] * E + idx_cur[(size_t)t * k + b]] += 1;
+}
+
+/* Tendency of the batch group towards the experts of this layer, and the K experts to prefetch.
+ * A token that activated p in the previous layer tends to e with the recorded frequency
+ * table[p][e] / sum_e' table[p][e']; the tendencies of all tokens of all batches are added up
+ * (tokens enter only through counts_prev[p], the number of assignments to p), in fp64, previous
+ * experts in increasing index.  Rows never observed contribute nothing.  The K best by
+ * (score desc, index asc) with a positive score are returned; *n_out <= K.
+ */
+void ko_corr_predict(const int64_t *table, const int32_t *counts_prev, int E, int K,
+                     double *score, int32_t *experts, int32_t *n_out) {
+    for (int e = 0; e < E; ++e) score[e] = 0.0;
+    for (int p = 0; p < E; ++p) {
+        if (counts_prev[p] <= 0) continue;
+        int64_t row = 0;
+        for (int e = 0; e < E; ++e) row += table[(size_t)p * E + e];
+        if (row <= 0) continue;
+        for (int e = 0; e < E; ++e) {
+            const double freq = (double)table[(size_t)p * E + e] / (double)row;
+            score[e] = score[e] + (double)counts_prev[p] * freq;
+        }
+    }
+    int n = 0;
+    for (int r = 0; r < K && r < E; ++r) {
+        int best = -1;
+        for (int e = 0; e < E; ++e) {
+            int taken = 0;
+            for (int q = 0; q < n; ++q) taken |= (experts[q] == e);
+            if (taken || !(score[e] > 0.0)) continue;
+            if (best < 0 || score[e] > score[best]) best = e; /* first index wins ties */
+        }
+        if (best < 0) break;
+        experts[n++] = best;
+    }
+    *n_out = n;
+}
+

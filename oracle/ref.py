@@ -205,3 +205,26 @@ def moe_layer(x, wg, w1, w3, w2, k: int, batch_offsets, dtype: str, n_shared: in
     if with_output:
         y = moe_forward(x, idx, w, w1, w3, w2, E, n_shared, tokens)
     return LayerRef(logits, idx, w, disp, y, None if tokens is None else _i32(tokens))
+
+
+def corr_update(table: np.ndarray, idx_prev, idx_cur) -> np.ndarray:
+    """Add one layer transition of a batch group to an [E, E] int64 correlation table (in place)."""
+    ip, ic = _i32(idx_prev), _i32(idx_cur)
+    assert ip.shape == ic.shape and table.dtype == np.int64 and table.flags.c_contiguous
+    N, k = ip.shape
+    lib().ko_corr_update(_p(ip, C.c_int32), _p(ic, C.c_int32), N, k, table.shape[0],
+                         _p(table, C.c_int64))
+    return table
+
+
+def corr_predict(table: np.ndarray, counts_prev, K: int):
+    """(experts to prefetch, fp64 scores) for the next layer from the previous layer's counts."""
+    E = table.shape[0]
+    cp = _i32(counts_prev)
+    score = np.zeros(E, dtype=np.float64)
+    experts = np.full(max(1, K), -1, dtype=np.int32)
+    n = C.c_int32(0)
+    lib().ko_corr_predict(_p(np.ascontiguousarray(table), C.c_int64), _p(cp, C.c_int32), E, K,
+                          _p(score, C.c_double), _p(experts, C.c_int32), C.byref(n))
+    return experts[:n.value].copy(), score
+
