@@ -112,17 +112,41 @@ def bench_streamed(w, args):
     ys = [torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev) for _ in xs]
     bo = [int(v) for v in w.batch_offsets]
     K = args.prefetch if args.prefetch >= 0 else w.top_k
-    state = {"hot": []}
+    use_corr = args.prefetch_policy == "corr"
+    if use_corr:
+        # table warm-up (the paper's pre-run): route other batch groups of the same model through
+        # the stack; no experts are moved or computed.  The table is then frozen, so that the
+        # accuracy below is measured on a batch group it has never seen.
+        ctx.corr_enable(1)
+        with torch.cuda.stream(compute):
+            for grp in range(8):
+                ww, nz = I.scaled(w, token_seed=1000 + grp), None
+                for l in range(w.n_layers):
+                    dl, nz = I.gen_layer(ww, l, nz, with_experts=False)
+                    ctx.route(l, dl.x.to(dev), bo)
+                ctx.route_wait()
+        ctx.corr_enable(2)
+    acc = {"predicted": 0, "in_true_topk": 0, "activated": 0}
+    guess = {}
 
     def one_pass():
         n_active = []
         for l in range(w.n_layers):
             ctx.route(l, xs[l], bo)
             counts, order, na = ctx.route_wait()
+            if l in guess and guess[l]:                                  # score the guess made for l
+                true_top = set(np.argsort(-np.asarray(counts), kind="stable")[:len(guess[l])].tolist())
+                acc["predicted"] += len(guess[l])
+                acc["in_true_topk"] += sum(1 for e in guess[l] if e in true_top)
+                acc["activated"] += sum(1 for e in guess[l] if counts[e] > 0)
             ctx.stream_experts(l, order[:na], B.MOE_ON_DEMAND)          # what the gate selected
             nxt = (l + 1) % w.n_layers
-            hot = list(np.argsort(-np.asarray(counts), kind="stable")[:K])
-            if K > 0:
+            if use_corr and nxt >= 1:
+                hot = ctx.corr_predict(nxt, K) if K > 0 else []
+            else:                                                        # previous layer's busiest
+                hot = list(np.argsort(-np.asarray(counts), kind="stable")[:K])
+            guess[nxt] = [int(e) for e in hot]
+            if hot:
                 ctx.stream_experts(nxt, hot, B.MOE_PREFETCH)            # guess for the next layer
             ctx.layer_forward(l, xs[l], ys[l])
             n_active.append(na)
@@ -133,6 +157,7 @@ def bench_streamed(w, args):
             one_pass()
     torch.cuda.synchronize()
     ctx.reset_stats()
+    acc.update(predicted=0, in_true_topk=0, activated=0)
     steps = args.steps if args.steps <= 20 else 5
     with torch.cuda.stream(compute):
         torch.cuda.synchronize()
@@ -151,7 +176,8 @@ def bench_streamed(w, args):
         "config": {"workload": w.name, "d_model": w.d_model, "d_ff": w.d_ff, "n_experts": w.n_experts,
                    "top_k": w.top_k, "n_shared": w.n_shared, "n_layers": w.n_layers,
                    "tokens": w.n_tokens, "n_batches": w.n_batches, "window_layers": w.window_layers,
-                   "prefetch_per_layer": K, "experts": "pinned host memory",
+                   "prefetch_per_layer": K, "prefetch_policy": args.prefetch_policy,
+                   "experts": "pinned host memory",
                    "n_active_per_layer": n_active},
         "token_layers_per_s": w.n_tokens * w.n_layers * steps / wall,
         "host_link": {"achieved_GBps": gbs, "measured_peak_GBps": link_peak, "nominal_peak_GBps": 64.0,
@@ -160,6 +186,9 @@ def bench_streamed(w, args):
                       "bytes_h2d_per_step": st["bytes_h2d"] / steps, "copies_per_step": st["n_copies"] / steps,
                       "prefetch_hits_per_step": st["n_prefetch_hits"] / steps,
                       "prefetch_unused_per_step": st["n_prefetch_unused"] / steps},
+        "prefetch": {"predicted": acc["predicted"],
+                     "hot_accuracy": acc["in_true_topk"] / max(1, acc["predicted"]),
+                     "activated_fraction": acc["activated"] / max(1, acc["predicted"])},
         "setup_s": t_setup,
     }
     ctx.close()
@@ -177,6 +206,9 @@ def main():
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
     ap.add_argument("--prefetch", type=int, default=-1,
                     help="streamed stacks: experts prefetched per layer (-1 = top_k)")
+    ap.add_argument("--prefetch-policy", choices=["prev", "corr"], default="prev",
+                    help="streamed stacks: prefetch the previous layer's busiest experts (prev) or "
+                         "the correlation table's prediction (corr, warmed up on other batch groups)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel before the "
                          "timed region, so that a counter run has a kernel of known traffic")

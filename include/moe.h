@@ -211,6 +211,37 @@ moe_status moe_reset_stats(moe_ctx* ctx);
 moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant);
 
 /*
+ * Correlation-aware expert prefetcher, path length 1 (paper Section 6.2).  Per layer the library
+ * keeps a table T[layer][p][e]: how often a token that activated expert p in layer - 1 activated
+ * expert e in this layer (every pair of a previous and a current top-k slot counts once).
+ *
+ * moe_corr_enable(mode): 0 = off, 1 = learn and predict, 2 = predict from the table as it is.
+ * While learning, every moe_route(layer) that follows a moe_route(layer - 1)
+ * of the same number of tokens adds the transitions of the batch group to T[layer] (one small
+ * kernel with integer atomics on the compute stream) and refreshes the host mirror of T[layer].
+ * The table lives in the caller's workspace and is zeroed by moe_create and moe_corr_reset
+ * (both stream-ordered on the compute stream).
+ *
+ * moe_corr_predict(layer, K): the K experts of `layer` that the batch group routed last (which
+ * must have been routed through layer - 1) tends to: score[e] = sum over previous experts p of
+ * counts[p] * T[layer][p][e] / rowsum(T[layer][p]) in fp64, p ascending; best K by (score desc,
+ * index asc), zero scores never returned.  Host only; blocks until the last moe_route has
+ * delivered its counts.  experts_out_host has room for K ids; *n_out <= K.
+ * Errors: MOE_ERR_STATE (not enabled, or the last routed layer is not layer - 1).
+ *
+ * moe_corr_table: copies the host mirror of T[layer] (E*E int32, row = previous expert).
+ * moe_corr_rank: the ranking alone, pure host function (no context): table [E][E] int32, the
+ * previous layer's tokens per expert; score_out (E doubles) may be null.
+ */
+moe_status moe_corr_enable(moe_ctx* ctx, int32_t mode);
+moe_status moe_corr_reset(moe_ctx* ctx);
+moe_status moe_corr_predict(moe_ctx* ctx, int32_t layer, int32_t K, int32_t* experts_out_host,
+                            int32_t* n_out);
+moe_status moe_corr_table(moe_ctx* ctx, int32_t layer, int32_t* table_out_host);
+moe_status moe_corr_rank(const int32_t* table_host, const int32_t* counts_prev_host, int32_t E,
+                         int32_t K, int32_t* experts_out_host, int32_t* n_out, double* score_out);
+
+/*
  * Per-kernel timing of the last moe_route + moe_layer_forward pair (all-resident layers only),
  * taken with HIP events on the compute stream between the launches.  For the fp32 path up_ms is
  * 0 and down_ms covers both expert kernels.  moe_get_profile blocks until that forward is done.

@@ -27,7 +27,8 @@ STATUS_NAMES = {0: "MOE_OK", 1: "MOE_ERR_INVALID_ARG", 2: "MOE_ERR_SHAPE", 3: "M
 EXPORTS = ["moe_plan", "moe_plan_batches", "moe_create", "moe_destroy", "moe_set_gate",
            "moe_set_expert", "moe_route", "moe_route_wait", "moe_stream_experts",
            "moe_layer_forward", "moe_get_stats", "moe_reset_stats", "moe_set_tuning",
-           "moe_set_profiling", "moe_get_profile", "moe_last_error"]
+           "moe_set_profiling", "moe_get_profile", "moe_last_error", "moe_corr_enable",
+           "moe_corr_reset", "moe_corr_predict", "moe_corr_table", "moe_corr_rank"]
 
 
 class MoeConfig(C.Structure):
@@ -89,6 +90,11 @@ def load_library():
     lib.moe_reset_stats.argtypes = [vp]
     lib.moe_set_tuning.argtypes = [vp, i32, i32, i32]
     lib.moe_set_profiling.argtypes = [vp, i32]
+    lib.moe_corr_enable.argtypes = [vp, i32]
+    lib.moe_corr_reset.argtypes = [vp]
+    lib.moe_corr_predict.argtypes = [vp, i32, i32, P(i32), P(i32)]
+    lib.moe_corr_table.argtypes = [vp, i32, P(i32)]
+    lib.moe_corr_rank.argtypes = [P(i32), P(i32), i32, i32, P(i32), P(i32), P(dbl)]
     lib.moe_get_profile.argtypes = [vp, P(MoeProfile)]
     lib.moe_last_error.argtypes = [vp]
     lib.moe_last_error.restype = C.c_char_p
@@ -97,6 +103,19 @@ def load_library():
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
+
+
+def corr_rank(table, counts_prev, K: int):
+    """Pure host ranking of the correlation prefetcher: (expert ids, fp64 scores)."""
+    E = len(counts_prev)
+    flat = [int(v) for row in table for v in row]
+    t = (C.c_int32 * (E * E))(*flat)
+    cp = (C.c_int32 * E)(*[int(v) for v in counts_prev])
+    out = (C.c_int32 * max(1, K))()
+    n = C.c_int32(0)
+    score = (C.c_double * E)()
+    _check(load_library().moe_corr_rank(t, cp, E, K, out, C.byref(n), score))
+    return [int(out[i]) for i in range(n.value)], [float(v) for v in score]
 
 
 def _check(status: int, ctx=None):
@@ -239,6 +258,25 @@ class MoeContext:
         p = MoeProfile()
         _check(self.lib.moe_get_profile(self.h, C.byref(p)), self.h)
         return {n: float(getattr(p, n)) for n, _ in MoeProfile._fields_}
+
+    def corr_enable(self, mode: int = 1):
+        """0 = off, 1 = learn and predict, 2 = predict from the table as it is."""
+        _check(self.lib.moe_corr_enable(self.h, int(mode)), self.h)
+
+    def corr_reset(self):
+        _check(self.lib.moe_corr_reset(self.h), self.h)
+
+    def corr_predict(self, layer: int, K: int) -> list:
+        out = (C.c_int32 * max(1, K))()
+        n = C.c_int32(0)
+        _check(self.lib.moe_corr_predict(self.h, layer, K, out, C.byref(n)), self.h)
+        return [int(out[i]) for i in range(n.value)]
+
+    def corr_table(self, layer: int) -> list:
+        E = self.cfg.n_experts
+        out = (C.c_int32 * (E * E))()
+        _check(self.lib.moe_corr_table(self.h, layer, out), self.h)
+        return [[int(out[p * E + e]) for e in range(E)] for p in range(E)]
 
     def close(self):
         if getattr(self, "h", None):

@@ -260,7 +260,29 @@ __global__ __launch_bounds__(kThreads) void plan_fused_kernel(const int32_t* __r
     rank_body(idx, A, s.E, p, 0, seg, off, nullptr);
 }
 
+// Correlation table update (paper Section 6.2, path length 1): one thread per token adds its
+// k x k (previous expert, current expert) pairs to the layer's table.  Integer atomics: the
+// result does not depend on the order.
+__global__ __launch_bounds__(kThreads) void corr_update_kernel(const int32_t* __restrict__ idx_prev,
+                                                               const int32_t* __restrict__ idx_cur,
+                                                               int N, int k, int E,
+                                                               int32_t* __restrict__ table) {
+    const int t = blockIdx.x * kThreads + threadIdx.x;
+    if (t >= N) return;
+    for (int a = 0; a < k; ++a) {
+        const int p = idx_prev[(size_t)t * k + a];
+        for (int b = 0; b < k; ++b) atomicAdd(&table[(size_t)p * E + idx_cur[(size_t)t * k + b]], 1);
+    }
+}
+
 }  // namespace
+
+void launch_corr_update(hipStream_t st, const int32_t* idx_prev, const int32_t* idx_cur, int N, int k,
+                        int E, int32_t* table) {
+    if (N <= 0) return;
+    hipLaunchKernelGGL(corr_update_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
+                       idx_prev, idx_cur, N, k, E, table);
+}
 
 void launch_plan(hipStream_t st, const Shape& s, const BatchOffsets& bo, const PlanPtrs& p,
                  int max_tiles) {

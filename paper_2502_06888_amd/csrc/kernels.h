@@ -94,6 +94,8 @@ struct FfnArgs {
 };
 void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a);
 void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a);
+void launch_corr_update(hipStream_t st, const int32_t* idx_prev, const int32_t* idx_cur, int N, int k,
+                        int E, int32_t* table);
 int ffn_configure();  // one-time function attributes (dynamic LDS); returns hipError_t
 
 // Y[t] = sum_j w[t,j] * sum_s O[s][row(t,j)] + shared rows; one rounding to the output type.

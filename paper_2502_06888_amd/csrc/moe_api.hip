@@ -38,6 +38,8 @@ struct Layout {
         exp_ntiles, blk_expert, mail, wtab, xp, h, o;
     int64_t o_split_stride = 0;  // elements
     int64_t h_plane_units = 0;   // 16-byte units between the two bf16 planes of H
+    int64_t corr_table = 0;      // int32 [n_layers][E][E]
+    int64_t prev_idx = 0;        // top-k ids of the previously routed layer
     int64_t total = 0;
 };
 
@@ -117,6 +119,8 @@ void compute_layout(const moe_config& c, Layout& L) {
     }
     L.o_split_stride = h_rows * d;
     L.o = take((int64_t)L.split_cap * L.o_split_stride * 4);
+    L.corr_table = take((int64_t)c.n_layers * E * E * 4);
+    L.prev_idx = take(L.A * 4);
     L.total = off;
 }
 
@@ -169,6 +173,11 @@ struct moe_ctx {
     int split_k_user = 0;
     int variant = 0;   // kernel shape selector of the bf16 FFN (0 = default)
     int h_planes = 2;  // bf16 path: carry H as value + rounding remainder (2) or as plain bf16 (1)
+    // correlation-aware prefetcher
+    bool corr_on = false;      // predictions allowed
+    bool corr_learn = false;   // moe_route adds transitions to the table
+    int32_t* corr_host = nullptr;  // pinned host mirror, [n_layers][E][E]
+    int prev_idx_layer = -1, prev_idx_tokens = -1;
     moe_stats stats{};
     bool profiling = false;
     hipEvent_t pev[8] = {};  // router start, router end, plan end, fwd start, gather, up, down, combine
@@ -463,10 +472,15 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
     e = hipMemsetAsync(w + L.meta, 0, 64, c->compute);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
+    e = hipMemsetAsync(w + L.corr_table, 0, (size_t)cfg->n_layers * E * E * 4, c->compute);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
     e = hipStreamSynchronize(c->compute);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipStreamSynchronize", e);
     e = hipHostMalloc((void**)&c->mailbox, (size_t)(2 * E + 1) * 4, hipHostMallocDefault);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipHostMalloc", e);
+    e = hipHostMalloc((void**)&c->corr_host, (size_t)cfg->n_layers * E * E * 4, hipHostMallocDefault);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipHostMalloc", e);
+    memset(c->corr_host, 0, (size_t)cfg->n_layers * E * E * 4);
     e = hipEventCreateWithFlags(&c->route_ev, hipEventDisableTiming);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipEventCreate", e);
     for (auto& ev : c->pev) {
@@ -502,6 +516,7 @@ moe_status moe_destroy(moe_ctx* ctx) {
     for (auto& ev : ctx->pev)
         if (ev) (void)hipEventDestroy(ev);
     if (ctx->mailbox) (void)hipHostFree(ctx->mailbox);
+    if (ctx->corr_host) (void)hipHostFree(ctx->corr_host);
     delete ctx;
     return MOE_OK;
 }
@@ -604,6 +619,19 @@ moe_status moe_route(moe_ctx* ctx, int32_t layer, const void* x_dev,
     HIP_TRY(ctx, out(perm_dev, ctx->plan.perm, A * 4));
     HIP_TRY(ctx, out(inv_perm_dev, ctx->plan.inv_perm, A * 4));
     HIP_TRY(ctx, out(exec_order_dev, ctx->plan.exec_order, (size_t)E * 4));
+    if (ctx->corr_learn) {
+        int32_t* prev = (int32_t*)(ctx->ws + ctx->L.prev_idx);
+        if (layer > 0 && ctx->prev_idx_layer == layer - 1 && ctx->prev_idx_tokens == N && N > 0) {
+            int32_t* tab = (int32_t*)(ctx->ws + ctx->L.corr_table) + (size_t)layer * E * E;
+            launch_corr_update(st, prev, ctx->plan.topk_idx, N, k, E, tab);
+            HIP_TRY(ctx, hipGetLastError());
+            HIP_TRY(ctx, hipMemcpyAsync(ctx->corr_host + (size_t)layer * E * E, tab, (size_t)E * E * 4,
+                                        hipMemcpyDeviceToHost, st));
+        }
+        if (A > 0) HIP_TRY(ctx, hipMemcpyAsync(prev, ctx->plan.topk_idx, A * 4, hipMemcpyDeviceToDevice, st));
+        ctx->prev_idx_layer = layer;
+        ctx->prev_idx_tokens = N;
+    }
     HIP_TRY(ctx, hipMemcpyAsync(ctx->mailbox, ctx->plan.mail, (size_t)(2 * E + 1) * 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipEventRecord(ctx->route_ev, st));
     ctx->routed_layer = layer;
@@ -835,6 +863,88 @@ moe_status moe_get_profile(moe_ctx* ctx, moe_profile* out) {
         HIP_TRY(ctx, hipEventElapsedTime(dst[i], ctx->pev[i], ctx->pev[i + 1]));
     }
     return MOE_OK;
+}
+
+moe_status moe_corr_rank(const int32_t* table_host, const int32_t* counts_prev_host, int32_t E,
+                         int32_t K, int32_t* experts_out_host, int32_t* n_out, double* score_out) {
+    if (!table_host || !counts_prev_host || !n_out || (K > 0 && !experts_out_host))
+        return fail(nullptr, MOE_ERR_INVALID_ARG, "null argument");
+    if (E < 1 || E > MOE_MAX_EXPERTS || K < 0) return fail(nullptr, MOE_ERR_INVALID_ARG, "E or K out of range");
+    std::vector<double> score((size_t)E, 0.0);
+    for (int p = 0; p < E; ++p) {  // previous experts in increasing index: fixed fp64 summation order
+        const int32_t n = counts_prev_host[p];
+        if (n <= 0) continue;
+        const int32_t* row = table_host + (size_t)p * E;
+        int64_t total = 0;
+        for (int e = 0; e < E; ++e) total += row[e];
+        if (total <= 0) continue;  // never observed: says nothing
+        const double dn = (double)n, dt = (double)total;
+        for (int e = 0; e < E; ++e) {
+            const double freq = (double)row[e] / dt;
+            const double term = dn * freq;
+            score[e] = score[e] + term;
+        }
+    }
+    std::vector<char> taken((size_t)E, 0);
+    int n = 0;
+    for (; n < K && n < E; ++n) {
+        int best = -1;
+        for (int e = 0; e < E; ++e)
+            if (!taken[e] && score[e] > 0.0 && (best < 0 || score[e] > score[best])) best = e;
+        if (best < 0) break;
+        taken[best] = 1;
+        experts_out_host[n] = best;
+    }
+    *n_out = n;
+    if (score_out) memcpy(score_out, score.data(), (size_t)E * sizeof(double));
+    return MOE_OK;
+}
+
+moe_status moe_corr_enable(moe_ctx* ctx, int32_t on) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (on < 0 || on > 2) return fail(ctx, MOE_ERR_INVALID_ARG, "mode must be 0, 1 or 2");
+    ctx->corr_on = on != 0;
+    ctx->corr_learn = on == 1;
+    ctx->prev_idx_layer = -1;
+    ctx->prev_idx_tokens = -1;
+    return MOE_OK;
+}
+
+moe_status moe_corr_reset(moe_ctx* ctx) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    const size_t bytes = (size_t)ctx->cfg.n_layers * ctx->cfg.n_experts * ctx->cfg.n_experts * 4;
+    HIP_TRY(ctx, hipMemsetAsync(ctx->ws + ctx->L.corr_table, 0, bytes, ctx->compute));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));  // no mirror refresh may still be in flight
+    memset(ctx->corr_host, 0, bytes);
+    ctx->prev_idx_layer = -1;
+    ctx->prev_idx_tokens = -1;
+    return MOE_OK;
+}
+
+moe_status moe_corr_table(moe_ctx* ctx, int32_t layer, int32_t* table_out_host) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (!table_out_host) return fail(ctx, MOE_ERR_INVALID_ARG, "output is null");
+    if (ctx->route_pending) {
+        moe_status st = wait_route(ctx);  // mirror refreshes are ordered before the route event
+        if (st != MOE_OK) return st;
+    }
+    const size_t EE = (size_t)ctx->cfg.n_experts * ctx->cfg.n_experts;
+    memcpy(table_out_host, ctx->corr_host + (size_t)layer * EE, EE * 4);
+    return MOE_OK;
+}
+
+moe_status moe_corr_predict(moe_ctx* ctx, int32_t layer, int32_t K, int32_t* experts_out_host,
+                            int32_t* n_out) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (layer < 1 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d has no previous expert layer", layer);
+    if (!ctx->corr_on) return fail(ctx, MOE_ERR_STATE, "correlation table is not enabled");
+    if (ctx->routed_layer != layer - 1) return fail(ctx, MOE_ERR_STATE, "prediction for layer %d needs the routing of layer %d, the last moe_route was for layer %d", layer, layer - 1, ctx->routed_layer);
+    moe_status st = wait_route(ctx);
+    if (st != MOE_OK) return st;
+    const size_t EE = (size_t)ctx->cfg.n_experts * ctx->cfg.n_experts;
+    return moe_corr_rank(ctx->corr_host + (size_t)layer * EE, ctx->h_counts.data(), ctx->cfg.n_experts, K,
+                         experts_out_host, n_out, nullptr);
 }
 
 moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant) {

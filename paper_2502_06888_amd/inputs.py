@@ -52,6 +52,7 @@ class Workload:
     zipf_s: float = 0.0                      # >0: skewed router targets
     corr: float = 0.0                        # layer-to-layer routing correlation
     seed: int = 0
+    token_seed: int = -1      # >= 0: tokens (activations, routing noise) drawn from this seed, weights from `seed`
     w_std: float = 0.02
 
     @property
@@ -154,7 +155,8 @@ def gen_expert(w: Workload, layer: int, e: int):
 
 
 def gen_x_gaussian(w: Workload, layer: int = 0) -> torch.Tensor:
-    return to_storage(_normal(w.seed, layer, TID_X, (w.n_tokens, w.d_model), 1.0), w.dtype)
+    return to_storage(_normal(w.token_seed if w.token_seed >= 0 else w.seed, layer, TID_X,
+                              (w.n_tokens, w.d_model), 1.0), w.dtype)
 
 
 def zipf_target_logits(w: Workload, layer: int, prev_noise: Optional[np.ndarray]):
@@ -170,6 +172,8 @@ def zipf_target_logits(w: Workload, layer: int, prev_noise: Optional[np.ndarray]
     E, N = w.n_experts, w.n_tokens
     g = np.random.Generator(np.random.PCG64(_sub_seed(w.seed, layer, 900)))
     rank_to_expert = g.permutation(E)
+    if w.token_seed >= 0:  # another batch group for the same model: same popularity map, new tokens
+        g = np.random.Generator(np.random.PCG64(_sub_seed(w.token_seed, layer, 901)))
     u = g.random((N, E))
     noise = -np.log(-np.log(np.clip(u, 1e-12, 1.0 - 1e-12)))
     if prev_noise is not None and w.corr > 0:
@@ -188,7 +192,8 @@ def gen_x_for_targets(w: Workload, layer: int, wg: torch.Tensor, targets: np.nda
     x = z - Wg^T (Wg Wg^T)^-1 (Wg z - target): the minimum-norm correction of a
     Gaussian draw z onto the affine set {x : Wg x = target}.
     """
-    z = _normal(w.seed, layer, TID_X, (w.n_tokens, w.d_model), 1.0).astype(np.float64)
+    z = _normal(w.token_seed if w.token_seed >= 0 else w.seed, layer, TID_X,
+                (w.n_tokens, w.d_model), 1.0).astype(np.float64)
     g = as_f32(wg).astype(np.float64)
     resid = z @ g.T - targets                       # [N, E]
     corr = np.linalg.solve(g @ g.T, resid.T).T @ g  # [N, d]

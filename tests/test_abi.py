@@ -126,3 +126,24 @@ def test_plan_batches_errors():
         B.moe_plan_batches(-1.0, 0.0, 0.0, [], 0.0, 1.0, 0.0, 0)
     lib = B.load_library()
     assert lib.moe_plan_batches(1.0, 0.0, 0.0, None, 2, 0.0, 1.0, 0.0, 0, C.byref(C.c_int32())) == B.MOE_ERR_INVALID_ARG
+
+
+def test_corr_rank_matches_oracle_on_cpu():
+    """The prefetcher's ranking is host code: same scores (bit for bit, same fp64 order) and the
+    same expert lists as the oracle, on random tables with unseen rows and tied scores."""
+    import numpy as np
+    from oracle import ref
+    rng = np.random.default_rng(5)
+    for E, K in [(8, 2), (64, 6), (5, 5), (16, 1)]:
+        for trial in range(4):
+            t = rng.integers(0, 40, size=(E, E)).astype(np.int64)
+            t[rng.integers(0, E)] = 0                      # a previous expert never observed
+            if trial == 3:
+                t[:] = 3                                   # all scores equal: index order decides
+            counts = rng.integers(0, 25, size=E).astype(np.int32)
+            want_e, want_s = ref.corr_predict(t, counts, K)
+            got_e, got_s = B.corr_rank(t.tolist(), counts.tolist(), K)
+            assert got_e == want_e.tolist()
+            assert np.array_equal(np.asarray(got_s).view(np.uint64), want_s.view(np.uint64))
+    got_e, _ = B.corr_rank(np.zeros((4, 4), dtype=int).tolist(), [1, 2, 3, 4], 2)
+    assert got_e == []                                     # empty table: nothing to prefetch
