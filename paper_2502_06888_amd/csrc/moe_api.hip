@@ -24,6 +24,8 @@ using namespace kmoe;
 
 namespace {
 constexpr int kTileRows = kRowBlk * kTileBlks;
+// experts smaller than this (bytes) are copied over two alternating streams
+constexpr int64_t kSecondCopyStreamBelow = 64ll << 20;
 
 
 thread_local std::string g_last_error;
@@ -134,6 +136,7 @@ struct Slot {
     hipEvent_t ready = nullptr;  // copy landed (recorded on the copy stream)
     hipEvent_t done = nullptr;   // last reader finished (recorded on the compute stream)
     bool done_pending = false;
+    bool ready_recorded = false;  // a copy into this slot has been issued at some time
 };
 
 struct LayerState {
@@ -153,6 +156,8 @@ struct moe_ctx {
     moe_config cfg{};
     Layout L;
     hipStream_t compute = nullptr, copy = nullptr;
+    hipStream_t copy2 = nullptr;  // library-owned second copy stream (small experts only)
+    uint64_t copies_issued = 0;
     uint8_t* ws = nullptr;
     uint8_t* window = nullptr;
     PlanPtrs plan{};
@@ -311,13 +316,21 @@ moe_status stream_one(moe_ctx* ctx, int layer, int e, bool prefetch) {
         }
     if (pick < 0) return fail(ctx, MOE_ERR_OOM, "no free window slot for layer %d expert %d", layer, e);
     Slot& s = ctx->slots[pick];
+    // Small experts alternate between two copy streams: the fixed start-up gap of one copy then
+    // hides behind the other stream's transfer and the link stays busy.  Every slot still has
+    // its own ready event, so nothing depends on the order in which the copies land.
+    hipStream_t cs = ctx->copy;
+    if (ctx->copy2 && (ctx->copies_issued++ & 1)) cs = ctx->copy2;
     if (s.done_pending) {  // the slot's previous readers must finish before it is overwritten
-        HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, s.done, 0));
+        HIP_TRY(ctx, hipStreamWaitEvent(cs, s.done, 0));
         s.done_pending = false;
     }
-    HIP_TRY(ctx, hipMemcpyAsync(s.ptr, ls.host[e], (size_t)ctx->L.expert_bytes, hipMemcpyHostToDevice,
-                                ctx->copy));
-    HIP_TRY(ctx, hipEventRecord(s.ready, ctx->copy));
+    // ... and so must its previous copy, which may have gone over the other copy stream (a
+    // dropped prefetch guess frees a slot without any reader)
+    if (ctx->copy2 && s.ready_recorded) HIP_TRY(ctx, hipStreamWaitEvent(cs, s.ready, 0));
+    HIP_TRY(ctx, hipMemcpyAsync(s.ptr, ls.host[e], (size_t)ctx->L.expert_bytes, hipMemcpyHostToDevice, cs));
+    HIP_TRY(ctx, hipEventRecord(s.ready, cs));
+    s.ready_recorded = true;
     s.layer = layer;
     s.expert = e;
     s.state = SLOT_LOADED;
@@ -487,6 +500,10 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
         e = hipEventCreate(&ev);
         if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipEventCreate", e);
     }
+    if (n_slots > 0 && L.expert_bytes < kSecondCopyStreamBelow) {
+        e = hipStreamCreateWithFlags(&c->copy2, hipStreamNonBlocking);  // default priority
+        if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipStreamCreateWithFlags", e);
+    }
     c->slots.resize(n_slots);
     for (int i = 0; i < n_slots; ++i) {
         Slot& s = c->slots[i];
@@ -508,6 +525,10 @@ moe_status moe_destroy(moe_ctx* ctx) {
     if (!ctx) return MOE_OK;
     if (ctx->compute || true) (void)hipStreamSynchronize(ctx->compute);
     if (ctx->copy != ctx->compute) (void)hipStreamSynchronize(ctx->copy);
+    if (ctx->copy2) {
+        (void)hipStreamSynchronize(ctx->copy2);
+        (void)hipStreamDestroy(ctx->copy2);
+    }
     for (Slot& s : ctx->slots) {
         if (s.ready) (void)hipEventDestroy(s.ready);
         if (s.done) (void)hipEventDestroy(s.done);
