@@ -68,6 +68,52 @@ def recorded_traffic(workload: str, kernel: str):
     return None
 
 
+def planner_report(ctx, w, xs, ys, K, compute, torch, B):
+    """Measurement stage + constraint solving of the planner on layer 0, then a sweep over the
+    number of batches per group n: measured time of the layer against the model
+    max(transfer time of the activated experts, compute time of the group)."""
+    tpb = w.batch_tokens[0]
+    rows = []
+    for n in [b for b in (1, 2, 4, 8, 16, 32) if b <= w.n_batches]:
+        N = n * tpb
+        bo = [i * tpb for i in range(n + 1)]
+        x, y = xs[0][:N], ys[0][:N]
+        with torch.cuda.stream(compute):
+            m = ctx.measure(0, x, bo, y, reps=3)
+            t_comp = (m["t_c_gate_group_s"] + m["t_c_gather_s"] + sum(m["t_c_expert_s"]) + m["t_c_combine_s"])
+            t_io = m["n_active"] * m["t_io_expert_s"]
+            # the layer as the pipeline runs it: on-demand transfers, compute as they land
+            reps, t0 = 3, None
+            for r in range(reps + 1):
+                if r == 1:
+                    compute.synchronize(); t0 = time.perf_counter()
+                ctx.route(0, x, bo)
+                counts, order, na = ctx.route_wait()
+                ctx.stream_experts(0, order[:na], B.MOE_ON_DEMAND)
+                ctx.layer_forward(0, x, y)
+            compute.synchronize()
+            t_layer = (time.perf_counter() - t0) / reps
+        pred = max(t_io, t_comp)
+        rows.append({"n_batches": n, "tokens": N, "n_active": m["n_active"],
+                     "t_io_expert_ms": m["t_io_expert_s"] * 1e3, "t_gate_group_us": m["t_c_gate_group_s"] * 1e6,
+                     "t_experts_us": sum(m["t_c_expert_s"]) * 1e6,
+                     "t_compute_us": t_comp * 1e6, "t_transfers_ms": t_io * 1e3,
+                     "layer_ms_measured": t_layer * 1e3, "layer_ms_predicted": pred * 1e3,
+                     "compute_bubble_measured": 1.0 - t_comp / t_layer,
+                     "compute_bubble_predicted": 1.0 - t_comp / pred})
+        last = m
+    # smallest n that satisfies the inequality group, from the figures of the largest group:
+    # per-batch gate time, hot experts = the first K in execution order, the rest queued
+    n = rows[-1]["n_batches"]
+    order = last["exec_order"]
+    hot, cold = order[:K], order[K:]
+    t_c_hot = sum(last["t_c_expert_s"][e] for e in hot)
+    t_c_q = [last["t_c_expert_s"][e] for e in cold]
+    n_min = B.moe_plan_batches(0.0, last["t_c_gate_group_s"] / n, t_c_hot, t_c_q, 0.0, 0.0, last["t_io_expert_s"], K)
+    return {"layer": 0, "tokens_per_batch": tpb, "K": K, "n_min": n_min, "sweep": rows,
+            "note": "t_c_A = t_IO_A = t_IO_G = 0: no attention in this build, gate resident"}
+
+
 def measure_link_peak(torch, nbytes: int = 1 << 30, reps: int = 5) -> float:
     """Best host->device rate of one large copy from pinned memory on this machine, GB/s."""
     src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
@@ -152,6 +198,9 @@ def bench_streamed(w, args):
             n_active.append(na)
         return n_active
 
+    plan_report = None
+    if args.plan:
+        plan_report = planner_report(ctx, w, xs, ys, K, compute, torch, B)
     with torch.cuda.stream(compute):
         for _ in range(max(1, args.warmup if args.warmup < 5 else 1)):
             one_pass()
@@ -191,6 +240,8 @@ def bench_streamed(w, args):
                      "activated_fraction": acc["activated"] / max(1, acc["predicted"])},
         "setup_s": t_setup,
     }
+    if plan_report is not None:
+        out["planner"] = plan_report
     ctx.close()
     return out
 
@@ -209,6 +260,9 @@ def main():
     ap.add_argument("--prefetch-policy", choices=["prev", "corr"], default="prev",
                     help="streamed stacks: prefetch the previous layer's busiest experts (prev) or "
                          "the correlation table's prediction (corr, warmed up on other batch groups)")
+    ap.add_argument("--plan", action="store_true",
+                    help="streamed stacks: run the planner's measurement stage on layer 0, solve the "
+                         "overlap inequalities for n, and sweep the number of batches per group")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel before the "
                          "timed region, so that a counter run has a kernel of known traffic")

@@ -211,6 +211,31 @@ moe_status moe_reset_stats(moe_ctx* ctx);
 moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant);
 
 /*
+ * Measurement stage of the constraint-sensitive planner (paper Section 7: before inference the
+ * computation and transfer times of the layer's parts are measured on the machine at hand and
+ * then applied to the inequality group, see moe_plan_batches).  Runs on the given batch group:
+ * the gate + dispatch plan, `reps` times; one expert's transfer from pinned host memory into a
+ * window slot, `reps` times (0 when the layer has no host-resident expert); then gather, the two
+ * expert kernels of every activated routed expert on its own tokens, one expert at a time in
+ * execution order, and the combine.  Blocks until done; leaves no expert in the window and the
+ * context as after a moe_route of this group.  y_dev receives the layer output of the group
+ * only if every expert of the layer is resident (otherwise the timed kernels run on a stand-in
+ * blob and y_dev is scratch).  All times in seconds, device time between HIP events.
+ */
+typedef struct {
+    double t_c_gate_group_s;                /* router + plan for the whole group */
+    double t_io_expert_s;                   /* one expert blob over the host link */
+    double t_c_gather_s, t_c_combine_s;     /* once per group */
+    double t_c_expert_s[MOE_MAX_EXPERTS];   /* up + down of expert e over the group's tokens; 0 = not activated */
+    int32_t n_active;
+    int32_t exec_order[MOE_MAX_EXPERTS];    /* activated experts, execution order */
+    int32_t counts[MOE_MAX_EXPERTS];        /* tokens per expert */
+} moe_measured;
+moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
+                       const int32_t* batch_offsets_host, int32_t n_batches, void* y_dev,
+                       int32_t reps, moe_measured* out);
+
+/*
  * Correlation-aware expert prefetcher, path length 1 (paper Section 6.2).  Per layer the library
  * keeps a table T[layer][p][e]: how often a token that activated expert p in layer - 1 activated
  * expert e in this layer (every pair of a previous and a current top-k slot counts once).

@@ -28,13 +28,23 @@ EXPORTS = ["moe_plan", "moe_plan_batches", "moe_create", "moe_destroy", "moe_set
            "moe_set_expert", "moe_route", "moe_route_wait", "moe_stream_experts",
            "moe_layer_forward", "moe_get_stats", "moe_reset_stats", "moe_set_tuning",
            "moe_set_profiling", "moe_get_profile", "moe_last_error", "moe_corr_enable",
-           "moe_corr_reset", "moe_corr_predict", "moe_corr_table", "moe_corr_rank"]
+           "moe_corr_reset", "moe_corr_predict", "moe_corr_table", "moe_corr_rank", "moe_measure"]
 
 
 class MoeConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("d_model", "d_ff", "n_experts", "top_k", "n_shared", "n_layers", "window_layers",
                  "max_tokens", "max_batches", "dtype", "renormalize")]
+
+
+MOE_MAX_EXPERTS = 256
+
+
+class MoeMeasured(C.Structure):
+    _fields_ = [("t_c_gate_group_s", C.c_double), ("t_io_expert_s", C.c_double),
+                ("t_c_gather_s", C.c_double), ("t_c_combine_s", C.c_double),
+                ("t_c_expert_s", C.c_double * MOE_MAX_EXPERTS), ("n_active", C.c_int32),
+                ("exec_order", C.c_int32 * MOE_MAX_EXPERTS), ("counts", C.c_int32 * MOE_MAX_EXPERTS)]
 
 
 class MoePlan(C.Structure):
@@ -90,6 +100,7 @@ def load_library():
     lib.moe_reset_stats.argtypes = [vp]
     lib.moe_set_tuning.argtypes = [vp, i32, i32, i32]
     lib.moe_set_profiling.argtypes = [vp, i32]
+    lib.moe_measure.argtypes = [vp, i32, vp, P(i32), i32, vp, i32, P(MoeMeasured)]
     lib.moe_corr_enable.argtypes = [vp, i32]
     lib.moe_corr_reset.argtypes = [vp]
     lib.moe_corr_predict.argtypes = [vp, i32, i32, P(i32), P(i32)]
@@ -258,6 +269,18 @@ class MoeContext:
         p = MoeProfile()
         _check(self.lib.moe_get_profile(self.h, C.byref(p)), self.h)
         return {n: float(getattr(p, n)) for n, _ in MoeProfile._fields_}
+
+    def measure(self, layer: int, x, batch_offsets, y, reps: int = 5) -> dict:
+        bo = (C.c_int32 * len(batch_offsets))(*[int(v) for v in batch_offsets])
+        m = MoeMeasured()
+        _check(self.lib.moe_measure(self.h, layer, x.data_ptr(), bo, len(batch_offsets) - 1,
+                                    y.data_ptr(), reps, C.byref(m)), self.h)
+        E = self.cfg.n_experts
+        return {"t_c_gate_group_s": m.t_c_gate_group_s, "t_io_expert_s": m.t_io_expert_s,
+                "t_c_gather_s": m.t_c_gather_s, "t_c_combine_s": m.t_c_combine_s,
+                "t_c_expert_s": [m.t_c_expert_s[e] for e in range(E)], "n_active": m.n_active,
+                "exec_order": [m.exec_order[i] for i in range(m.n_active)],
+                "counts": [m.counts[e] for e in range(E)]}
 
     def corr_enable(self, mode: int = 1):
         """0 = off, 1 = learn and predict, 2 = predict from the table as it is."""

@@ -886,6 +886,146 @@ moe_status moe_get_profile(moe_ctx* ctx, moe_profile* out) {
     return MOE_OK;
 }
 
+moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
+                       const int32_t* batch_offsets_host, int32_t n_batches, void* y_dev,
+                       int32_t reps, moe_measured* out) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (!out || !y_dev) return fail(ctx, MOE_ERR_INVALID_ARG, "null argument");
+    if (reps < 1 || reps > 1000) return fail(ctx, MOE_ERR_INVALID_ARG, "reps outside [1, 1000]");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (ctx->cfg.dtype != MOE_BF16) return fail(ctx, MOE_ERR_STATE, "measurement covers the bf16 path");
+    memset(out, 0, sizeof *out);
+    const int E = ctx->cfg.n_experts, S = ctx->cfg.n_shared;
+    LayerState& ls = ctx->layers[layer];
+    for (int e = 0; e < E + S; ++e)
+        if (!ls.resident[e] && (e >= E || !ls.host[e]))
+            return fail(ctx, MOE_ERR_STATE, "weights of layer %d expert %d not set", layer, e);
+    hipStream_t st = ctx->compute;
+    std::vector<hipEvent_t> evs;
+    auto mark = [&](hipStream_t on) -> int {
+        hipEvent_t ev = nullptr;
+        if (hipEventCreate(&ev) != hipSuccess) return -1;
+        (void)hipEventRecord(ev, on);
+        evs.push_back(ev);
+        return (int)evs.size() - 1;
+    };
+    auto done = [&](moe_status r) {
+        for (hipEvent_t ev : evs) (void)hipEventDestroy(ev);
+        return r;
+    };
+    auto secs = [&](int a, int b) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, evs[a], evs[b]);
+        return (double)ms * 1e-3;
+    };
+    const bool learn = ctx->corr_learn;  // repeated routing of one group must not feed the table
+    ctx->corr_learn = false;
+    // gate + plan
+    const int g0 = mark(st);
+    moe_status r = MOE_OK;
+    for (int i = 0; i < reps && r == MOE_OK; ++i)
+        r = moe_route(ctx, layer, x_dev, batch_offsets_host, n_batches, nullptr, nullptr, nullptr, nullptr,
+                      nullptr, nullptr, nullptr, nullptr);
+    const int g1 = mark(st);
+    ctx->corr_learn = learn;
+    if (r != MOE_OK) return done(r);
+    r = wait_route(ctx);
+    if (r != MOE_OK) return done(r);
+    const int N = ctx->routed_tokens;
+    out->n_active = ctx->h_nactive;
+    for (int e = 0; e < E; ++e) out->counts[e] = ctx->h_counts[e];
+    for (int i = 0; i < ctx->h_nactive; ++i) out->exec_order[i] = ctx->h_order[i];
+    // one expert over the link, into a free slot that then serves as a stand-in blob
+    const uint8_t* standin = nullptr;
+    int io0 = -1, io1 = -1, slot = -1;
+    int host_e = -1;
+    for (int i = 0; i < ctx->h_nactive && host_e < 0; ++i)
+        if (!ls.resident[ctx->h_order[i]]) host_e = ctx->h_order[i];
+    if (host_e >= 0) {
+        for (size_t i = 0; i < ctx->slots.size() && slot < 0; ++i)
+            if (ctx->slots[i].state == SLOT_FREE) slot = (int)i;
+        if (slot < 0) return done(fail(ctx, MOE_ERR_OOM, "no free window slot to measure a transfer"));
+        Slot& sl = ctx->slots[slot];
+        if (sl.done_pending) {
+            (void)hipStreamWaitEvent(ctx->copy, sl.done, 0);
+            sl.done_pending = false;
+        }
+        if (sl.ready_recorded) (void)hipStreamWaitEvent(ctx->copy, sl.ready, 0);
+        io0 = mark(ctx->copy);
+        for (int i = 0; i < reps; ++i)
+            (void)hipMemcpyAsync(sl.ptr, ls.host[host_e], (size_t)ctx->L.expert_bytes, hipMemcpyHostToDevice, ctx->copy);
+        io1 = mark(ctx->copy);
+        (void)hipEventRecord(sl.ready, ctx->copy);
+        sl.ready_recorded = true;
+        (void)hipStreamWaitEvent(st, sl.ready, 0);
+        standin = sl.ptr;
+    }
+    if (N > 0) {
+        const Shape s = make_shape(ctx, N);
+        const PlanPtrs& p = ctx->plan;
+        uint8_t* w = ctx->ws;
+        const int split = auto_split_k(ctx, N);
+        float* o = (float*)(w + ctx->L.o);
+        FfnArgs a{};
+        a.wtab = ctx->wtab_dev + (size_t)layer * (E + S);
+        a.tile_expert = p.tile_expert;
+        a.tile_xblk = p.tile_xblk;
+        a.tile_hblk = p.tile_hblk;
+        a.tile_nblk = p.tile_nblk;
+        a.d = s.d;
+        a.f = s.f;
+        a.o_split_stride = ctx->L.o_split_stride;
+        a.variant = ctx->variant % 10;
+        a.passes = ctx->variant / 10;
+        a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
+        a.h_planes = ctx->h_planes;
+        a.h_plane_units = ctx->L.h_plane_units;
+        auto run_expert = [&](int e, const uint8_t* blob) {
+            a.w_single = blob;
+            a.tile_first = p.exp_tile0 + e;
+            a.tile_count = p.exp_ntiles + e;
+            a.max_tiles = ctx->h_tiles[e].count;
+            a.est_tiles = a.max_tiles;
+            if (a.max_tiles == 0) return;
+            a.act = w + ctx->L.xp;
+            a.out = w + ctx->L.h;
+            a.split_k = 1;
+            launch_ffn_up_bf16(st, a);
+            a.act = w + ctx->L.h;
+            a.out = o;
+            a.split_k = split;
+            launch_ffn_down_bf16(st, a);
+        };
+        const int q0 = mark(st);
+        for (int i = 0; i < reps; ++i) launch_gather_bf16(st, x_dev, s, p, w + ctx->L.xp);
+        const int q1 = mark(st);
+        for (int sh = 0; sh < S; ++sh) run_expert(E + sh, ls.resident[E + sh]);
+        std::vector<int> e0(ctx->h_nactive), e1(ctx->h_nactive);
+        for (int i = 0; i < ctx->h_nactive; ++i) {
+            const int e = ctx->h_order[i];
+            const uint8_t* blob = ls.resident[e] ? ls.resident[e] : standin;
+            e0[i] = mark(st);
+            for (int j = 0; j < reps; ++j) run_expert(e, blob);
+            e1[i] = mark(st);
+        }
+        const int c0 = mark(st);
+        for (int i = 0; i < reps; ++i) launch_combine(st, 1, s, p, o, split, ctx->L.o_split_stride, y_dev);
+        const int c1 = mark(st);
+        if (hipStreamSynchronize(st) != hipSuccess || hipStreamSynchronize(ctx->copy) != hipSuccess)
+            return done(fail(ctx, MOE_ERR_HIP, "synchronisation failed during measurement"));
+        out->t_c_gather_s = secs(q0, q1) / reps;
+        out->t_c_combine_s = secs(c0, c1) / reps;
+        for (int i = 0; i < ctx->h_nactive; ++i) out->t_c_expert_s[ctx->h_order[i]] = secs(e0[i], e1[i]) / reps;
+    } else {
+        (void)hipStreamSynchronize(st);
+        (void)hipStreamSynchronize(ctx->copy);
+    }
+    out->t_c_gate_group_s = secs(g0, g1) / reps;
+    if (io0 >= 0) out->t_io_expert_s = secs(io0, io1) / reps;
+    if (hipGetLastError() != hipSuccess) return done(fail(ctx, MOE_ERR_HIP, "a measurement launch failed"));
+    return done(MOE_OK);
+}
+
 moe_status moe_corr_rank(const int32_t* table_host, const int32_t* counts_prev_host, int32_t E,
                          int32_t K, int32_t* experts_out_host, int32_t* n_out, double* score_out) {
     if (!table_host || !counts_prev_host || !n_out || (K > 0 && !experts_out_host))

@@ -153,3 +153,39 @@ def test_f32_streamed_equals_resident():
     for l in range(2):
         assert np.array_equal(got[l][0], want[l]["y"])
     ctx.close()
+
+
+def test_measure_reports_times_and_leaves_the_context_usable():
+    """Measurement stage of the planner: positive device times for the gate, one expert transfer
+    and every activated expert; resident layers also deliver the layer output; afterwards the
+    streamed pipeline still reproduces the resident result bit for bit."""
+    w = STACK
+    layers = gen_stack(w)
+    want = resident_reference(w, layers)
+    ctx = H.make_ctx(w)
+    for l, data in enumerate(layers):
+        H.place_layer(ctx, w, l, data, streamed=True)
+    dev = ctx.device
+    x = layers[1].x.to(dev)
+    y = torch.zeros((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
+    m = ctx.measure(1, x, w.batch_offsets, y, reps=3)
+    assert m["n_active"] == int((want[1]["counts"] > 0).sum())
+    assert m["counts"] == want[1]["counts"].tolist()
+    assert m["exec_order"] == [int(e) for e in want[1]["exec_order"][:m["n_active"]]]
+    assert m["t_c_gate_group_s"] > 0 and m["t_io_expert_s"] > 0
+    assert m["t_c_gather_s"] > 0 and m["t_c_combine_s"] > 0
+    for e in range(w.n_experts):
+        assert (m["t_c_expert_s"][e] > 0) == (want[1]["counts"][e] > 0)
+    assert ctx.stats()["n_copies"] == 0                        # measurement copies are not pipeline copies
+    got = streamed_pass(ctx, w, layers, prefetch_k=2)
+    for l in range(w.n_layers):
+        assert np.array_equal(got[l][0], want[l]["y"])
+    ctx.close()
+    # all-resident layer: the measured run is the real computation
+    ctx = H.make_ctx(w, window_layers=0)
+    H.place_layer(ctx, w, 0, layers[0])
+    y = torch.zeros((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
+    m = ctx.measure(0, layers[0].x.to(dev), w.batch_offsets, y, reps=2)
+    assert m["t_io_expert_s"] == 0.0
+    assert np.array_equal(y.to(torch.float32).cpu().numpy(), want[0]["y"])
+    ctx.close()
