@@ -58,9 +58,10 @@ static double bf16_to_double(uint16_t b) {
     return (double)f;
 }
 
-/* wtype: 0 = float32 array, 1 = bfloat16 bit patterns (uint16). */
+/* wtype: 0 = float32 array, 1 = bfloat16 bit patterns (uint16), 2 = float64 array. */
 static double weight_at(const void *w, int wtype, size_t i) {
     if (wtype == 0) return (double)((const float *)w)[i];
+    if (wtype == 2) return ((const double *)w)[i];
     return bf16_to_double(((const uint16_t *)w)[i]);
 }
 
@@ -327,5 +328,47 @@ void ko_corr_predict(const int64_t *table, const int32_t *counts_prev, int E, in
         experts[n++] = best;
     }
     *n_out = n;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * 4-bit group quantisation of expert weights (paper Section 7, "Quantization", Eq. 8).
+ *
+ * A row of `cols` weights is cut into groups of `group` consecutive weights; group g of row r
+ * has a scale s and a zero point z (bf16-valued, real: the zero point is not an integer), and
+ * every weight is a 4-bit code q in 0..15:
+ *     W_q = round(W / s + z)            (ko_quant_q4, clamped to the 4-bit range)
+ *     W   = s * (W_q - z)               (ko_dequant_q4)
+ * Codes are stored two per byte, the even column in the low nibble.  Dequantisation is done in
+ * fp64 from the exact values of s and z.
+ */
+void ko_dequant_q4(const uint8_t *q, const uint16_t *s_bf16, const uint16_t *z_bf16, int rows,
+                   int cols, int group, double *out) {
+    const int ng = cols / group;
+    for (int r = 0; r < rows; ++r)
+        for (int c = 0; c < cols; ++c) {
+            const uint8_t byte = q[(size_t)r * (cols / 2) + c / 2];
+            const int code = (c & 1) ? (byte >> 4) : (byte & 15);
+            const double s = bf16_to_double(s_bf16[(size_t)r * ng + c / group]);
+            const double z = bf16_to_double(z_bf16[(size_t)r * ng + c / group]);
+            out[(size_t)r * cols + c] = s * ((double)code - z);
+        }
+}
+
+/* Eq. 8 forward for given s and z (how they are chosen is not part of it): round to nearest,
+ * ties to even (rint under the default rounding mode), then clamp to 0..15. */
+void ko_quant_q4(const double *w, const uint16_t *s_bf16, const uint16_t *z_bf16, int rows, int cols,
+                 int group, uint8_t *q) {
+    const int ng = cols / group;
+    memset(q, 0, (size_t)rows * (cols / 2));
+    for (int r = 0; r < rows; ++r)
+        for (int c = 0; c < cols; ++c) {
+            const double s = bf16_to_double(s_bf16[(size_t)r * ng + c / group]);
+            const double z = bf16_to_double(z_bf16[(size_t)r * ng + c / group]);
+            double v = rint(w[(size_t)r * cols + c] / s + z);
+            if (v < 0.0) v = 0.0;
+            if (v > 15.0) v = 15.0;
+            const uint8_t code = (uint8_t)v;
+            q[(size_t)r * (cols / 2) + c / 2] |= (c & 1) ? (uint8_t)(code << 4) : code;
+        }
 }
 

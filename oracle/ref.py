@@ -128,7 +128,9 @@ def _wtype(a: np.ndarray) -> int:
         return 0
     if a.dtype == np.uint16:
         return 1
-    raise TypeError(f"expert weights must be float32 or uint16 (bf16 bits), got {a.dtype}")
+    if a.dtype == np.float64:
+        return 2
+    raise TypeError(f"expert weights must be float32, float64 or uint16 (bf16 bits), got {a.dtype}")
 
 
 def expert_ffn(x, w1, w3, w2) -> np.ndarray:
@@ -205,6 +207,31 @@ def moe_layer(x, wg, w1, w3, w2, k: int, batch_offsets, dtype: str, n_shared: in
     if with_output:
         y = moe_forward(x, idx, w, w1, w3, w2, E, n_shared, tokens)
     return LayerRef(logits, idx, w, disp, y, None if tokens is None else _i32(tokens))
+
+
+def dequant_q4(q, s_bits, z_bits, group: int = 64) -> np.ndarray:
+    """fp64 weights s * (code - z) of a [rows, cols/2] uint8 code array (Eq. 8)."""
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    s_bits = np.ascontiguousarray(s_bits, dtype=np.uint16)
+    z_bits = np.ascontiguousarray(z_bits, dtype=np.uint16)
+    rows, cols = q.shape[0], q.shape[1] * 2
+    assert cols % group == 0 and s_bits.shape == z_bits.shape == (rows, cols // group)
+    out = np.empty((rows, cols), dtype=np.float64)
+    lib().ko_dequant_q4(_p(q, C.c_uint8), _p(s_bits, C.c_uint16), _p(z_bits, C.c_uint16), rows, cols,
+                        group, _p(out, C.c_double))
+    return out
+
+
+def quant_q4(w, s_bits, z_bits, group: int = 64) -> np.ndarray:
+    """4-bit codes round(w / s + z), clamped, packed two per byte (Eq. 8)."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    s_bits = np.ascontiguousarray(s_bits, dtype=np.uint16)
+    z_bits = np.ascontiguousarray(z_bits, dtype=np.uint16)
+    rows, cols = w.shape
+    q = np.empty((rows, cols // 2), dtype=np.uint8)
+    lib().ko_quant_q4(_p(w, C.c_double), _p(s_bits, C.c_uint16), _p(z_bits, C.c_uint16), rows, cols,
+                      group, _p(q, C.c_uint8))
+    return q
 
 
 def corr_update(table: np.ndarray, idx_prev, idx_cur) -> np.ndarray:
