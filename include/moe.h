@@ -67,6 +67,8 @@ typedef struct {
     int32_t max_batches;   /* largest number of batches in a group, <= MOE_MAX_BATCHES */
     int32_t dtype;         /* moe_dtype of X, Y and all weights */
     int32_t renormalize;   /* 1: routing weights renormalised over the k winners; 0: full softmax */
+    int32_t weight_bits;   /* 0 or 16: expert weights as dtype; 4 (bf16 only): 4-bit codes in groups
+                              of 64 with a bf16 scale and zero point each, set with moe_set_expert_q4 */
 } moe_config;
 
 /* Sizes and first-order time estimates for one configuration (moe_plan). */
@@ -141,6 +143,21 @@ moe_status moe_set_gate(moe_ctx* ctx, int32_t layer, const void* wg_dev);
  */
 moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const void* w1_dev,
                           const void* w3_dev, const void* w2_dev, int32_t where, void* packed_dst);
+
+/*
+ * moe_set_expert_q4 -- placement of one 4-bit group-quantised expert (contexts created with
+ * weight_bits == 4).  Quantisation and dequantisation follow the paper's Eq. 8 (Section 7,
+ * "Quantization"): W = s * (W_q - z) with one scale s and one real zero point z per group of 64
+ * consecutive weights of a row.  For each of W1, W3 ([f, d]) and W2 ([d, f]), all device
+ * pointers: q = codes, uint8 [rows, cols / 2], the even column in the low nibble; s, z = bf16
+ * [rows, cols / 64].  How s and z were fitted is the caller's business.  The kernels turn a
+ * weight back into bf16 (fp32 fma, one rounding) right before it is multiplied.  Everything
+ * else as moe_set_expert; the packed blob has moe_plan().expert_bytes = 27/16 * d * f bytes.
+ */
+moe_status moe_set_expert_q4(moe_ctx* ctx, int32_t layer, int32_t expert, const void* q1_dev,
+                             const void* s1_dev, const void* z1_dev, const void* q3_dev,
+                             const void* s3_dev, const void* z3_dev, const void* q2_dev,
+                             const void* s2_dev, const void* z2_dev, int32_t where, void* packed_dst);
 
 /*
  * moe_route -- gate + dispatch plan of one layer for a batch group (Section 2.1: softmax gate,

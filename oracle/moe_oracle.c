@@ -339,10 +339,25 @@ void ko_corr_predict(const int64_t *table, const int32_t *counts_prev, int E, in
  *     W_q = round(W / s + z)            (ko_quant_q4, clamped to the 4-bit range)
  *     W   = s * (W_q - z)               (ko_dequant_q4)
  * Codes are stored two per byte, the even column in the low nibble.  Dequantisation is done in
- * fp64 from the exact values of s and z.
+ * fp64 from the exact values of s and z.  The paper converts the tensors back to their original
+ * precision before computing with them: with to_bf16 != 0 the dequantised weight is rounded to
+ * bfloat16 (nearest, ties to even), which is what the expert then multiplies with.
  */
+/* x rounded to bfloat16 (8 significant bits), nearest-even, directly from fp64. */
+static double round_to_bf16(double x) {
+    if (x == 0.0 || !isfinite(x)) return x;
+    int e;
+    frexp(x, &e);              /* |x| = m * 2^e, 0.5 <= m < 1  ->  leading bit at 2^(e-1) */
+    int qe = e - 8;            /* unit in the last place of 8 significant bits */
+    if (qe < -133) qe = -133;  /* bfloat16 subnormals */
+    const double q = ldexp(1.0, qe);
+    return rint(x / q) * q;    /* both scalings by a power of two are exact */
+}
+
+double ko_round_bf16(double x) { return round_to_bf16(x); }
+
 void ko_dequant_q4(const uint8_t *q, const uint16_t *s_bf16, const uint16_t *z_bf16, int rows,
-                   int cols, int group, double *out) {
+                   int cols, int group, int to_bf16, double *out) {
     const int ng = cols / group;
     for (int r = 0; r < rows; ++r)
         for (int c = 0; c < cols; ++c) {
@@ -350,7 +365,8 @@ void ko_dequant_q4(const uint8_t *q, const uint16_t *s_bf16, const uint16_t *z_b
             const int code = (c & 1) ? (byte >> 4) : (byte & 15);
             const double s = bf16_to_double(s_bf16[(size_t)r * ng + c / group]);
             const double z = bf16_to_double(z_bf16[(size_t)r * ng + c / group]);
-            out[(size_t)r * cols + c] = s * ((double)code - z);
+            const double v = s * ((double)code - z);
+            out[(size_t)r * cols + c] = to_bf16 ? round_to_bf16(v) : v;
         }
 }
 

@@ -209,8 +209,15 @@ def moe_layer(x, wg, w1, w3, w2, k: int, batch_offsets, dtype: str, n_shared: in
     return LayerRef(logits, idx, w, disp, y, None if tokens is None else _i32(tokens))
 
 
-def dequant_q4(q, s_bits, z_bits, group: int = 64) -> np.ndarray:
-    """fp64 weights s * (code - z) of a [rows, cols/2] uint8 code array (Eq. 8)."""
+def round_bf16(x: float) -> float:
+    lib().ko_round_bf16.restype = C.c_double
+    lib().ko_round_bf16.argtypes = [C.c_double]
+    return float(lib().ko_round_bf16(float(x)))
+
+
+def dequant_q4(q, s_bits, z_bits, group: int = 64, to_bf16: bool = False) -> np.ndarray:
+    """fp64 weights s * (code - z) of a [rows, cols/2] uint8 code array (Eq. 8); with
+    ``to_bf16`` each is then rounded to bfloat16, the model's original precision."""
     q = np.ascontiguousarray(q, dtype=np.uint8)
     s_bits = np.ascontiguousarray(s_bits, dtype=np.uint16)
     z_bits = np.ascontiguousarray(z_bits, dtype=np.uint16)
@@ -218,7 +225,7 @@ def dequant_q4(q, s_bits, z_bits, group: int = 64) -> np.ndarray:
     assert cols % group == 0 and s_bits.shape == z_bits.shape == (rows, cols // group)
     out = np.empty((rows, cols), dtype=np.float64)
     lib().ko_dequant_q4(_p(q, C.c_uint8), _p(s_bits, C.c_uint16), _p(z_bits, C.c_uint16), rows, cols,
-                        group, _p(out, C.c_double))
+                        group, int(to_bf16), _p(out, C.c_double))
     return out
 
 

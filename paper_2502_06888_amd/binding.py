@@ -28,13 +28,13 @@ EXPORTS = ["moe_plan", "moe_plan_batches", "moe_create", "moe_destroy", "moe_set
            "moe_set_expert", "moe_route", "moe_route_wait", "moe_stream_experts",
            "moe_layer_forward", "moe_get_stats", "moe_reset_stats", "moe_set_tuning",
            "moe_set_profiling", "moe_get_profile", "moe_last_error", "moe_corr_enable",
-           "moe_corr_reset", "moe_corr_predict", "moe_corr_table", "moe_corr_rank", "moe_measure"]
+           "moe_corr_reset", "moe_corr_predict", "moe_corr_table", "moe_corr_rank", "moe_measure", "moe_set_expert_q4"]
 
 
 class MoeConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("d_model", "d_ff", "n_experts", "top_k", "n_shared", "n_layers", "window_layers",
-                 "max_tokens", "max_batches", "dtype", "renormalize")]
+                 "max_tokens", "max_batches", "dtype", "renormalize", "weight_bits")]
 
 
 MOE_MAX_EXPERTS = 256
@@ -92,6 +92,7 @@ def load_library():
     lib.moe_destroy.argtypes = [vp]
     lib.moe_set_gate.argtypes = [vp, i32, vp]
     lib.moe_set_expert.argtypes = [vp, i32, i32, vp, vp, vp, i32, vp]
+    lib.moe_set_expert_q4.argtypes = [vp, i32, i32] + [vp] * 9 + [i32, vp]
     lib.moe_route.argtypes = [vp, i32, vp, P(i32), i32] + [vp] * 8
     lib.moe_route_wait.argtypes = [vp, P(i32), P(i32), P(i32)]
     lib.moe_stream_experts.argtypes = [vp, i32, P(i32), i32, i32]
@@ -136,9 +137,10 @@ def _check(status: int, ctx=None):
 
 
 def make_config(d_model, d_ff, n_experts, top_k, n_shared=0, n_layers=1, window_layers=0,
-                max_tokens=512, max_batches=64, dtype=MOE_BF16, renormalize=1) -> MoeConfig:
+                max_tokens=512, max_batches=64, dtype=MOE_BF16, renormalize=1,
+                weight_bits=0) -> MoeConfig:
     return MoeConfig(d_model, d_ff, n_experts, top_k, n_shared, n_layers, window_layers,
-                     max_tokens, max_batches, dtype, renormalize)
+                     max_tokens, max_batches, dtype, renormalize, weight_bits)
 
 
 def moe_plan(cfg: MoeConfig, n_tokens: int, hbm_Bps: float = 8e12, link_Bps: float = 64e9,
@@ -221,6 +223,21 @@ class MoeContext:
         self._keep.append(packed)
         _check(self.lib.moe_set_expert(self.h, layer, expert, w1.data_ptr(), w3.data_ptr(),
                                        w2.data_ptr(), where, packed.data_ptr()), self.h)
+        return packed
+
+    def set_expert_q4(self, layer: int, expert: int, q4, where: int = MOE_RESIDENT, packed=None):
+        """Pack one 4-bit expert.  ``q4`` = ((q1, s1, z1), (q3, s3, z3), (q2, s2, z2)): device
+        tensors, codes uint8 [rows, cols/2], scales and zero points bf16 [rows, cols/64]."""
+        import torch
+        if packed is None:
+            if where == MOE_RESIDENT:
+                packed = torch.empty(self.plan.expert_bytes, dtype=torch.uint8, device=self.device)
+            else:
+                packed = torch.empty(self.plan.expert_bytes, dtype=torch.uint8, pin_memory=True)
+        self._keep.append(packed)
+        ptrs = [t.data_ptr() for trip in q4 for t in trip]
+        _check(self.lib.moe_set_expert_q4(self.h, layer, expert, *ptrs, where, packed.data_ptr()),
+               self.h)
         return packed
 
     # -- per batch group --------------------------------------------------------------

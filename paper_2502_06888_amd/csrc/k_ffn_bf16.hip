@@ -475,6 +475,225 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
 // chip-wide, not per workgroup.  One pass keeps the most workgroups in flight.
 static int pick_passes(int64_t) { return 1; }
 
+// ---- 4-bit group-quantised expert weights ------------------------------------------------------
+//
+// Experts may be kept and moved as 4-bit codes with one scale and one zero point per group of 64
+// weights along the reduction axis, W = s * (W_q - z) (paper Section 7, "Quantization", Eq. 8);
+// they are converted back to bf16 right before the multiplication.  A group of 64 is exactly
+// four reduction steps of one fragment row, so the packed stream of an output unit is, per
+// step quad, 1 KiB of codes (lane l: four dwords = steps 4q..4q+3, eight codes each, in the
+// lane's fragment order) and 128 bytes of (s, z) bf16 pairs (one per fragment row).  The ring
+// holds quads; a step's weight fragment is dequantised in registers (fp32 fma, hardware bf16
+// rounding) before its MFMAs.  One output unit per wavefront.
+typedef const __attribute__((address_space(1))) uint32_t* gptr32;
+
+struct QCtx {
+    gptr nib;     // codes of this wavefront's unit (+lane), 64 units per quad
+    gptr32 sz;    // (s | z << 16) of this wavefront's unit (+ lane & 31), 32 dwords per quad
+};
+
+__device__ __forceinline__ bf16x8 dequant8(uint32_t codes, uint32_t sz) {
+    const float s = __uint_as_float(sz << 16);
+    const float z = __uint_as_float(sz & 0xffff0000u);
+    const float zs = -z * s;
+    float v[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) v[p] = __builtin_fmaf((float)((codes >> (4 * p)) & 15u), s, zs);
+    bf16x8 r;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) r[p] = (__bf16)v[p];
+    return r;
+}
+
+template <int NB, int WAVES, int SX>
+struct PipeQ {
+    static constexpr int T = WAVES * 64;
+    static constexpr int PASSES = (NB * kBlkStageUnits + T - 1) / T;
+    static constexpr int RQ = 4;                  // ring depth in quads (16 reduction steps)
+    static constexpr int QS = SX / 4;             // quads per stage
+    static constexpr int RS = RQ / QS;            // ring depth in stages
+    static constexpr int DX = (NB <= 5) ? 2 : 1;  // activation look-ahead in stages
+    static constexpr int G = RS > DX ? RS : DX;
+    static_assert(SX % 4 == 0 && RQ % QS == 0 && G % RS == 0 && G % DX == 0, "ring geometry");
+    u32x4 wq[RQ];
+    uint32_t sz[RQ];
+    u32x4 xr[DX][PASSES];
+};
+
+template <int NB, int WAVES, int SX, int PL>
+__device__ __forceinline__ void open_pass_q4(const TileCtx& c, const QCtx& q, PipeQ<NB, WAVES, SX>& pp) {
+    using P = PipeQ<NB, WAVES, SX>;
+#pragma unroll
+    for (int i = 0; i < P::G; ++i) {
+        if (i < P::DX) load_x<P::PASSES, P::T, SX, PL>(c, pp.xr[i], c.k0 + i * SX);
+        if (i < P::RS) {
+#pragma unroll
+            for (int h = 0; h < P::QS; ++h) {  // past the end: re-read the last quad (in bounds, unused)
+                const int quad = min(c.k0 / 4 + i * P::QS + h, c.k1 / 4 - 1);
+                pp.wq[i * P::QS + h] = load_stream(q.nib + (size_t)quad * 64);
+                pp.sz[i * P::QS + h] = q.sz[(size_t)quad * 32];
+            }
+        }
+    }
+}
+
+template <int MODE, int NB, int WAVES, int SX, int PL>
+__device__ __forceinline__ void run_pass_q4(const TileCtx& c, const QCtx& q, PipeQ<NB, WAVES, SX>& pp,
+                                            f32x16 (&acc)[1][NB]) {
+    static_assert(SX * PL == kFragsPerBlk, "stage geometry");
+    using P = PipeQ<NB, WAVES, SX>;
+    constexpr int T = P::T, PASSES = P::PASSES, RS = P::RS, DX = P::DX, G = P::G, QS = P::QS;
+    constexpr int NS = NB * PL, NF = NS * SX, D = 3, DD = D < NF ? D : NF;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[0][b][i] = 0.f;
+    store_x<PASSES, T>(c, pp.xr[0], 0);
+    __syncthreads();
+
+    int k = c.k0, buf = 0;
+#define KMOE_FRAG_AT(t) L[(((t) % NS) * SX + (t) / NS) * 64]
+    for (; k + (G + RS) * SX <= c.k1; k += G * SX) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int kk = k + g * SX;
+            load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
+            __builtin_amdgcn_sched_barrier(0);
+            const u32x4* L = c.lds + buf * kBufUnits + lane;
+            u32x4 win[DD];
+#pragma unroll
+            for (int t = 0; t < DD; ++t) win[t] = KMOE_FRAG_AT(t);
+            bf16x8 wf;
+#pragma unroll
+            for (int t = 0; t < NF; ++t) {
+                const int j = t / NS, b = (t % NS) / PL;
+                const int slot = (g % RS) * QS + j / 4;
+                if (t % NS == 0) wf = dequant8(pp.wq[slot][j % 4], pp.sz[slot]);
+                acc[0][b] = mfma<MODE>(wf, as_bf16x8(win[t % DD]), acc[0][b]);
+                if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
+                if (t % NS == NS - 1 && j % 4 == 3) {  // the quad is consumed: next ring turn
+                    const size_t quad = (size_t)((kk + RS * SX) / 4 + j / 4);
+                    pp.wq[slot] = load_stream(q.nib + quad * 64);
+                    pp.sz[slot] = q.sz[quad * 32];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+    // drain: the last stages, guarded step by step
+    for (; k < c.k1; k += G * SX) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int kk = k + g * SX;
+            if (kk < c.k1) {  // uniform over the workgroup
+                const bool more = kk + SX < c.k1;
+                if (kk + DX * SX < c.k1)
+                    load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
+                const u32x4* L = c.lds + buf * kBufUnits + lane;
+#pragma unroll
+                for (int j = 0; j < SX; ++j) {
+                    if (kk + j < c.k1) {
+                        const int slot = (g % RS) * QS + j / 4;
+                        const bf16x8 wf = dequant8(pp.wq[slot][j % 4], pp.sz[slot]);
+#pragma unroll
+                        for (int i = 0; i < NS; ++i)
+                            acc[0][i / PL] = mfma<MODE>(wf, as_bf16x8(L[(i * SX + j) * 64]), acc[0][i / PL]);
+                        if (j % 4 == 3 && kk + RS * SX + j < c.k1) {
+                            const size_t quad = (size_t)((kk + RS * SX) / 4 + j / 4);
+                            pp.wq[slot] = load_stream(q.nib + quad * 64);
+                            pp.sz[slot] = q.sz[quad * 32];
+                        }
+                    }
+                }
+                if (more) store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
+                __syncthreads();
+                buf ^= 1;
+            }
+        }
+    }
+#undef KMOE_FRAG_AT
+}
+
+template <int MODE, int NB, int WAVES, int PL>
+__device__ __forceinline__ void run_tile_q4(const FfnArgs& a, TileCtx c, const uint8_t* nib_section,
+                                            const uint8_t* sz_section, int n_units, int grp,
+                                            int hblk0, int sp) {
+    constexpr int SX = 8 / PL;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int unit0 = grp * WAVES + wave;
+    const int wunit = min(unit0, n_units - 1);
+    const size_t quads = (size_t)c.nks / 4;
+    QCtx q;
+    q.nib = as_global(nib_section) + (size_t)wunit * quads * 64 + lane;
+    q.sz = (gptr32)(uintptr_t)sz_section + (size_t)wunit * quads * 32 + (lane & 31);
+    PipeQ<NB, WAVES, SX> pp;
+    f32x16 acc[1][NB];
+    open_pass_q4<NB, WAVES, SX, PL>(c, q, pp);
+    run_pass_q4<MODE, NB, WAVES, SX, PL>(c, q, pp, acc);
+    if (MODE == 0)
+        store_up<NB, 1>(a, acc, c.nblk, wunit, unit0, hblk0);
+    else
+        store_down<NB, 1>(a, acc, c.nblk, wunit, unit0, hblk0, sp);
+}
+
+// Blob of a 4-bit expert: [up codes d*f | up (s,z) d*f/8 | down codes d*f/2 | down (s,z) d*f/16] bytes.
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void ffn_up_q4_kernel(FfnArgs a, int n_groups) {
+    extern __shared__ u32x4 lds[];
+    const Wg w = locate(a, n_groups, 1);
+    if (!w.live) return;
+    const int e = a.tile_expert[w.tile];
+    const int nblk = a.tile_nblk[w.tile];
+    const int hblk0 = a.tile_hblk[w.tile];
+    const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
+    TileCtx c;
+    c.nks = a.d / 16;
+    c.ustride = 0;
+    c.wbase = nullptr;
+    c.actbase = as_global(a.act) + (size_t)a.tile_xblk[w.tile] * c.nks * 64;
+    c.plane = 0;
+    c.lds = lds;
+    c.k0 = 0;
+    c.k1 = c.nks;
+    c.nblk = nblk;
+    const size_t df = (size_t)a.d * a.f;
+#define CALL(NB) run_tile_q4<0, NB, WAVES, 1>(a, c, blob, blob + df, a.f / 16, w.grp, hblk0, 0)
+    NB_SWITCH(CALL)
+#undef CALL
+}
+
+template <int WAVES, int PL>
+__global__ __launch_bounds__(WAVES * 64) void ffn_down_q4_kernel(FfnArgs a, int n_groups) {
+    extern __shared__ u32x4 lds[];
+    const Wg w = locate(a, n_groups, a.split_k);
+    if (!w.live) return;
+    const int e = a.tile_expert[w.tile];
+    const int nblk = a.tile_nblk[w.tile];
+    const int hblk0 = a.tile_hblk[w.tile];
+    const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
+    TileCtx c;
+    c.nks = a.f / 16;
+    c.ustride = 0;
+    c.wbase = nullptr;
+    c.actbase = as_global(a.act) + (size_t)hblk0 * c.nks * 64;
+    c.plane = (size_t)a.h_plane_units;
+    c.lds = lds;
+    constexpr int SX = 8 / PL;
+    const int nstage = (c.nks + SX - 1) / SX;
+    c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
+    c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
+    c.nblk = nblk;
+    const size_t df = (size_t)a.d * a.f;
+    const uint8_t* down = blob + df + df / 8;
+#define CALL(NB) run_tile_q4<1, NB, WAVES, PL>(a, c, down, down + df / 2, a.d / 32, w.grp, hblk0, w.sp)
+    NB_SWITCH(CALL)
+#undef CALL
+}
+
 template <int WAVES, int U>
 void launch_up(hipStream_t st, const FfnArgs& a) {
     const int runs = (a.f / 16 + WAVES * U - 1) / (WAVES * U);
@@ -505,6 +724,9 @@ hipError_t allow_lds(K kernel) {
 
 int ffn_configure() {
     hipError_t e = allow_lds(&ffn_up_kernel<8, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_up_q4_kernel<8>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_q4_kernel<8, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_q4_kernel<8, 2>);
 
     if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<7, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<4, 2>);
@@ -520,6 +742,12 @@ int ffn_configure() {
 // two MFMAs).  Default: tiles expected to be full (many rows per expert, MFMA-bound) take the
 // two-unit shape, small tiles (weight streaming dominates) eight single-unit wavefronts.
 void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) {
+    if (a.weight_bits == 4) {
+        const int n_groups = (a.f / 16 + 7) / 8;
+        const int grid = (a.max_tiles * n_groups + kXcd - 1) / kXcd * kXcd;
+        hipLaunchKernelGGL((ffn_up_q4_kernel<8>), dim3(grid), dim3(512), kLdsBytes, st, a, n_groups);
+        return;
+    }
     const int units = a.f / 16;
     int v = a.variant;
     if (v == 0) v = a.full_tiles ? 3 : 1;
@@ -532,6 +760,15 @@ void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) {
 }
 
 void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
+    if (a.weight_bits == 4) {
+        const int n_groups = (a.d / 32 + 7) / 8;
+        const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
+        if (a.h_planes == 2)
+            hipLaunchKernelGGL((ffn_down_q4_kernel<8, 2>), dim3(grid), dim3(512), kLdsBytes, st, a, n_groups);
+        else
+            hipLaunchKernelGGL((ffn_down_q4_kernel<8, 1>), dim3(grid), dim3(512), kLdsBytes, st, a, n_groups);
+        return;
+    }
     const int units = a.d / 32;
     const bool two = a.variant == 3 && units >= 2;  // measured: one unit per wavefront is faster here
     if (a.h_planes == 2) {

@@ -57,6 +57,85 @@ __global__ __launch_bounds__(kThreads) void pack_down_kernel(const uint16_t* __r
     }
 }
 
+// ---- offline packing of a 4-bit group-quantised expert -------------------------------------------
+// Codes: [unit][quad = 4 steps][lane 64] x 16 B, dword i of a lane = its eight codes of step
+// 4*quad + i in the lane's fragment order (the same orders as the bf16 fragments above).
+// Scales: [unit][quad][fragment row 32] x (s | z << 16).
+__global__ __launch_bounds__(kThreads) void pack_up_q4_kernel(const uint8_t* __restrict__ q1,
+                                                              const uint8_t* __restrict__ q3, int d,
+                                                              int f, uint4* __restrict__ out) {
+    const int nq = d / 64;
+    const size_t units = (size_t)(f / 16) * nq * 64;
+    for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
+         u += (size_t)gridDim.x * kThreads) {
+        const int lane = (int)(u & 63);
+        const size_t qd = u >> 6;
+        const int quad = (int)(qd % nq);
+        const int unit = (int)(qd / nq);
+        const int r = lane & 31, hi = lane >> 5;
+        const uint8_t* row = r < 16 ? q1 + (size_t)(unit * 16 + r) * (d / 2)
+                                    : q3 + (size_t)(unit * 16 + r - 16) * (d / 2);
+        uint32_t v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)  // codes of columns 64*quad + 16*i + 8*hi + 0..7: four bytes
+            v[i] = *reinterpret_cast<const uint32_t*>(row + 32 * quad + 8 * i + 4 * hi);
+        out[u] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void pack_down_q4_kernel(const uint8_t* __restrict__ q2, int d,
+                                                                int f, uint4* __restrict__ out) {
+    const int nq = f / 64;
+    const size_t units = (size_t)(d / 32) * nq * 64;
+    for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
+         u += (size_t)gridDim.x * kThreads) {
+        const int lane = (int)(u & 63);
+        const size_t qd = u >> 6;
+        const int quad = (int)(qd % nq);
+        const int unit = (int)(qd / nq);
+        const int col = unit * 32 + (lane & 31), hi = lane >> 5;
+        const uint8_t* row = q2 + (size_t)col * (f / 2);
+        uint32_t v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {  // features 64q + 16i + 4hi + 0..3, then the same + 8
+            const int f0 = 64 * quad + 16 * i + 4 * hi;
+            const uint32_t lo = *reinterpret_cast<const uint16_t*>(row + f0 / 2);
+            const uint32_t up = *reinterpret_cast<const uint16_t*>(row + (f0 + 8) / 2);
+            v[i] = lo | (up << 16);
+        }
+        out[u] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+// (s, z) of fragment row r of every (unit, quad); rows_per_unit fragment rows come from `a`
+// (first half_rows rows, may be all) and then from `b`.
+__global__ __launch_bounds__(kThreads) void pack_sz_q4_kernel(const uint16_t* __restrict__ sa,
+                                                              const uint16_t* __restrict__ za,
+                                                              const uint16_t* __restrict__ sb,
+                                                              const uint16_t* __restrict__ zb,
+                                                              int n_units, int nq, int half_rows,
+                                                              uint32_t* __restrict__ out) {
+    const size_t n = (size_t)n_units * nq * 32;
+    for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < n;
+         u += (size_t)gridDim.x * kThreads) {
+        const int r = (int)(u & 31);
+        const size_t qd = u >> 5;
+        const int quad = (int)(qd % nq);
+        const int unit = (int)(qd / nq);
+        uint32_t s, z;
+        if (r < half_rows) {
+            const size_t at = (size_t)(unit * half_rows + r) * nq + quad;
+            s = sa[at];
+            z = za[at];
+        } else {
+            const size_t at = (size_t)(unit * half_rows + r - half_rows) * nq + quad;
+            s = sb[at];
+            z = zb[at];
+        }
+        out[u] = s | (z << 16);
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict__ src, size_t units,
                                                         uint4* __restrict__ dst) {
     for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
@@ -169,6 +248,21 @@ void launch_pack_expert_bf16(hipStream_t st, const void* w1, const void* w3, con
                        (const uint16_t*)w1, (const uint16_t*)w3, d, f, up);
     hipLaunchKernelGGL(pack_down_kernel, dim3(grid_for((size_t)f * d / 8)), dim3(kThreads), 0, st,
                        (const uint16_t*)w2, d, f, down);
+}
+
+void launch_pack_expert_q4(hipStream_t st, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
+                           const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
+                           const uint16_t* s2, const uint16_t* z2, int d, int f, void* blob) {
+    const size_t df = (size_t)d * f;
+    uint8_t* b = (uint8_t*)blob;
+    hipLaunchKernelGGL(pack_up_q4_kernel, dim3(grid_for(df / 16)), dim3(kThreads), 0, st, q1, q3, d, f,
+                       (uint4*)b);
+    hipLaunchKernelGGL(pack_sz_q4_kernel, dim3(grid_for(df / 32)), dim3(kThreads), 0, st, s1, z1, s3, z3,
+                       f / 16, d / 64, 16, (uint32_t*)(b + df));
+    hipLaunchKernelGGL(pack_down_q4_kernel, dim3(grid_for(df / 32)), dim3(kThreads), 0, st, q2, d, f,
+                       (uint4*)(b + df + df / 8));
+    hipLaunchKernelGGL(pack_sz_q4_kernel, dim3(grid_for(df / 64)), dim3(kThreads), 0, st, s2, z2, s2, z2,
+                       d / 32, f / 64, 32, (uint32_t*)(b + df + df / 8 + df / 2));
 }
 
 void launch_pack_expert_f32(hipStream_t st, const void* w1, const void* w3, const void* w2, int d,

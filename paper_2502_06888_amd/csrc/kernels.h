@@ -66,6 +66,11 @@ void launch_plan(hipStream_t st, const Shape& s, const BatchOffsets& bo, const P
 // Offline packing of one expert (W1,W3 [f,d]; W2 [d,f]) into the fragment-ordered blob.
 void launch_pack_expert_bf16(hipStream_t st, const void* w1, const void* w3, const void* w2,
                              int d, int f, void* blob);
+// The same for a 4-bit group-quantised expert: codes [rows, cols/2] (even column in the low
+// nibble), scales and zero points [rows, cols/64] as bf16, for W1, W3 ([f, d]) and W2 ([d, f]).
+void launch_pack_expert_q4(hipStream_t st, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
+                           const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
+                           const uint16_t* s2, const uint16_t* z2, int d, int f, void* blob);
 // Gather token rows per expert (and the plain rows for shared experts) into fragment order.
 void launch_gather_bf16(hipStream_t st, const void* x, const Shape& s, const PlanPtrs& p,
                         void* xp);
@@ -89,6 +94,7 @@ struct FfnArgs {
     int32_t variant;             // kernel shape (waves per workgroup x units per wave); 0 = default
     int32_t passes;              // runs of units per workgroup (0 = chosen from the tile estimate)
     int32_t full_tiles;          // host estimate: most tiles are full (more than 160 rows per expert)
+    int32_t weight_bits;         // 0/16: bf16 weights; 4: 4-bit codes in groups of 64 with (s, z)
     int32_t split_k;             // down projection only
     int64_t o_split_stride;      // elements between split-K partials of O
 };

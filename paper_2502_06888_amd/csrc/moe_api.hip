@@ -67,6 +67,8 @@ moe_status check_config(const moe_config* c, std::string& err) {
     if (c->window_layers < 0 || c->window_layers > c->n_layers) return bad("window_layers out of range", MOE_ERR_SHAPE);
     if (c->max_tokens < 1 || (int64_t)c->max_tokens * c->top_k > (1 << 28)) return bad("max_tokens out of range", MOE_ERR_SHAPE);
     if (c->max_batches < 1 || c->max_batches > MOE_MAX_BATCHES) return bad("max_batches out of range", MOE_ERR_SHAPE);
+    if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4) return bad("weight_bits must be 0, 16 or 4", MOE_ERR_INVALID_ARG);
+    if (c->weight_bits == 4 && c->dtype != MOE_BF16) return bad("4-bit expert weights need the bf16 path", MOE_ERR_INVALID_ARG);
     return MOE_OK;
 }
 
@@ -81,7 +83,7 @@ void compute_layout(const moe_config& c, Layout& L) {
     L.nchunks = (int32_t)((L.A + kPlanChunk - 1) / kPlanChunk);
     L.max_tiles = max_tiles_for((int)L.max_rowblks, (int)E, (int)S, c.max_tokens);
     L.split_cap = (c.dtype == MOE_BF16 && L.A <= 8192) ? 8 : 1;
-    L.expert_bytes = 3 * d * f * elt;
+    L.expert_bytes = c.weight_bits == 4 ? d * f * 27 / 16 : 3 * d * f * elt;  // q4: codes + (s, z) pairs
     int64_t off = 0;
     auto take = [&](int64_t bytes) {
         int64_t at = off;
@@ -550,16 +552,21 @@ moe_status moe_set_gate(moe_ctx* ctx, int32_t layer, const void* wg_dev) {
     return MOE_OK;
 }
 
-moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const void* w1_dev,
-                          const void* w3_dev, const void* w2_dev, int32_t where, void* packed_dst) {
-    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+}  // extern "C"
+
+namespace {
+
+// Common part of expert placement: validation, staging through window slot 0 for pinned
+// destinations, the pack launches (given as a callable), bookkeeping of where the blob lives.
+template <typename PackFn>
+moe_status place_expert(moe_ctx* ctx, int32_t layer, int32_t expert, int32_t where, void* packed_dst,
+                        PackFn pack) {
     const int E = ctx->cfg.n_experts, S = ctx->cfg.n_shared;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
     if (expert < 0 || expert >= E + S) return fail(ctx, MOE_ERR_INVALID_ARG, "expert %d out of range", expert);
-    if (!w1_dev || !w3_dev || !w2_dev || !packed_dst) return fail(ctx, MOE_ERR_INVALID_ARG, "null weight pointer");
+    if (!packed_dst) return fail(ctx, MOE_ERR_INVALID_ARG, "null weight pointer");
     if (where != MOE_RESIDENT && where != MOE_HOST_PINNED) return fail(ctx, MOE_ERR_INVALID_ARG, "bad residency");
     if (((uintptr_t)packed_dst & 15u) != 0) return fail(ctx, MOE_ERR_INVALID_ARG, "packed_dst must be 16-byte aligned");
-    const int d = ctx->cfg.d_model, f = ctx->cfg.d_ff;
     LayerState& ls = ctx->layers[layer];
     void* pack_to = packed_dst;
     if (where == MOE_HOST_PINNED) {
@@ -569,13 +576,11 @@ moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const voi
         for (const Slot& s : ctx->slots)
             if (s.state != SLOT_FREE) return fail(ctx, MOE_ERR_STATE, "placement while experts are in the window");
         HIP_TRY(ctx, hipStreamSynchronize(ctx->copy));
+        if (ctx->copy2) HIP_TRY(ctx, hipStreamSynchronize(ctx->copy2));
         pack_to = ctx->slots[0].ptr;  // staging: slot 0 is idle during the offline phase
     }
     HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
-    if (ctx->cfg.dtype == MOE_BF16)
-        launch_pack_expert_bf16(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, pack_to);
-    else
-        launch_pack_expert_f32(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, pack_to);
+    pack(pack_to);
     HIP_TRY(ctx, hipGetLastError());
     HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
     if (where == MOE_HOST_PINNED) {
@@ -592,6 +597,44 @@ moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const voi
         HIP_TRY(ctx, hipMemcpy((void*)(ctx->wtab_dev + (size_t)layer * (E + S) + expert), &ptr, 8, hipMemcpyHostToDevice));
     }
     return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const void* w1_dev,
+                          const void* w3_dev, const void* w2_dev, int32_t where, void* packed_dst) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (!w1_dev || !w3_dev || !w2_dev) return fail(ctx, MOE_ERR_INVALID_ARG, "null weight pointer");
+    if (ctx->cfg.weight_bits == 4) return fail(ctx, MOE_ERR_STATE, "this context holds 4-bit experts: use moe_set_expert_q4");
+    const int d = ctx->cfg.d_model, f = ctx->cfg.d_ff;
+    return place_expert(ctx, layer, expert, where, packed_dst, [&](void* to) {
+        if (ctx->cfg.dtype == MOE_BF16)
+            launch_pack_expert_bf16(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, to);
+        else
+            launch_pack_expert_f32(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, to);
+    });
+}
+
+moe_status moe_set_expert_q4(moe_ctx* ctx, int32_t layer, int32_t expert, const void* q1_dev,
+                             const void* s1_dev, const void* z1_dev, const void* q3_dev,
+                             const void* s3_dev, const void* z3_dev, const void* q2_dev,
+                             const void* s2_dev, const void* z2_dev, int32_t where, void* packed_dst) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (ctx->cfg.weight_bits != 4) return fail(ctx, MOE_ERR_STATE, "the context was not created with weight_bits = 4");
+    const void* all[9] = {q1_dev, s1_dev, z1_dev, q3_dev, s3_dev, z3_dev, q2_dev, s2_dev, z2_dev};
+    for (const void* p : all)
+        if (!p) return fail(ctx, MOE_ERR_INVALID_ARG, "null weight pointer");
+    for (const void* p : all)
+        if (((uintptr_t)p & 3u) != 0) return fail(ctx, MOE_ERR_INVALID_ARG, "quantised tensors must be 4-byte aligned");
+    const int d = ctx->cfg.d_model, f = ctx->cfg.d_ff;
+    return place_expert(ctx, layer, expert, where, packed_dst, [&](void* to) {
+        launch_pack_expert_q4(ctx->compute, (const uint8_t*)q1_dev, (const uint16_t*)s1_dev,
+                              (const uint16_t*)z1_dev, (const uint8_t*)q3_dev, (const uint16_t*)s3_dev,
+                              (const uint16_t*)z3_dev, (const uint8_t*)q2_dev, (const uint16_t*)s2_dev,
+                              (const uint16_t*)z2_dev, d, f, to);
+    });
 }
 
 moe_status moe_route(moe_ctx* ctx, int32_t layer, const void* x_dev,
@@ -743,6 +786,7 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
     a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
     a.h_planes = ctx->h_planes;
     a.h_plane_units = ctx->L.h_plane_units;
+    a.weight_bits = ctx->cfg.weight_bits;
 
     const bool prof = ctx->profiling && all_resident_layer(ctx, layer);
     ctx->prof_fwd = false;
@@ -980,6 +1024,7 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
         a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
         a.h_planes = ctx->h_planes;
         a.h_plane_units = ctx->L.h_plane_units;
+        a.weight_bits = ctx->cfg.weight_bits;
         auto run_expert = [&](int e, const uint8_t* blob) {
             a.w_single = blob;
             a.tile_first = p.exp_tile0 + e;

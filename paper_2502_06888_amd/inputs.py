@@ -154,6 +154,23 @@ def gen_expert(w: Workload, layer: int, e: int):
     return w1, w3, w2
 
 
+def gen_expert_q4(w: Workload, layer: int, e: int, group: int = 64):
+    """A 4-bit group-quantised expert as random inputs: for each of W1, W3 ([f, d]) and W2
+    ([d, f]) a triple (codes uint8 [rows, cols/2] with the even column in the low nibble,
+    scales bf16 [rows, cols/group], zero points bf16 [rows, cols/group]).  Codes are uniform on
+    0..15, zero points uniform on [6, 9], scales uniform on [0.5, 1.5] x w_std / 4.6, so that the
+    weights s * (code - z) have a standard deviation near w_std."""
+    out = []
+    for j, (rows, cols) in enumerate(((w.d_ff, w.d_model), (w.d_ff, w.d_model), (w.d_model, w.d_ff))):
+        g = np.random.Generator(np.random.PCG64(_sub_seed(w.seed, layer, 500 + tid_expert(e, j))))
+        codes = g.integers(0, 256, size=(rows, cols // 2), dtype=np.uint8)   # two uniform nibbles
+        s = (g.uniform(0.5, 1.5, size=(rows, cols // group)) * (w.w_std / 4.6)).astype(np.float32)
+        z = g.uniform(6.0, 9.0, size=(rows, cols // group)).astype(np.float32)
+        out.append((torch.from_numpy(codes), torch.from_numpy(s).to(torch.bfloat16),
+                    torch.from_numpy(z).to(torch.bfloat16)))
+    return tuple(out)
+
+
 def gen_x_gaussian(w: Workload, layer: int = 0) -> torch.Tensor:
     return to_storage(_normal(w.token_seed if w.token_seed >= 0 else w.seed, layer, TID_X,
                               (w.n_tokens, w.d_model), 1.0), w.dtype)

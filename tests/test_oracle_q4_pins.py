@@ -82,3 +82,34 @@ def test_double_weights_feed_the_expert_like_float32_ones():
     g = w1 @ x
     want = w2 @ ((g / (1 + np.exp(-g))) * (w3 @ x))
     assert np.allclose(ref.expert_ffn(x, w1, w3, w2), want, rtol=1e-12, atol=1e-14)
+
+
+def test_rounding_to_bf16_matches_the_library_conversion_and_hand_ties():
+    rng = np.random.default_rng(3)
+    vals = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-6, 6, 4000),
+                           [1.0, -1.0, 0.0, 3.0e38, 1e-39]]).astype(np.float32)
+    want = torch.from_numpy(vals).to(torch.bfloat16).to(torch.float64).numpy()    # library RNE
+    got = np.array([ref.round_bf16(float(v)) for v in vals])
+    assert np.array_equal(got, want)
+    # 8 significant bits: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1); 1 + 3*2^-8 -> 1 + 2^-6
+    assert ref.round_bf16(1.0 + 2.0 ** -8) == 1.0
+    assert ref.round_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert ref.round_bf16(1.0 + 2.0 ** -8 + 2.0 ** -40) == 1.0 + 2.0 ** -7        # just above the tie
+    # a double that rounds differently when it goes through float32 first (double rounding)
+    x = 1.0 + 2.0 ** -8 + 2.0 ** -30
+    assert float(np.float32(x)) == 1.0 + 2.0 ** -8 and ref.round_bf16(x) == 1.0 + 2.0 ** -7
+
+
+def test_dequant_to_original_precision_is_the_rounded_exact_value():
+    rng = np.random.default_rng(4)
+    rows, cols = 4, 128
+    q = rng.integers(0, 256, size=(rows, cols // 2), dtype=np.uint8)
+    s = bf16_bits(rng.uniform(1e-3, 1e-2, size=(rows, 2)))
+    z = bf16_bits(rng.uniform(6, 9, size=(rows, 2)))
+    exact = ref.dequant_q4(q, s, z)
+    rounded = ref.dequant_q4(q, s, z, to_bf16=True)
+    assert np.array_equal(rounded, np.vectorize(ref.round_bf16)(exact))
+    assert np.all(np.abs(rounded - exact) <= np.abs(exact) * 2.0 ** -8)
+    as_f32 = rounded.astype(np.float32)
+    assert np.array_equal(torch.from_numpy(as_f32).to(torch.bfloat16).to(torch.float32).numpy(), as_f32)
+
