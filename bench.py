@@ -140,18 +140,23 @@ def bench_streamed(w, args):
     from paper_2502_06888_amd import inputs as I
     dev = torch.device("cuda:0")
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    q4 = args.weight_bits == 4
     cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, w.n_layers,
-                        w.window_layers, w.n_tokens, w.n_batches, B.MOE_BF16, 1)
+                        w.window_layers, w.n_tokens, w.n_batches, B.MOE_BF16, 1, 4 if q4 else 0)
     ctx = B.MoeContext(cfg, compute, copy)
     link_peak = measure_link_peak(torch)
     t_setup = time.perf_counter()
     xs, noise = [], None
     for l in range(w.n_layers):                      # placement: generate, pack, park in pinned memory
-        data, noise = I.gen_layer(w, l, noise, threads=16)
+        data, noise = I.gen_layer(w, l, noise, threads=16, with_experts=not q4)
         ctx.set_gate(l, data.wg.to(dev))
         for e in range(w.n_experts + w.n_shared):
             where = B.MOE_HOST_PINNED if e < w.n_experts else B.MOE_RESIDENT
-            ctx.set_expert(l, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev), where)
+            if q4:
+                trip = I.gen_expert_q4(w, l, e)
+                ctx.set_expert_q4(l, e, tuple(tuple(t.to(dev) for t in m) for m in trip), where)
+            else:
+                ctx.set_expert(l, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev), where)
         xs.append(data.x.to(dev))
         del data
     t_setup = time.perf_counter() - t_setup
@@ -225,6 +230,7 @@ def bench_streamed(w, args):
         "config": {"workload": w.name, "d_model": w.d_model, "d_ff": w.d_ff, "n_experts": w.n_experts,
                    "top_k": w.top_k, "n_shared": w.n_shared, "n_layers": w.n_layers,
                    "tokens": w.n_tokens, "n_batches": w.n_batches, "window_layers": w.window_layers,
+                   "weight_bits": args.weight_bits,
                    "prefetch_per_layer": K, "prefetch_policy": args.prefetch_policy,
                    "experts": "pinned host memory",
                    "n_active_per_layer": n_active},
@@ -260,6 +266,8 @@ def main():
     ap.add_argument("--prefetch-policy", choices=["prev", "corr"], default="prev",
                     help="streamed stacks: prefetch the previous layer's busiest experts (prev) or "
                          "the correlation table's prediction (corr, warmed up on other batch groups)")
+    ap.add_argument("--weight-bits", type=int, choices=[16, 4], default=16,
+                    help="expert weights as bf16 (16) or as 4-bit codes in groups of 64 (4)")
     ap.add_argument("--plan", action="store_true",
                     help="streamed stacks: run the planner's measurement stage on layer 0, solve the "
                          "overlap inequalities for n, and sweep the number of batches per group")
@@ -286,14 +294,19 @@ def main():
         print(json.dumps(bench_streamed(w, args)))
         return
     dev = torch.device("cuda:0")
-    data, _ = I.gen_layer(w, 0, threads=16)
+    data, _ = I.gen_layer(w, 0, threads=16, with_experts=args.weight_bits != 4)
     compute = torch.cuda.Stream()
+    q4 = args.weight_bits == 4
     cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
-                        w.n_batches, B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1)
+                        w.n_batches, B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1, 4 if q4 else 0)
     ctx = B.MoeContext(cfg, compute)
     ctx.set_gate(0, data.wg.to(dev))
     for e in range(w.n_experts + w.n_shared):
-        ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
+        if q4:
+            trip = I.gen_expert_q4(w, 0, e)
+            ctx.set_expert_q4(0, e, tuple(tuple(t.to(dev) for t in m) for m in trip))
+        else:
+            ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
     if args.h_planes or args.split_k:
         ctx.set_tuning(args.split_k, args.h_planes)
     x = data.x.to(dev)
@@ -346,8 +359,9 @@ def main():
     A = w.n_tokens * w.top_k
     # algorithmic bytes of the dominant kernel (up projections + SwiGLU): W1 and W3 of every
     # activated expert once, the gathered token rows once, H written once
-    up_bytes = n_active * 2 * w.d_model * w.d_ff * elt + A * w.d_model * elt + A * w.d_ff * elt
-    layer_bytes = (n_active * 3 * w.d_model * w.d_ff * elt + w.n_tokens * w.d_model * elt * 2 +
+    wbytes = 9.0 / 16.0 if q4 else elt      # 4-bit codes + one (scale, zero point) pair per 64 weights
+    up_bytes = int(n_active * 2 * w.d_model * w.d_ff * wbytes) + A * w.d_model * elt + A * w.d_ff * elt
+    layer_bytes = (int(n_active * 3 * w.d_model * w.d_ff * wbytes) + w.n_tokens * w.d_model * elt * 2 +
                    2 * A * w.d_ff * elt + A * w.d_model * 4)
     achieved = up_bytes / (prof["up_ms"] * 1e-3) / 1e9 if prof.get("up_ms", 0) > 0 else 0.0
 
@@ -358,18 +372,19 @@ def main():
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "d_model": w.d_model, "d_ff": w.d_ff,
                    "n_experts": w.n_experts, "top_k": w.top_k, "n_batches": w.n_batches,
-                   "tokens": w.n_tokens, "experts": "resident in HBM", "n_active": n_active,
+                   "tokens": w.n_tokens, "experts": "resident in HBM", "weight_bits": args.weight_bits,
+                   "n_active": n_active,
                    "tokens_per_expert": counts},
         "roofline": {"bound": "hbm", "kernel": "ffn_up_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": recorded_traffic(w.name, "ffn_up_kernel"),
+                     "traffic": None if q4 else recorded_traffic(w.name, "ffn_up_kernel"),
                      "algorithmic_bytes": up_bytes},
         "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()},
         "layer": {"algorithmic_bytes": layer_bytes,
                   "hbm_frac_of_peak": layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                   "device_ms_per_step": dev_ms / args.steps},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not q4:
         out["cpu_baseline"] = cpu_baseline(w, data)
     ctx.close()
     print(json.dumps(out))
