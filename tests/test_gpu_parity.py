@@ -171,3 +171,27 @@ def test_mixtral_prefill_full_size_sampled_outputs(mixtral_layer):
     tokens = np.random.Generator(np.random.PCG64(6)).choice(w.n_tokens, 12, replace=False)
     got, want, err = run_case(w, tokens=np.sort(tokens).astype(np.int32), data=d2, ctx=ctx)
     assert got["counts"].sum() == 32768
+
+
+@pytest.mark.parametrize("w", [
+    I.scaled(SMALL, name="shapes_ragged", d_model=192, d_ff=448, n_experts=4, batch_tokens=(33, 1, 200)),
+    I.scaled(SMALL, name="shapes_full_tiles", n_experts=2, top_k=1, batch_tokens=(300, 300)),
+], ids=lambda w: w.name)
+def test_every_launch_shape_gives_the_same_bits(w):
+    """The launch shapes (8 or 7 wavefronts x 1 unit, 4 x 2 units, several passes per workgroup,
+    split-K 1) only change who computes what: every accumulator still adds the same products in
+    the same order, so the outputs must be identical bit for bit, and right."""
+    data, _ = I.gen_layer(w, 0)
+    ctx = H.make_ctx(w)
+    H.place_layer(ctx, w, 0, data)
+    want = H.oracle_layer(w, data, w.batch_offsets)
+    base = None
+    for variant in (1, 2, 3, 21, 22, 23, 41):
+        ctx.set_tuning(1, 2, variant)
+        got = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
+        if base is None:
+            base = got["y"]
+            H.check_routing(got, want, w.n_experts)
+            H.check_output(got["y"], want.y, w.dtype)
+        assert np.array_equal(got["y"], base), f"variant {variant} differs from variant 1"
+    ctx.close()
