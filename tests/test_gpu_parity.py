@@ -195,3 +195,20 @@ def test_every_launch_shape_gives_the_same_bits(w):
             H.check_output(got["y"], want.y, w.dtype)
         assert np.array_equal(got["y"], base), f"variant {variant} differs from variant 1"
     ctx.close()
+
+
+def test_maximum_experts_topk_shared_and_batches():
+    """The configured maxima at once: 256 routed experts, top-8, 8 shared experts, 64 batches (some
+    empty), more assignments than one plan chunk, most experts with a handful of tokens and many
+    with none."""
+    w = I.Workload("maxima", "bf16", 512, 192, 256, 8, n_shared=8,          # d > E: the skewed-routing
+                   batch_tokens=tuple([5, 0, 9, 3] * 16), zipf_s=1.2, corr=0.0, w_std=0.06)  # inputs need it
+    assert w.n_batches == 64 and w.n_tokens * w.top_k > 1024
+    got, want, err = run_case(w)
+    assert (got["counts"] == 0).any() and got["counts"].sum() == w.n_tokens * 8
+
+
+def test_f32_maximum_topk_and_many_experts():
+    w = I.Workload("maxima_f32", "f32", 64, 128, 128, 8, n_shared=2, batch_tokens=(7, 0, 11, 2, 30),
+                   w_std=0.1)
+    run_case(w)
