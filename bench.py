@@ -114,6 +114,40 @@ def planner_report(ctx, w, xs, ys, K, compute, torch, B):
             "note": "t_c_A = t_IO_A = t_IO_G = 0: no attention in this build, gate resident"}
 
 
+def fp16_intermediate_variant(w, data, args, torch, B):
+    """The same step with the opt-in H format (h_planes = 3: H and W2 as fp16 in the down
+    projection, same tolerance); reported beside the headline, which keeps the all-bf16 default."""
+    dev = torch.device("cuda:0")
+    compute = torch.cuda.Stream()
+    cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
+                        w.n_batches, B.MOE_BF16, 1)
+    ctx = B.MoeContext(cfg, compute)
+    ctx.set_tuning(0, 3, 0)
+    ctx.set_gate(0, data.wg.to(dev))
+    for e in range(w.n_experts + w.n_shared):
+        ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
+    x = data.x.to(dev)
+    y = torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
+    bo = [int(v) for v in w.batch_offsets]
+    steps = max(1, args.steps // 2)
+    with torch.cuda.stream(compute):
+        for _ in range(args.warmup):
+            ctx.route(0, x, bo); ctx.layer_forward(0, x, y)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ctx.route(0, x, bo); ctx.layer_forward(0, x, y)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        ctx.set_profiling(True)
+        ctx.route(0, x, bo); ctx.layer_forward(0, x, y)
+        prof = ctx.profile()
+    ctx.close()
+    return {"h_format": "fp16", "steps": steps, "ms_per_step": ms,
+            "value": w.n_tokens / (ms * 1e-3), "unit": "tokens/s",
+            "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()}}
+
+
 def measure_link_peak(torch, nbytes: int = 1 << 30, reps: int = 5) -> float:
     """Best host->device rate of one large copy from pinned memory on this machine, GB/s."""
     src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
@@ -259,6 +293,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="mixtral8x7b_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the extra measurement of the opt-in fp16 intermediate format")
     ap.add_argument("--h-planes", type=int, default=0, help="0 = library default")
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
     ap.add_argument("--prefetch", type=int, default=-1,
@@ -300,6 +336,8 @@ def main():
     cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
                         w.n_batches, B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1, 4 if q4 else 0)
     ctx = B.MoeContext(cfg, compute)
+    if args.h_planes or args.split_k:       # before placement: h_planes 3 packs W2 differently
+        ctx.set_tuning(args.split_k, args.h_planes)
     ctx.set_gate(0, data.wg.to(dev))
     for e in range(w.n_experts + w.n_shared):
         if q4:
@@ -307,8 +345,6 @@ def main():
             ctx.set_expert_q4(0, e, tuple(tuple(t.to(dev) for t in m) for m in trip))
         else:
             ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
-    if args.h_planes or args.split_k:
-        ctx.set_tuning(args.split_k, args.h_planes)
     x = data.x.to(dev)
     y = torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
     bo = [int(v) for v in w.batch_offsets]
@@ -374,6 +410,7 @@ def main():
                    "n_experts": w.n_experts, "top_k": w.top_k, "n_batches": w.n_batches,
                    "tokens": w.n_tokens, "experts": "resident in HBM", "weight_bits": args.weight_bits,
                    "n_active": n_active,
+                   "h_format": {0: "bf16 pair", 1: "bf16", 2: "bf16 pair", 3: "fp16"}[args.h_planes],
                    "tokens_per_expert": counts},
         "roofline": {"bound": "hbm", "kernel": "ffn_up_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -384,9 +421,12 @@ def main():
                   "hbm_frac_of_peak": layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                   "device_ms_per_step": dev_ms / args.steps},
     }
+    ctx.close()
+    if (w.dtype == "bf16" and not q4 and args.h_planes == 0 and not args.calibrate_copy
+            and not args.no_variants):
+        out["opt_in_fp16_intermediate"] = fp16_intermediate_variant(w, data, args, torch, B)
     if not args.no_cpu_baseline and not q4:
         out["cpu_baseline"] = cpu_baseline(w, data)
-    ctx.close()
     print(json.dumps(out))
 
 

@@ -221,6 +221,12 @@ moe_status moe_reset_stats(moe_ctx* ctx);
  * H = silu(X W1^T) .* (X W3^T) between the two GEMMs as a pair of bf16 numbers (value and
  * rounding remainder), which keeps the layer inside the 1e-2 absolute tolerance at d_ff = 14336;
  * 1 stores plain bf16 H (one third fewer MFMA operations, about twice the output error).
+ * 3 (opt-in, bf16 experts only) carries H as fp16 (11 significant bits, saturating at 65504) and
+ * multiplies it with W2 converted to fp16 on an fp16 MFMA: the accuracy of the pair at the cost
+ * of the single plane.  The conversion of W2 happens at placement, so h_planes must be set to 3
+ * before moe_set_expert and kept; it is exact for |w| in [2^-14, 65504], rounds smaller weights
+ * to fp16 subnormals (absolute error at most 2^-25) and fails with MOE_ERR_SHAPE on larger ones.
+ * moe_layer_forward returns MOE_ERR_STATE when the experts were placed for another H format.
  * variant: launch shape of the bf16 expert kernels, ones digit: 1 = 8 wavefronts x 1 output unit,
  * 2 = 7 x 1, 3 = 4 x 2 (0 = chosen by tile size); tens digit: passes per workgroup (0 = default);
  * -1 selects the defaults again.

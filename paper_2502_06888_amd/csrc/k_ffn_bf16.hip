@@ -25,6 +25,8 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte unit as a first-class value
 typedef const __attribute__((address_space(1))) u32x4* gptr;  // global (HBM) address space
@@ -92,8 +94,12 @@ __device__ __forceinline__ void store_x(const TileCtx& c, const u32x4 (&xr)[PASS
     }
 }
 
-template <int MODE>
+// HT = 0: bf16 operands; HT = 1: fp16 operands (down projection with H carried as fp16).
+template <int MODE, int HT = 0>
 __device__ __forceinline__ f32x16 mfma(const bf16x8 wf, const bf16x8 xa, const f32x16 acc) {
+    if (HT == 1)  // rows = tokens, cols = output columns; same bits, read as fp16
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, xa),
+                                                      __builtin_bit_cast(f16x8, wf), acc, 0, 0, 0);
     if (MODE == 0)  // rows = 16 gate + 16 up features, cols = tokens
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xa, acc, 0, 0, 0);
     // rows = tokens, cols = output columns
@@ -103,7 +109,7 @@ __device__ __forceinline__ f32x16 mfma(const bf16x8 wf, const bf16x8 xa, const f
 // MFMAs of one reduction step for the U units of a wavefront: NB*PL activation fragments read
 // from LDS through a rolling window of D registers, each fragment feeding U MFMAs.  Used by the
 // guarded drain.
-template <int MODE, int NB, int U, int SX, int PL, int D>
+template <int MODE, int NB, int U, int SX, int PL, int D, int HT = 0>
 __device__ __forceinline__ void step_mfma(const u32x4* L, int j, const u32x4 (&w)[U],
                                           f32x16 (&acc)[U][NB]) {
     constexpr int NF = NB * PL;
@@ -116,7 +122,7 @@ __device__ __forceinline__ void step_mfma(const u32x4* L, int j, const u32x4 (&w
         const int b = i / PL;
         const bf16x8 xa = as_bf16x8(win[i % DD]);
 #pragma unroll
-        for (int u = 0; u < U; ++u) acc[u][b] = mfma<MODE>(as_bf16x8(w[u]), xa, acc[u][b]);
+        for (int u = 0; u < U; ++u) acc[u][b] = mfma<MODE, HT>(as_bf16x8(w[u]), xa, acc[u][b]);
         if (i + DD < NF) win[i % DD] = L[((i + DD) * SX + j) * 64];
     }
     __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
@@ -132,7 +138,7 @@ __device__ __forceinline__ void step_mfma(const u32x4* L, int j, const u32x4 (&w
 // each ring slot is reloaded right after the last MFMA that reads it.  Order pinned: D reads,
 // then per fragment U MFMAs and one read (while any are left) and, after the last fragment of a
 // step, the U reloads of that step's slot.
-template <int MODE, int NB, int U, int SX, int PL, int D>
+template <int MODE, int NB, int U, int SX, int PL, int D, int HT = 0>
 __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gptr wnext,
                                            size_t ustride, f32x16 (&acc)[U][NB]) {
     constexpr int NS = NB * PL;   // fragments per step
@@ -148,7 +154,7 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
         const int j = t / NS, b = (t % NS) / PL;
         const bf16x8 xa = as_bf16x8(win[t % DD]);
 #pragma unroll
-        for (int u = 0; u < U; ++u) acc[u][b] = mfma<MODE>(as_bf16x8(w[j][u]), xa, acc[u][b]);
+        for (int u = 0; u < U; ++u) acc[u][b] = mfma<MODE, HT>(as_bf16x8(w[j][u]), xa, acc[u][b]);
         if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
         if (t % NS == NS - 1) {
 #pragma unroll
@@ -217,7 +223,7 @@ __device__ __forceinline__ void open_pass(const TileCtx& c, Pipe<NB, WAVES, U, S
 
 // One pass over the reduction range of the tile for the U units of every wavefront; the pass
 // must have been opened.  On return all LDS reads of the pass are behind a barrier.
-template <int MODE, int NB, int WAVES, int U, int SX, int PL>
+template <int MODE, int NB, int WAVES, int U, int SX, int PL, int HT = 0>
 __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX>& pp,
                                          f32x16 (&acc)[U][NB]) {
     static_assert(SX * PL == kFragsPerBlk, "stage geometry");
@@ -246,7 +252,7 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
             load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
             __builtin_amdgcn_sched_barrier(0);
             const u32x4* L = c.lds + buf * kBufUnits + lane;
-            stage_mfma<MODE, NB, U, SX, PL, D>(L, pp.wr[g % RS],
+            stage_mfma<MODE, NB, U, SX, PL, D, HT>(L, pp.wr[g % RS],
                                                c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc);
             __builtin_amdgcn_sched_barrier(0);
             store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
@@ -267,7 +273,7 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
 #pragma unroll
                 for (int j = 0; j < SX; ++j) {
                     if (kk + j < c.k1) {
-                        step_mfma<MODE, NB, U, SX, PL, D>(L, j, pp.wr[g % RS][j], acc);
+                        step_mfma<MODE, NB, U, SX, PL, D, HT>(L, j, pp.wr[g % RS][j], acc);
                         if (kk + RS * SX + j < c.k1) {
 #pragma unroll
                             for (int u = 0; u < U; ++u)
@@ -343,6 +349,20 @@ __device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U
                     lo[q] = __builtin_bit_cast(uint32_t, l);
                 }
                 const size_t at = ((size_t)(hblk0 + b) * ksteps_h + (size_t)(wunit + u)) * 64 + lane;
+                if (a.h_planes == 3) {  // H as fp16 (nearest-even, saturating at the largest finite value)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float h[2];
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            const float gv = acc[u][b][2 * q + t];
+                            const float v = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][2 * q + t + 8];
+                            h[t] = __builtin_fminf(__builtin_fmaxf(v, -65504.f), 65504.f);
+                        }
+                        const f16x2 v = {(_Float16)h[0], (_Float16)h[1]};
+                        hi[q] = __builtin_bit_cast(uint32_t, v);
+                    }
+                }
                 // streaming stores: measurably cheaper next to the weight stream than cached ones
                 __builtin_nontemporal_store(u32x4{hi[0], hi[1], hi[2], hi[3]}, hp + at);
                 if (a.h_planes == 2)
@@ -384,7 +404,7 @@ __device__ __forceinline__ void store_down(const FfnArgs& a, const f32x16 (&acc)
 // streams U real units, wunit = min(unit0, n_units - U) onwards, so that every load stays in
 // bounds, and stores only those it owns (wunit + u >= unit0).  The loads that open pass p + 1 are
 // issued before the epilogue of pass p.
-template <int MODE, int NB, int WAVES, int U, int PL>
+template <int MODE, int NB, int WAVES, int U, int PL, int HT = 0>
 __device__ __forceinline__ void run_tile(const FfnArgs& a, TileCtx c, gptr wsection, int n_units,
                                          int grp, int passes, int hblk0, int sp) {
     constexpr int SX = 8 / PL;
@@ -398,7 +418,7 @@ __device__ __forceinline__ void run_tile(const FfnArgs& a, TileCtx c, gptr wsect
     c.wbase = wsection + (size_t)wunit * c.ustride + lane;
     open_pass<NB, WAVES, U, SX, PL>(c, pp);
     for (int p = 0; live(p); ++p) {  // uniform over the workgroup
-        run_pass<MODE, NB, WAVES, U, SX, PL>(c, pp, acc);
+        run_pass<MODE, NB, WAVES, U, SX, PL, HT>(c, pp, acc);
         const int done_wunit = wunit, done_unit0 = unit0;
         if (live(p + 1)) {
             unit0 = first_unit(p + 1);
@@ -444,7 +464,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
 #undef CALL
 }
 
-template <int WAVES, int U, int PL>
+template <int WAVES, int U, int PL, int HT = 0>
 __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups, int passes) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, a.split_k);
@@ -465,7 +485,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
     c.nblk = nblk;
 #define CALL(NB) \
-    run_tile<1, NB, WAVES, U, PL>(a, c, as_global(blob + (size_t)a.d * a.f * 4), a.d / 32, w.grp, passes, hblk0, w.sp)
+    run_tile<1, NB, WAVES, U, PL, HT>(a, c, as_global(blob + (size_t)a.d * a.f * 4), a.d / 32, w.grp, passes, hblk0, w.sp)
     NB_SWITCH(CALL)
 #undef CALL
 }
@@ -704,13 +724,13 @@ void launch_up(hipStream_t st, const FfnArgs& a) {
                        n_groups, passes);
 }
 
-template <int WAVES, int U, int PL>
+template <int WAVES, int U, int PL, int HT = 0>
 void launch_down(hipStream_t st, const FfnArgs& a) {
     const int runs = (a.d / 32 + WAVES * U - 1) / (WAVES * U);
     const int passes = a.passes > 0 ? a.passes : pick_passes((int64_t)a.est_tiles * runs * a.split_k);
     const int n_groups = (runs + passes - 1) / passes;
     const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((ffn_down_kernel<WAVES, U, PL>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
+    hipLaunchKernelGGL((ffn_down_kernel<WAVES, U, PL, HT>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
                        st, a, n_groups, passes);
 }
 
@@ -732,6 +752,8 @@ int ffn_configure() {
     if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<4, 2>);
     if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 2>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 1, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 2>);
     return (int)e;
@@ -771,6 +793,10 @@ void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
     }
     const int units = a.d / 32;
     const bool two = a.variant == 3 && units >= 2;  // measured: one unit per wavefront is faster here
+    if (a.h_planes == 3) {  // H and W2 as fp16
+        if (two) launch_down<4, 2, 1, 1>(st, a); else launch_down<8, 1, 1, 1>(st, a);
+        return;
+    }
     if (a.h_planes == 2) {
         if (two) launch_down<4, 2, 2>(st, a); else launch_down<8, 1, 2>(st, a);
     } else {

@@ -136,6 +136,44 @@ __global__ __launch_bounds__(kThreads) void pack_sz_q4_kernel(const uint16_t* __
     }
 }
 
+// W2 for the fp16 form of the down projection: every bf16 weight converted to fp16 (nearest
+// even).  Exact for |w| in [2^-14, 65504]; smaller weights land on fp16 subnormals (absolute
+// error at most 2^-25); weights beyond the fp16 range are counted in *overflow and make the
+// placement fail.
+__global__ __launch_bounds__(kThreads) void pack_down_f16_kernel(const uint16_t* __restrict__ w2, int d,
+                                                                 int f, uint4* __restrict__ out,
+                                                                 int32_t* __restrict__ overflow) {
+    const size_t units = (size_t)f * d / 8;
+    const int nks = f / 16;
+    int bad = 0;
+    for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
+         u += (size_t)gridDim.x * kThreads) {
+        const int lane = (int)(u & 63);
+        const size_t q = u >> 6;
+        const int ks = (int)(q % nks);
+        const int unit = (int)(q / nks);
+        const int col = unit * 32 + (lane & 31);
+        const int hi = lane >> 5;
+        const uint16_t* src = w2 + (size_t)col * f + ks * 16 + 4 * hi;
+        uint32_t v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {  // positions 2i, 2i+1: features 4hi + 2(i%2) + 8(i/2) + 0..1
+            const uint16_t* pp = src + 8 * (i / 2) + 2 * (i % 2);
+            uint32_t packed = 0;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const float w = __uint_as_float((uint32_t)pp[t] << 16);
+                if (fabsf(w) > 65504.f) ++bad;  // also catches NaN-free infinities; NaN compares false
+                const _Float16 hv = (_Float16)w;
+                packed |= (uint32_t)__builtin_bit_cast(uint16_t, hv) << (16 * t);
+            }
+            v[i] = packed;
+        }
+        out[u] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+    if (bad) atomicAdd(overflow, bad);
+}
+
 __global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict__ src, size_t units,
                                                         uint4* __restrict__ dst) {
     for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
@@ -241,13 +279,17 @@ inline int grid_for(size_t work_items, int cap = 4096) {
 }  // namespace
 
 void launch_pack_expert_bf16(hipStream_t st, const void* w1, const void* w3, const void* w2, int d,
-                             int f, void* blob) {
+                             int f, void* blob, int32_t* w2_f16_overflow) {
     uint4* up = (uint4*)blob;
     uint4* down = up + (size_t)f * d * 2 / 8;
     hipLaunchKernelGGL(pack_up_kernel, dim3(grid_for((size_t)f * d / 4)), dim3(kThreads), 0, st,
                        (const uint16_t*)w1, (const uint16_t*)w3, d, f, up);
-    hipLaunchKernelGGL(pack_down_kernel, dim3(grid_for((size_t)f * d / 8)), dim3(kThreads), 0, st,
-                       (const uint16_t*)w2, d, f, down);
+    if (w2_f16_overflow)  // down section as fp16, for H carried as fp16
+        hipLaunchKernelGGL(pack_down_f16_kernel, dim3(grid_for((size_t)f * d / 8)), dim3(kThreads), 0,
+                           st, (const uint16_t*)w2, d, f, down, w2_f16_overflow);
+    else
+        hipLaunchKernelGGL(pack_down_kernel, dim3(grid_for((size_t)f * d / 8)), dim3(kThreads), 0, st,
+                           (const uint16_t*)w2, d, f, down);
 }
 
 void launch_pack_expert_q4(hipStream_t st, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,

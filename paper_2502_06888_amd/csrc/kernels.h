@@ -64,8 +64,10 @@ void launch_plan(hipStream_t st, const Shape& s, const BatchOffsets& bo, const P
 
 // ---- bf16 path ----------------------------------------------------------------------------
 // Offline packing of one expert (W1,W3 [f,d]; W2 [d,f]) into the fragment-ordered blob.
+// w2_f16_overflow != null: the down section holds W2 as fp16; the counter (device, zeroed by the
+// caller) receives the number of weights beyond the fp16 range.
 void launch_pack_expert_bf16(hipStream_t st, const void* w1, const void* w3, const void* w2,
-                             int d, int f, void* blob);
+                             int d, int f, void* blob, int32_t* w2_f16_overflow);
 // The same for a 4-bit group-quantised expert: codes [rows, cols/2] (even column in the low
 // nibble), scales and zero points [rows, cols/64] as bf16, for W1, W3 ([f, d]) and W2 ([d, f]).
 void launch_pack_expert_q4(hipStream_t st, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
@@ -89,7 +91,7 @@ struct FfnArgs {
     int32_t max_tiles;           // tiles the grid was sized for
     int32_t est_tiles;           // tiles the host expects to be live (launch-shape heuristic)
     int32_t d, f;
-    int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder)
+    int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder); 3: H (and W2) as fp16
     int64_t h_plane_units;       // 16-byte units between the two planes of H
     int32_t variant;             // kernel shape (waves per workgroup x units per wave); 0 = default
     int32_t passes;              // runs of units per workgroup (0 = chosen from the tile estimate)

@@ -146,6 +146,7 @@ struct LayerState {
     std::vector<const uint8_t*> resident;  // E+S device blobs (null if not resident)
     std::vector<const uint8_t*> host;      // E pinned host blobs (null if resident)
     std::vector<int> slot_of;              // E: window slot holding the expert, or -1
+    std::vector<char> w2_f16;              // E+S: the expert's down section holds W2 as fp16
 };
 
 struct HostTile {
@@ -476,6 +477,7 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
         ls.resident.assign(E + S, nullptr);
         ls.host.assign(E, nullptr);
         ls.slot_of.assign(E, -1);
+        ls.w2_f16.assign(E + S, 0);
     }
     auto cleanup = [&](moe_status s, const char* what, hipError_t e) {
         moe_status r = fail(nullptr, s, "%s failed: %s", what, hipGetErrorString(e));
@@ -609,12 +611,27 @@ moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const voi
     if (!w1_dev || !w3_dev || !w2_dev) return fail(ctx, MOE_ERR_INVALID_ARG, "null weight pointer");
     if (ctx->cfg.weight_bits == 4) return fail(ctx, MOE_ERR_STATE, "this context holds 4-bit experts: use moe_set_expert_q4");
     const int d = ctx->cfg.d_model, f = ctx->cfg.d_ff;
-    return place_expert(ctx, layer, expert, where, packed_dst, [&](void* to) {
+    const bool f16 = ctx->cfg.dtype == MOE_BF16 && ctx->h_planes == 3;
+    int32_t* overflow = (int32_t*)(ctx->ws + ctx->L.meta) + 8;  // spare word of the meta block
+    if (f16) HIP_TRY(ctx, hipMemsetAsync(overflow, 0, 4, ctx->compute));
+    moe_status st = place_expert(ctx, layer, expert, where, packed_dst, [&](void* to) {
         if (ctx->cfg.dtype == MOE_BF16)
-            launch_pack_expert_bf16(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, to);
+            launch_pack_expert_bf16(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, to, f16 ? overflow : nullptr);
         else
             launch_pack_expert_f32(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, to);
     });
+    if (st != MOE_OK) return st;
+    ctx->layers[layer].w2_f16[expert] = f16 ? 1 : 0;
+    if (f16) {
+        int32_t n_bad = 0;
+        HIP_TRY(ctx, hipMemcpy(&n_bad, overflow, 4, hipMemcpyDeviceToHost));
+        if (n_bad > 0) {
+            ctx->layers[layer].resident[expert] = nullptr;  // the blob is not usable
+            if (expert < ctx->cfg.n_experts) ctx->layers[layer].host[expert] = nullptr;
+            return fail(ctx, MOE_ERR_SHAPE, "W2 of layer %d expert %d has %d weights beyond the fp16 range: place it with h_planes 1 or 2", layer, expert, n_bad);
+        }
+    }
+    return MOE_OK;
 }
 
 moe_status moe_set_expert_q4(moe_ctx* ctx, int32_t layer, int32_t expert, const void* q1_dev,
@@ -763,6 +780,10 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
             if (e >= E || !ls.host[e]) return fail(ctx, MOE_ERR_STATE, "weights of layer %d expert %d not set", layer, e);
         }
     }
+    if (ctx->cfg.dtype == MOE_BF16 && ctx->cfg.weight_bits != 4)
+        for (int e = 0; e < E + S; ++e)
+            if ((ls.w2_f16[e] != 0) != (ctx->h_planes == 3))
+                return fail(ctx, MOE_ERR_STATE, "layer %d expert %d was placed for %s H, the context is set to h_planes %d", layer, e, ls.w2_f16[e] ? "fp16" : "bf16", ctx->h_planes);
     const Shape s = make_shape(ctx, N);
     const PlanPtrs& p = ctx->plan;
     hipStream_t st = ctx->compute;
@@ -1157,7 +1178,9 @@ moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32
     if (variant < -1 || variant > 49) return fail(ctx, MOE_ERR_INVALID_ARG, "variant out of range");
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
     if (split_k < 0 || split_k > 64) return fail(ctx, MOE_ERR_INVALID_ARG, "split_k out of range");
-    if (h_planes < 0 || h_planes > 2) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1 or 2");
+    if (h_planes < 0 || h_planes > 3) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1, 2 or 3");
+    if (h_planes == 3 && (ctx->cfg.dtype != MOE_BF16 || ctx->cfg.weight_bits == 4))
+        return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes 3 (fp16 H) needs bf16 experts");
     ctx->split_k_user = split_k;
     if (h_planes > 0) ctx->h_planes = h_planes;
     if (variant != 0) ctx->variant = variant < 0 ? 0 : variant;

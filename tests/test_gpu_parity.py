@@ -212,3 +212,45 @@ def test_f32_maximum_topk_and_many_experts():
     w = I.Workload("maxima_f32", "f32", 64, 128, 128, 8, n_shared=2, batch_tokens=(7, 0, 11, 2, 30),
                    w_std=0.1)
     run_case(w)
+
+
+def test_fp16_intermediate_option_small_and_full_size():
+    """h_planes = 3: H as fp16, W2 converted to fp16 at placement, fp16 MFMA in the down
+    projection.  Same oracle, same tolerance as the default."""
+    for w, tokens in ((SMALL, None),
+                      (I.scaled(SMALL, name="f16_ragged", d_model=128, d_ff=192, batch_tokens=(33, 1, 17)), None),
+                      (I.WORKLOADS["mixtral8x7b_decode"], list(range(3, 512, 43)))):
+        data, _ = I.gen_layer(w, 0, threads=16)
+        ctx = H.make_ctx(w)
+        ctx.set_tuning(0, 3, 0)                      # before placement: W2 is packed for it
+        H.place_layer(ctx, w, 0, data)
+        got = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
+        want = H.oracle_layer(w, data, w.batch_offsets, tokens=tokens)
+        H.check_routing(got, want, w.n_experts)
+        H.check_output(got["y"], want.y, w.dtype, tokens)
+        # the experts are now tied to that format
+        ctx.set_tuning(0, 2, 0)
+        x = data.x.to(ctx.device)
+        y = torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=ctx.device)
+        with torch.cuda.stream(ctx.compute_stream):
+            ctx.route(0, x, w.batch_offsets)
+            with pytest.raises(B.MoeError) as ei:
+                ctx.layer_forward(0, x, y)
+        assert ei.value.status == B.MOE_ERR_STATE
+        ctx.close()
+
+
+def test_fp16_option_refuses_weights_beyond_the_fp16_range():
+    w = SMALL
+    data, _ = I.gen_layer(w, 0)
+    ctx = H.make_ctx(w)
+    ctx.set_tuning(0, 3, 0)
+    dev = ctx.device
+    w2 = data.w2[0].clone()
+    w2[3, 5] = 1.0e5
+    with pytest.raises(B.MoeError) as ei:
+        ctx.set_expert(0, 0, data.w1[0].to(dev), data.w3[0].to(dev), w2.to(dev))
+    assert ei.value.status == B.MOE_ERR_SHAPE
+    ctx.set_expert(0, 0, data.w1[0].to(dev), data.w3[0].to(dev), data.w2[0].to(dev))   # in range: fine
+    ctx.close()
+
