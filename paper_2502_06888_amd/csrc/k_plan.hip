@@ -14,11 +14,17 @@ constexpr int kThreads = 256;
 constexpr int kRounds = kPlanChunk / kThreads;  // 4
 constexpr int kSegs = kRounds * (kThreads / 64);  // 16 (round, wave) segments per chunk
 
-__device__ __forceinline__ int batch_of(const BatchOffsets& bo, int t) {
-    int lo = 0, hi = bo.n;  // find b with v[b] <= t < v[b+1]
+// The batch offsets arrive as a kernel argument; a per-lane index into them would be a chain of
+// dependent global loads, so they are first copied to LDS (sbo, kMaxBatches + 1 ints).
+__device__ __forceinline__ void stage_offsets(const BatchOffsets& bo, int32_t* sbo) {
+    for (int b = threadIdx.x; b <= kMaxBatches; b += kThreads) sbo[b] = bo.v[b];
+}
+
+__device__ __forceinline__ int batch_of(const int32_t* sbo, int n, int t) {
+    int lo = 0, hi = n;  // find b with v[b] <= t < v[b+1]
     while (hi - lo > 1) {
         int mid = (lo + hi) >> 1;
-        if (bo.v[mid] <= t) lo = mid; else hi = mid;
+        if (sbo[mid] <= t) lo = mid; else hi = mid;
     }
     return lo;
 }
@@ -30,6 +36,8 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t* __r
                                                               unsigned long long* __restrict__ blk_mask) {
     __shared__ int32_t cnt[kMaxExperts];
     __shared__ unsigned long long msk[kMaxExperts];
+    __shared__ int32_t sbo[kMaxBatches + 1];
+    stage_offsets(bo, sbo);
     for (int e = threadIdx.x; e < E; e += kThreads) {
         cnt[e] = 0;
         msk[e] = 0ull;
@@ -41,7 +49,7 @@ __global__ __launch_bounds__(kThreads) void plan_count_kernel(const int32_t* __r
         if (a < A) {
             const int e = idx[a];
             atomicAdd(&cnt[e], 1);
-            atomicOr(&msk[e], 1ull << batch_of(bo, a / k));
+            atomicOr(&msk[e], 1ull << batch_of(sbo, bo.n, a / k));
         }
     }
     __syncthreads();
@@ -110,7 +118,8 @@ __device__ __forceinline__ void scan_body(const Shape& s, const PlanPtrs& p, int
         const int routed_blks = pof[E] / kRowBlk;
         const int nblk_tok = (s.N + kRowBlk - 1) / kRowBlk;
         for (int sh = 0; sh < s.S; ++sh) {
-            p.exp_tile0[E + sh] = nt;
+            const int first = nt;  // kept in a register: reading exp_tile0 back would wait on the store
+            p.exp_tile0[E + sh] = first;
             for (int b = 0; b < nblk_tok && nt < max_tiles; b += kTileBlks) {
                 p.tile_expert[nt] = E + sh;
                 p.tile_xblk[nt] = routed_blks + b;
@@ -118,12 +127,13 @@ __device__ __forceinline__ void scan_body(const Shape& s, const PlanPtrs& p, int
                 p.tile_nblk[nt] = min(kTileBlks, nblk_tok - b);
                 ++nt;
             }
-            p.exp_ntiles[E + sh] = nt - p.exp_tile0[E + sh];
+            p.exp_ntiles[E + sh] = nt - first;
         }
         for (int i = 0; i < nact; ++i) {
             const int e = ord[i];
             const int b0 = pof[e] / kRowBlk, nb = (cnt[e] + kRowBlk - 1) / kRowBlk;
-            p.exp_tile0[e] = nt;
+            const int first = nt;
+            p.exp_tile0[e] = first;
             for (int b = 0; b < nb && nt < max_tiles; b += kTileBlks) {
                 p.tile_expert[nt] = e;
                 p.tile_xblk[nt] = b0 + b;
@@ -131,7 +141,7 @@ __device__ __forceinline__ void scan_body(const Shape& s, const PlanPtrs& p, int
                 p.tile_nblk[nt] = min(kTileBlks, nb - b);
                 ++nt;
             }
-            p.exp_ntiles[e] = nt - p.exp_tile0[e];
+            p.exp_ntiles[e] = nt - first;
         }
         p.meta[0] = nact;
         p.meta[1] = nt;
@@ -168,7 +178,8 @@ __global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunk
 // exclusive expert offsets, base[] (may be null = zeros) the tokens of earlier chunks.
 __device__ __forceinline__ void rank_body(const int32_t* __restrict__ idx, int A, int E,
                                           const PlanPtrs& p, int chunk, int32_t (*seg)[kMaxExperts],
-                                          const int32_t* off, const int32_t* base_of_chunk) {
+                                          const int32_t* off, const int32_t* base_of_chunk,
+                                          const int32_t* preloaded = nullptr) {
     for (int i = threadIdx.x; i < kSegs * kMaxExperts; i += kThreads) (&seg[0][0])[i] = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -177,7 +188,7 @@ __device__ __forceinline__ void rank_body(const int32_t* __restrict__ idx, int A
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int a = base + r * kThreads + threadIdx.x;
-        const int e = a < A ? idx[a] : -1;
+        const int e = preloaded ? preloaded[r] : (a < A ? idx[a] : -1);
         my_e[r] = e;
         my_rank[r] = 0;
         bool done = e < 0;
@@ -238,18 +249,26 @@ __global__ __launch_bounds__(kThreads) void plan_fused_kernel(const int32_t* __r
     __shared__ int32_t ord[kMaxExperts];
     __shared__ int32_t nact;
     __shared__ int32_t seg[kSegs][kMaxExperts];
+    __shared__ int32_t sbo[kMaxBatches + 1];
     const int A = s.N * s.k;
+    int32_t mine[kRounds];  // this thread's assignments, loaded once for both phases
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int a = r * kThreads + threadIdx.x;
+        mine[r] = a < A ? idx[a] : -1;
+    }
+    stage_offsets(bo, sbo);
     for (int e = threadIdx.x; e < s.E; e += kThreads) {
         cnt[e] = 0;
         msk[e] = 0ull;
     }
     __syncthreads();
+#pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int a = r * kThreads + threadIdx.x;
-        if (a < A) {
-            const int e = idx[a];
-            atomicAdd(&cnt[e], 1);
-            atomicOr(&msk[e], 1ull << batch_of(bo, a / s.k));
+        if (mine[r] >= 0) {
+            atomicAdd(&cnt[mine[r]], 1);
+            atomicOr(&msk[mine[r]], 1ull << batch_of(sbo, bo.n, a / s.k));
         }
     }
     __syncthreads();
@@ -257,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void plan_fused_kernel(const int32_t* __r
     __syncthreads();
     scan_body(s, p, max_tiles, cnt, nbt, off, pof, ord, &nact);
     __syncthreads();
-    rank_body(idx, A, s.E, p, 0, seg, off, nullptr);
+    rank_body(idx, A, s.E, p, 0, seg, off, nullptr, mine);
 }
 
 // Correlation table update (paper Section 6.2, path length 1): one thread per token adds its
