@@ -237,3 +237,78 @@ def gen_layer(w: Workload, layer: int = 0, prev_noise: Optional[np.ndarray] = No
             data.w3.append(w3)
             data.w2.append(w2)
     return data, noise
+
+
+# ---- attention (non-expert) layer of the pipeline --------------------------------------------
+
+@dataclass(frozen=True)
+class AttnWorkload:
+    """One decoding step of the attention layer over a batch group (Algorithm 1, non-expert
+    branch): every batch brings its hidden state and its key-value cache."""
+    name: str
+    d_model: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    batch_seqs: tuple          # sequences per batch of the group
+    batch_pos: tuple           # cached positions per batch (all sequences of a batch alike)
+    max_len: int               # capacity of the caches, in positions
+    rope_theta: float = 1.0e6
+    rms_eps: float = 1.0e-5
+    kv_on_host: bool = True    # caches in pinned host memory, streamed batch by batch
+    seed: int = 0
+    w_std: float = 0.02
+
+    @property
+    def n_batches(self) -> int:
+        return len(self.batch_seqs)
+
+    @property
+    def n_tokens(self) -> int:
+        return int(sum(self.batch_seqs))
+
+    def kv_bytes(self, b: int) -> int:
+        """Bytes of valid K and V of batch b before the step."""
+        return 2 * self.batch_seqs[b] * self.n_kv_heads * self.batch_pos[b] * self.head_dim * 2
+
+
+# Mixtral-8x7B attention shape; 8 batches x 64 sequences after a 512-token prompt (Section 9.1).
+ATTN_WORKLOADS: Dict[str, AttnWorkload] = {
+    "attn_tiny": AttnWorkload("attn_tiny", 256, 8, 2, 32, (5, 3, 8), (17, 0, 40), 48, kv_on_host=True),
+    "attn_mixtral8x7b_decode": AttnWorkload("attn_mixtral8x7b_decode", 4096, 32, 8, 128, (64,) * 8,
+                                            (512,) * 8, 576, kv_on_host=True),
+    "attn_mixtral8x7b_decode_hbm": AttnWorkload("attn_mixtral8x7b_decode_hbm", 4096, 32, 8, 128,
+                                                (64,) * 8, (512,) * 8, 576, kv_on_host=False),
+}
+
+_TID_ATTN = {"norm": 700, "wq": 701, "wk": 702, "wv": 703, "wo": 704}
+
+
+def gen_attn_weights(w: AttnWorkload, layer: int = 0) -> Dict[str, torch.Tensor]:
+    """bf16 tensors: norm [d] ~ 1 + N(0, 0.1), wq [Hq*hd, d], wk / wv [Hkv*hd, d], wo [d, Hq*hd]."""
+    dq, dkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
+    out = {"norm": to_storage(1.0 + _normal(w.seed, layer, _TID_ATTN["norm"], (w.d_model,), 0.1), "bf16")}
+    for name, shape in (("wq", (dq, w.d_model)), ("wk", (dkv, w.d_model)), ("wv", (dkv, w.d_model)),
+                        ("wo", (w.d_model, dq))):
+        out[name] = to_storage(_normal(w.seed, layer, _TID_ATTN[name], shape, w.w_std), "bf16")
+    return out
+
+
+def gen_attn_hidden(w: AttnWorkload, layer: int, b: int) -> torch.Tensor:
+    """Hidden state of batch b entering the layer: bf16 [n_seq, d], N(0, 1)."""
+    return to_storage(_normal(w.seed, layer, 710 + b, (w.batch_seqs[b], w.d_model), 1.0), "bf16")
+
+
+def gen_kv_cache(w: AttnWorkload, layer: int, b: int, pin: bool = False):
+    """(K, V) caches of batch b: bf16 [n_seq, Hkv, max_len, hd]; the first batch_pos[b] positions
+    hold N(0, 1) draws, the rest zeros."""
+    shape = (w.batch_seqs[b], w.n_kv_heads, w.max_len, w.head_dim)
+    out = []
+    for j in range(2):
+        t = torch.zeros(shape, dtype=torch.bfloat16, pin_memory=pin)
+        if w.batch_pos[b] > 0:
+            g = np.random.Generator(np.random.PCG64(_sub_seed(w.seed, layer, 800 + 2 * b + j)))
+            a = g.standard_normal((shape[0], shape[1], w.batch_pos[b], shape[3]), dtype=np.float32)
+            t[:, :, :w.batch_pos[b], :] = torch.from_numpy(a).to(torch.bfloat16)
+        out.append(t)
+    return out[0], out[1]
