@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libklotski_moe.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["moe_api.hip", "k_router.hip", "k_plan.hip", "k_misc.hip", "k_ffn_f32.hip",
-           "k_ffn_bf16.hip"]
+           "k_ffn_bf16.hip", "attn_api.hip", "k_attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -24,7 +24,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     """Compile every source and link the shared library.  ``force`` recompiles everything."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    headers = [os.path.join(CSRC, "kernels.h"), os.path.join(HERE, "..", "include", "moe.h")]
+    headers = [os.path.join(CSRC, "kernels.h"), os.path.join(CSRC, "attn_kernels.h"),
+               os.path.join(HERE, "..", "include", "moe.h"), os.path.join(HERE, "..", "include", "moe_attn.h")]
     jobs = []
     for name in SOURCES:
         src = os.path.join(CSRC, name)

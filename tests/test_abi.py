@@ -13,8 +13,8 @@ from paper_2502_06888_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+def declared_symbols(header="moe.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
 
@@ -26,6 +26,25 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in moe.h but not exported"
     assert sorted(B.EXPORTS) == names
+
+
+def test_library_exports_every_attention_symbol():
+    from paper_2502_06888_amd import attn_binding as A
+    lib = A.load_library()
+    names = declared_symbols("moe_attn.h")
+    assert "moe_attn_forward_group" in names
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in moe_attn.h but not exported"
+    assert sorted(A.ATTN_EXPORTS) == names
+    assert C.sizeof(A.MoeAttnConfig) == 8 * 4
+    assert C.sizeof(A.MoeAttnBatch) == 4 * 4 + 4 * 8
+    assert C.sizeof(A.MoeAttnProfile) == 6 * 8
+    # host-only sizing: Mixtral-8x7B attention with two staged caches of 64 x 8 x 576 x 128 bf16
+    cfg = A.MoeAttnConfig(4096, 32, 8, 128, 64, 576, 1e6, 1e-5)
+    need = A.workspace_bytes(cfg)
+    cache = 64 * 8 * 576 * 128 * 2
+    weights = (4096 + 2 * 1024) * 4096 * 2 + 4096 * 4096 * 2
+    assert need > 4 * cache + weights and need < 4 * cache + weights + (200 << 20)
 
 
 def test_struct_sizes_match_header():

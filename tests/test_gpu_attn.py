@@ -1,0 +1,136 @@
+"""Attention (non-expert) layer on the GPU against the CPU oracle, through the C ABI.
+
+Tolerance: the layer output and the appended cache rows are bf16 results of contractions over
+bf16 operands (the normalised activations are rounded to bf16 for the matrix cores): 2e-2
+relative / 1e-2 absolute, the bar of the bf16 MoE outputs.  Cache rows the step does not
+write must come back bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attn_ref as R
+from paper_2502_06888_amd import attn_binding as A
+from paper_2502_06888_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def oracle_group(w, ws, hs, caches):
+    raw = {k: I.as_raw(v) for k, v in ws.items()}
+    out = []
+    for b in range(w.n_batches):
+        y, k2, v2 = R.attn_decode(I.as_f32(hs[b]), raw["norm"], raw["wq"], raw["wk"], raw["wv"], raw["wo"],
+                                  I.as_raw(caches[b][0]), I.as_raw(caches[b][1]), w.batch_pos[b],
+                                  w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, w.rms_eps)
+        out.append((y, k2, v2))
+    return out
+
+
+def widen(bits):
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+
+
+def check_group(w, batches, want):
+    for b, (bt, (y, k2, v2)) in enumerate(zip(batches, want)):
+        got = bt.h_out.cpu().to(torch.float64).numpy()
+        err = np.abs(got - y) - (1e-2 + 2e-2 * np.abs(y))
+        assert err.max() <= 0, f"batch {b}: output off by {err.max()} beyond tolerance"
+        for name, g, o in (("K", bt.k_cache, k2), ("V", bt.v_cache, v2)):
+            gb = I.as_raw(g.cpu())
+            pos = w.batch_pos[b]
+            keep_mask = np.ones(gb.shape[2], bool)
+            keep_mask[pos] = False
+            assert np.array_equal(gb[:, :, keep_mask, :], o[:, :, keep_mask, :]), \
+                f"batch {b}: {name} rows other than pos changed"
+            # the appended row: same bar as the layer output, and much closer than that on average
+            gr, orow = widen(gb[:, :, pos, :]), widen(o[:, :, pos, :])
+            err = np.abs(gr - orow) - (1e-2 + 2e-2 * np.abs(orow))
+            assert err.max() <= 0, f"batch {b}: new {name} row off by {err.max()} beyond tolerance"
+            rms = np.sqrt((orow ** 2).mean())
+            assert np.abs(gr - orow).mean() <= 4e-3 * rms, \
+                f"batch {b}: new {name} row mean error {np.abs(gr - orow).mean() / rms:.2e} of rms"
+
+
+def run_group(w, on_host, layer=0, ctx=None):
+    ws = I.gen_attn_weights(w, layer)
+    hs = [I.gen_attn_hidden(w, layer, b) for b in range(w.n_batches)]
+    caches = [I.gen_kv_cache(w, layer, b) for b in range(w.n_batches)]
+    own = ctx is None
+    if own:
+        ctx = A.AttnContext(A.config_for(w), DEV)
+    ctx.set_weights(*[ws[n].to(DEV) for n in ("norm", "wq", "wk", "wv", "wo")])
+    batches = []
+    for b in range(w.n_batches):
+        if on_host:
+            k, v = caches[b][0].clone().pin_memory(), caches[b][1].clone().pin_memory()
+            h_in = hs[b].clone().pin_memory()
+            h_out = torch.zeros_like(h_in).pin_memory()
+        else:
+            k, v = caches[b][0].to(DEV), caches[b][1].to(DEV)
+            h_in = hs[b].to(DEV)
+            h_out = torch.zeros_like(h_in)
+        batches.append(A.AttnBatch(k, v, h_in, h_out, w.batch_pos[b]))
+    torch.cuda.synchronize()
+    ctx.forward_group(batches)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    check_group(w, batches, oracle_group(w, ws, hs, caches))
+    if own:
+        ctx.close()
+
+
+@pytest.mark.parametrize("on_host", [False, True])
+def test_tiny_group_matches_oracle(on_host):
+    run_group(I.ATTN_WORKLOADS["attn_tiny"], on_host)
+
+
+@pytest.mark.parametrize("hd,hq,hkv", [(32, 8, 8), (64, 4, 2), (128, 8, 1), (128, 2, 1)])
+def test_head_shapes(hd, hq, hkv):
+    w = I.scaled(I.ATTN_WORKLOADS["attn_tiny"], head_dim=hd, n_q_heads=hq, n_kv_heads=hkv,
+                 d_model=256, batch_seqs=(33, 2), batch_pos=(70, 3), max_len=80, seed=3)
+    run_group(w, on_host=True)
+
+
+def test_ragged_rows_and_several_row_tiles():
+    # 130 sequences: five row blocks -> two row tiles of four blocks, the last one ragged
+    w = I.scaled(I.ATTN_WORKLOADS["attn_tiny"], d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64,
+                 batch_seqs=(130, 1, 64), batch_pos=(9, 255, 128), max_len=256, seed=5)
+    run_group(w, on_host=False)
+    run_group(w, on_host=True)
+
+
+def test_context_reuse_with_shrinking_batches():
+    big = I.scaled(I.ATTN_WORKLOADS["attn_tiny"], batch_seqs=(8, 8, 8, 8, 8), batch_pos=(40, 41, 42, 43, 44), seed=7)
+    small = I.scaled(big, batch_seqs=(3, 2), batch_pos=(5, 0), seed=8)
+    ctx = A.AttnContext(A.config_for(big), DEV)
+    run_group(big, True, ctx=ctx)
+    run_group(small, True, ctx=ctx)
+    run_group(big, False, ctx=ctx)
+    ctx.close()
+
+
+def test_argument_errors():
+    from paper_2502_06888_amd import binding as B
+    w = I.ATTN_WORKLOADS["attn_tiny"]
+    ctx = A.AttnContext(A.config_for(w), DEV)
+    k, v = [t.to(DEV) for t in I.gen_kv_cache(w, 0, 0)]
+    h = I.gen_attn_hidden(w, 0, 0).to(DEV)
+    with pytest.raises(B.MoeError) as ei:
+        ctx.forward_group([A.AttnBatch(k, v, h, h, 1)])
+    assert ei.value.status == B.MOE_ERR_STATE
+    ws = I.gen_attn_weights(w, 0)
+    ctx.set_weights(*[ws[n] for n in ("norm", "wq", "wk", "wv", "wo")])   # plain host tensors
+    with pytest.raises(B.MoeError) as ei:
+        ctx.forward_group([A.AttnBatch(k, v, h, h, w.max_len)])
+    assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    with pytest.raises(B.MoeError) as ei:   # pageable host memory where pinned is required
+        ctx.forward_group([A.AttnBatch(k.cpu(), v.cpu(), h, h, 1)])
+    assert ei.value.status == B.MOE_ERR_NOT_PINNED
+    ctx.forward_group([A.AttnBatch(k, v, h, h, w.batch_pos[0])])          # in place, still usable
+    ctx.synchronize()
+    ctx.close()
+    with pytest.raises(B.MoeError) as ei:
+        A.workspace_bytes(A.MoeAttnConfig(200, 8, 2, 32, 4, 16, 1e4, 1e-5))
+    assert ei.value.status == B.MOE_ERR_SHAPE
