@@ -286,6 +286,113 @@ def bench_streamed(w, args):
     return out
 
 
+def attn_cpu_baseline(w, ws, hs, caches, budget_s: float = 12.0):
+    """The attention oracle on the host cores, on the first sequences of batch 0."""
+    from oracle import attn_ref, ref
+    from paper_2502_06888_amd import inputs as I
+    raw = {k: I.as_raw(v) for k, v in ws.items()}
+    x, kc, vc = I.as_f32(hs[0]), I.as_raw(caches[0][0]), I.as_raw(caches[0][1])
+    cores = ref.num_threads()
+
+    def run(n):
+        t0 = time.perf_counter()
+        attn_ref.attn_decode(x[:n], raw["norm"], raw["wq"], raw["wk"], raw["wv"], raw["wo"], kc[:n], vc[:n],
+                             w.batch_pos[0], w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, w.rms_eps)
+        return time.perf_counter() - t0
+
+    probe = min(w.batch_seqs[0], cores)
+    t_probe = run(probe)
+    n = int(min(w.batch_seqs[0], max(probe, probe * budget_s / max(t_probe, 1e-3))))
+    n = max(probe, n // cores * cores)
+    t = run(n) if n != probe else t_probe
+    return {"value": n / t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {n} of {w.batch_seqs[0]} sequences of batch 0 of the same workload "
+                      f"(fp64 attention layer over {w.batch_pos[0]} cached positions), {t:.1f} s"}
+
+
+def bench_attention(w, args):
+    """Attention (non-expert) layer of one decoding step over the batch group: batch by batch,
+    each batch's key-value cache and hidden state either resident in HBM or streamed from pinned
+    host memory by the load / store streams.  A step is one moe_attn_forward_group call."""
+    import torch
+    from paper_2502_06888_amd import attn_binding as A
+    from paper_2502_06888_amd import inputs as I
+    dev = torch.device("cuda:0")
+    ctx = A.AttnContext(A.config_for(w), dev)
+    ws = I.gen_attn_weights(w, 0)
+    ctx.set_weights(*[ws[n].to(dev) for n in ("norm", "wq", "wk", "wv", "wo")])
+    hs = [I.gen_attn_hidden(w, 0, b) for b in range(w.n_batches)]
+    caches = [I.gen_kv_cache(w, 0, b) for b in range(w.n_batches)]
+    link_peak = measure_link_peak(torch) if w.kv_on_host else None
+    batches = []
+    for b in range(w.n_batches):
+        if w.kv_on_host:
+            k, v = caches[b][0].pin_memory(), caches[b][1].pin_memory()
+            h_in = hs[b].pin_memory()
+            h_out = torch.zeros_like(h_in).pin_memory()
+        else:
+            k, v, h_in = caches[b][0].to(dev), caches[b][1].to(dev), hs[b].to(dev)
+            h_out = torch.zeros_like(h_in)
+        batches.append(A.AttnBatch(k, v, h_in, h_out, w.batch_pos[b]))
+    steps = min(args.steps, 20 if w.kv_on_host else 200)
+    warmup = min(args.warmup, 2 if w.kv_on_host else 20)
+    for _ in range(max(1, warmup)):
+        ctx.forward_group(batches)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx.forward_group(batches)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    ctx.set_profiling(True)                      # separate passes: event timing of streams and kernels
+    prof = []
+    for _ in range(3):
+        ctx.forward_group(batches)
+        prof.append(ctx.profile())
+    ctx.set_profiling(False)
+    pr = min(prof, key=lambda p: p.wall_s)
+    names = ["rmsnorm", "qkv_proj", "qkv_finish", "attn_decode", "out_proj", "out_finish"]
+    kern_us = {n: pr.kernel_s[i] / w.n_batches * 1e6 for i, n in enumerate(names)}
+    dq, dkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
+    kv_bytes = sum(2 * w.batch_seqs[b] * dkv * (w.batch_pos[b] + 1) * 2 for b in range(w.n_batches))
+    attn_bytes = kv_bytes + sum(w.batch_seqs[b] * dq * (4 + 2) for b in range(w.n_batches))
+    weight_bytes = ((dq + 2 * dkv) * w.d_model + w.d_model * dq) * 2
+    out = {
+        "metric": "attn_layer_tokens_per_s", "value": w.n_tokens / wall, "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": max(1, warmup), "ms_per_step": wall * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "d_model": w.d_model, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_batches": w.n_batches,
+                   "seqs_per_batch": list(w.batch_seqs), "cached_positions": list(w.batch_pos),
+                   "cache": "pinned host memory" if w.kv_on_host else "HBM"},
+        "kernels_us_per_batch": kern_us,
+        "pipeline": {"wall_ms": pr.wall_s * 1e3, "load_busy_ms": pr.load_busy_s * 1e3,
+                     "store_busy_ms": pr.store_busy_s * 1e3, "compute_busy_ms": pr.compute_busy_s * 1e3,
+                     "bytes_loaded": pr.bytes_loaded, "bytes_stored": pr.bytes_stored},
+    }
+    t_attn = pr.kernel_s[3] / w.n_batches
+    out["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel",
+                       "achieved": attn_bytes / w.n_batches / t_attn / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": attn_bytes / w.n_batches / t_attn / 1e9 / HBM_PEAK_GBS,
+                       "traffic": recorded_traffic(w.name, "attn_decode_kernel"),
+                       "algorithmic_bytes_per_launch": attn_bytes // w.n_batches,
+                       "layer_bytes_per_batch": (kv_bytes + weight_bytes * w.n_batches) // w.n_batches,
+                       "layer_GBps": (kv_bytes + weight_bytes * w.n_batches) / pr.compute_busy_s / 1e9}
+    if w.kv_on_host:
+        gbs = pr.bytes_loaded / pr.wall_s / 1e9
+        out["host_link"] = {"achieved_GBps": gbs, "measured_peak_GBps": link_peak, "nominal_peak_GBps": 64.0,
+                            "frac_of_nominal": gbs / 64.0, "frac_of_measured": gbs / link_peak,
+                            "bubble_link_idle": max(0.0, 1.0 - pr.load_busy_s / pr.wall_s),
+                            "copy_rate_GBps": pr.bytes_loaded / pr.load_busy_s / 1e9,
+                            "compute_busy_fraction": pr.compute_busy_s / pr.wall_s}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = attn_cpu_baseline(w, ws, hs, caches)
+    ctx.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -325,6 +432,9 @@ def main():
         sys.exit(2)
     B.load_library()  # fails loudly when the HIP library is not built
 
+    if args.workload in I.ATTN_WORKLOADS:
+        print(json.dumps(bench_attention(I.ATTN_WORKLOADS[args.workload], args)))
+        return
     w = I.WORKLOADS[args.workload]
     if w.streamed:
         print(json.dumps(bench_streamed(w, args)))

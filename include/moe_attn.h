@@ -35,7 +35,7 @@ extern "C" {
 typedef struct moe_attn_ctx moe_attn_ctx; /* opaque, library-owned */
 
 typedef struct {
-    int32_t d_model;    /* multiple of 128 */
+    int32_t d_model;    /* multiple of 128, at most 8192 */
     int32_t n_q_heads;  /* n_q_heads / n_kv_heads in {1, 2, 4, 8} */
     int32_t n_kv_heads;
     int32_t head_dim;   /* 32, 64 or 128; n_q_heads*head_dim a multiple of 128 */
@@ -64,6 +64,8 @@ typedef struct {
     double load_busy_s;    /* sum over batches of the load stream's copy time */
     double store_busy_s;   /* the same for the store stream */
     double compute_busy_s; /* sum over batches of kernel time */
+    double kernel_s[6];    /* the same per kernel: norm, q|k|v projection, rotation + cache append,
+                              attention, output projection, residual */
     int64_t bytes_loaded;  /* host -> device */
     int64_t bytes_stored;  /* device -> host */
 } moe_attn_profile;

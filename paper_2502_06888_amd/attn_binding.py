@@ -30,7 +30,7 @@ class MoeAttnBatch(C.Structure):
 
 class MoeAttnProfile(C.Structure):
     _fields_ = [("wall_s", C.c_double), ("load_busy_s", C.c_double), ("store_busy_s", C.c_double),
-                ("compute_busy_s", C.c_double), ("bytes_loaded", C.c_int64),
+                ("compute_busy_s", C.c_double), ("kernel_s", C.c_double * 6), ("bytes_loaded", C.c_int64),
                 ("bytes_stored", C.c_int64)]
 
 

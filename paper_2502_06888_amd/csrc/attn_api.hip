@@ -25,7 +25,7 @@ struct moe_attn_ctx {
     bool has_weights;
     hipEvent_t entry, finish, loaded[2], done[2], stored[2];
     bool profiling;
-    std::vector<hipEvent_t> ev;  // 6 per batch when profiling
+    std::vector<hipEvent_t> ev;  // kEv per batch when profiling
     moe_attn_profile prof;
     bool prof_valid;
     mutable std::string err;
@@ -34,6 +34,10 @@ struct moe_attn_ctx {
 namespace {
 
 thread_local std::string g_attn_error;
+
+// profiling events of one batch: load begin / end, store begin / end, then the 7 boundaries of
+// the 6 kernels on the compute stream
+constexpr int kEv = 11, kEvLoad = 0, kEvStore = 2, kEvKernel = 4;
 
 moe_status fail(const moe_attn_ctx* ctx, moe_status s, const char* fmt, ...) {
     char buf[512];
@@ -71,7 +75,7 @@ moe_status check_config(const moe_attn_config* c, std::string* why) {
         *why = m;
         return MOE_ERR_SHAPE;
     };
-    if (c->d_model <= 0 || c->d_model % 128 != 0) return bad("d_model must be a positive multiple of 128");
+    if (c->d_model <= 0 || c->d_model % 128 != 0 || c->d_model > 8192) return bad("d_model must be a multiple of 128 in 128..8192");
     if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return bad("head_dim must be 32, 64 or 128");
     if (c->n_kv_heads <= 0 || c->n_q_heads <= 0 || c->n_q_heads % c->n_kv_heads != 0) return bad("n_q_heads must be a multiple of n_kv_heads");
     const int g = c->n_q_heads / c->n_kv_heads;
@@ -269,7 +273,7 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
     const bool prof = ctx->profiling;
     if (prof) {
         ctx->prof_valid = false;
-        while (ctx->ev.size() < (size_t)n_batches * 6) {
+        while (ctx->ev.size() < (size_t)n_batches * kEv) {
             hipEvent_t e;
             HIP_TRY(ctx, hipEventCreate(&e));
             ctx->ev.push_back(e);
@@ -290,7 +294,7 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
         const moe_attn_batch& B = batches[b];
         const int buf = b & 1;
         if (used_done[buf]) HIP_TRY(ctx, hipStreamWaitEvent(ld, ctx->done[buf], 0));
-        if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * 6 + 0], ld));
+        if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvLoad], ld));
         if (B.kv_on_host && B.pos > 0) {
             const size_t width = (size_t)B.pos * hd * 2, height = (size_t)B.n_seq * c.n_kv_heads;
             HIP_TRY(ctx, hipMemcpy2DAsync(w + ctx->o_kv[buf][0], pitch, B.k_cache, pitch, width, height, hipMemcpyHostToDevice, ld));
@@ -301,7 +305,7 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
             HIP_TRY(ctx, hipMemcpyAsync(w + ctx->o_hin[buf], B.h_in, (size_t)B.n_seq * d * 2, hipMemcpyHostToDevice, ld));
             bytes_loaded += (int64_t)B.n_seq * d * 2;
         }
-        if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * 6 + 1], ld));
+        if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvLoad + 1], ld));
         HIP_TRY(ctx, hipEventRecord(ctx->loaded[buf], ld));
         return MOE_OK;
     };
@@ -317,7 +321,8 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
         }
         HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->loaded[buf], 0));
         if (used_stored[buf]) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->stored[buf], 0));
-        if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * 6 + 2], st));
+        auto mark = [&](int i) -> hipError_t { return prof ? hipEventRecord(ctx->ev[b * kEv + kEvKernel + i], st) : hipSuccess; };
+        HIP_TRY(ctx, mark(0));
         const void* x = B.h_on_host ? (const void*)(w + ctx->o_hin[buf]) : B.h_in;
         void* y = B.h_on_host ? (void*)(w + ctx->o_hout[buf]) : B.h_out;
         void* kc = B.kv_on_host ? (void*)(w + ctx->o_kv[buf][0]) : B.k_cache;
@@ -328,22 +333,27 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
         const int nrb = (B.n_seq + kRowBlk - 1) / kRowBlk;
         const int n_qkv = (int)(dq + 2 * dkv);
         launch_rmsnorm(st, x, w + ctx->o_g, B.n_seq, (int)d, c.rms_eps, w + ctx->o_ax);
+        HIP_TRY(ctx, mark(1));
         const int sp1 = pick_splits(nrb, (int)d, n_qkv);
         launch_proj(st, w + ctx->o_ax, w + ctx->o_wqkv, nrb, (int)d, n_qkv, sp1, part, ctx->part_stride);
+        HIP_TRY(ctx, mark(2));
         launch_qkv_finish(st, part, sp1, ctx->part_stride, ctx->dm, B.n_seq, B.pos, (const double*)(w + ctx->o_freq), q, kc, vc, new_rows);
+        HIP_TRY(ctx, mark(3));
         if (launch_attention(st, q, kc, vc, ctx->dm, B.n_seq, B.pos, w + ctx->o_ao) != 0)
             return fail(ctx, MOE_ERR_SHAPE, "no attention kernel for this head shape");
+        HIP_TRY(ctx, mark(4));
         const int sp2 = pick_splits(nrb, (int)dq, (int)d);
         launch_proj(st, w + ctx->o_ao, w + ctx->o_wo, nrb, (int)dq, (int)d, sp2, part, ctx->part_stride);
+        HIP_TRY(ctx, mark(5));
         launch_out_finish(st, part, sp2, ctx->part_stride, x, B.n_seq, (int)d, y);
         HIP_TRY(ctx, hipGetLastError());
-        if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * 6 + 3], st));
+        HIP_TRY(ctx, mark(6));
         HIP_TRY(ctx, hipEventRecord(ctx->done[buf], st));
         used_done[buf] = true;
 
         if (B.kv_on_host || B.h_on_host) {
             HIP_TRY(ctx, hipStreamWaitEvent(sv, ctx->done[buf], 0));
-            if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * 6 + 4], sv));
+            if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvStore], sv));
             if (B.kv_on_host) {
                 const size_t height = (size_t)B.n_seq * c.n_kv_heads, row = hd * 2;
                 const uint8_t* nr = w + ctx->o_new[buf];
@@ -355,12 +365,12 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
                 HIP_TRY(ctx, hipMemcpyAsync(B.h_out, w + ctx->o_hout[buf], (size_t)B.n_seq * d * 2, hipMemcpyDeviceToHost, sv));
                 bytes_stored += (int64_t)B.n_seq * d * 2;
             }
-            if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * 6 + 5], sv));
+            if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvStore + 1], sv));
             HIP_TRY(ctx, hipEventRecord(ctx->stored[buf], sv));
             used_stored[buf] = true;
         } else if (prof) {
-            HIP_TRY(ctx, hipEventRecord(ctx->ev[b * 6 + 4], sv));
-            HIP_TRY(ctx, hipEventRecord(ctx->ev[b * 6 + 5], sv));
+            HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvStore], sv));
+            HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvStore + 1], sv));
         }
     }
     for (int buf = 0; buf < 2; ++buf)
@@ -375,12 +385,17 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
         HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->entry, ctx->finish));
         p.wall_s = ms * 1e-3;
         for (int b = 0; b < n_batches; ++b) {
-            HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev[b * 6 + 0], ctx->ev[b * 6 + 1]));
+            hipEvent_t* e = &ctx->ev[(size_t)b * kEv];
+            HIP_TRY(ctx, hipEventElapsedTime(&ms, e[kEvLoad], e[kEvLoad + 1]));
             p.load_busy_s += ms * 1e-3;
-            HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev[b * 6 + 2], ctx->ev[b * 6 + 3]));
-            p.compute_busy_s += ms * 1e-3;
-            HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev[b * 6 + 4], ctx->ev[b * 6 + 5]));
+            HIP_TRY(ctx, hipEventElapsedTime(&ms, e[kEvStore], e[kEvStore + 1]));
             p.store_busy_s += ms * 1e-3;
+            HIP_TRY(ctx, hipEventElapsedTime(&ms, e[kEvKernel], e[kEvKernel + 6]));
+            p.compute_busy_s += ms * 1e-3;
+            for (int i = 0; i < 6; ++i) {
+                HIP_TRY(ctx, hipEventElapsedTime(&ms, e[kEvKernel + i], e[kEvKernel + i + 1]));
+                p.kernel_s[i] += ms * 1e-3;
+            }
         }
         p.bytes_loaded = bytes_loaded;
         p.bytes_stored = bytes_stored;

@@ -48,34 +48,54 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const u32x4* __restric
     out[i] = w[((size_t)row * K + k0) / 8];
 }
 
-// One wavefront per row.
+// One workgroup per row; a thread keeps its 16-byte pieces of the row in registers between the
+// sum of squares and the scaling (rows of up to 256 * 8 * kNormPieces elements).
+constexpr int kNormPieces = 4;
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const u32x4* __restrict__ x,
                                                       const u32x4* __restrict__ g, int n_seq, int d,
                                                       float eps, u32x4* __restrict__ a) {
-    const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= n_seq) return;
-    const int nch = d / 8, S = d / 16;
+    __shared__ float part[4];
+    const int row = blockIdx.x, nch = d / 8, S = d / 16;
     const u32x4* xr = x + (size_t)row * nch;
-    float ss = 0.f;
-    for (int c = lane; c < nch; c += 64) {
-        float f[8];
-        widen8(xr[c], f);
+    u32x4 xv[kNormPieces], gv[kNormPieces];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) ss = __builtin_fmaf(f[j], f[j], ss);
+    for (int i = 0; i < kNormPieces; ++i) {
+        const int c = threadIdx.x + i * 256;
+        if (c < nch) {
+            xv[i] = xr[c];
+            gv[i] = g[c];
+        }
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < kNormPieces; ++i) {
+        if (threadIdx.x + i * 256 < nch) {
+            float f[8];
+            widen8(xv[i], f);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ss = __builtin_fmaf(f[j], f[j], ss);
+        }
     }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    ss = (part[0] + part[1]) + (part[2] + part[3]);
     const float r = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = lane; c < nch; c += 64) {
-        float f[8], gg[8];
-        widen8(xr[c], f);
-        widen8(g[c], gg);
-        u32x4 o;
-        o.x = pack2(f[0] * r * gg[0], f[1] * r * gg[1]);
-        o.y = pack2(f[2] * r * gg[2], f[3] * r * gg[3]);
-        o.z = pack2(f[4] * r * gg[4], f[5] * r * gg[5]);
-        o.w = pack2(f[6] * r * gg[6], f[7] * r * gg[7]);
-        a[frag_piece(row, c, S)] = o;
+#pragma unroll
+    for (int i = 0; i < kNormPieces; ++i) {
+        const int c = threadIdx.x + i * 256;
+        if (c < nch) {
+            float f[8], gg[8];
+            widen8(xv[i], f);
+            widen8(gv[i], gg);
+            u32x4 o;
+            o.x = pack2(f[0] * r * gg[0], f[1] * r * gg[1]);
+            o.y = pack2(f[2] * r * gg[2], f[3] * r * gg[3]);
+            o.z = pack2(f[4] * r * gg[4], f[5] * r * gg[5]);
+            o.w = pack2(f[6] * r * gg[6], f[7] * r * gg[7]);
+            a[frag_piece(row, c, S)] = o;
+        }
     }
 }
 
@@ -133,30 +153,36 @@ __global__ __launch_bounds__(256) void proj_kernel(const u32x4* __restrict__ A,
         }
 }
 
-// One workgroup per sequence.
+// One thread per rotated pair of q or k, or per element of v, of one sequence.
 __global__ __launch_bounds__(256) void qkv_finish_kernel(const float* __restrict__ part, int splits,
                                                          int64_t split_stride, Dims dm, int n_seq,
                                                          int pos, const double* __restrict__ inv_freq,
                                                          float* __restrict__ q, uint16_t* __restrict__ kc,
                                                          uint16_t* __restrict__ vc,
                                                          uint16_t* __restrict__ new_rows) {
-    const int s = blockIdx.x, hd = dm.hd, half = hd / 2;
+    const int s = blockIdx.y, hd = dm.hd, half = hd / 2;
     const int dq = dm.Hq * hd, dkv = dm.Hkv * hd, n_out = dq + 2 * dkv;
+    const int n_pairs = (dm.Hq + dm.Hkv) * half;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_pairs + dkv) return;
     const float* row = part + (size_t)s * n_out;
     auto total = [&](int col) {
         float a = 0.f;
         for (int sp = 0; sp < splits; ++sp) a += row[(size_t)sp * split_stride + col];
         return a;
     };
-    const float qscale = 1.0f / sqrtf((float)hd);
-    for (int i = threadIdx.x; i < (dm.Hq + dm.Hkv) * half; i += 256) {
+    if (i < n_pairs) {
         const int h = i / half, j = i % half;  // heads 0..Hq-1 are q, then k
         const float a = total(h * hd + j), b = total(h * hd + j + half);
-        double sn, cs;
-        sincos((double)pos * inv_freq[j], &sn, &cs);
-        const float c = (float)cs, sf = (float)sn;
+        // angle reduced to [-pi, pi] in double, sine and cosine of the remainder in single
+        const double ang = (double)pos * inv_freq[j];
+        const double turns = rint(ang * 0.15915494309189535);
+        const float red = (float)(ang - turns * 6.283185307179586);
+        float sf, c;
+        sincosf(red, &sf, &c);
         const float r0 = a * c - b * sf, r1 = b * c + a * sf;
         if (h < dm.Hq) {
+            const float qscale = 1.0f / sqrtf((float)hd);
             q[((size_t)s * dm.Hq + h) * hd + j] = r0 * qscale;
             q[((size_t)s * dm.Hq + h) * hd + j + half] = r1 * qscale;
         } else {
@@ -171,10 +197,9 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(const float* __restrict
                 nr[j + half] = b1;
             }
         }
-    }
-    for (int i = threadIdx.x; i < dkv; i += 256) {
-        const int hk = i / hd, j = i % hd;
-        const uint16_t b = (uint16_t)bf_bits(total(dq + dkv + i));
+    } else {
+        const int e = i - n_pairs, hk = e / hd, j = e % hd;
+        const uint16_t b = (uint16_t)bf_bits(total(dq + dkv + e));
         vc[(((size_t)s * dm.Hkv + hk) * dm.max_len + pos) * hd + j] = b;
         if (new_rows != nullptr) new_rows[((size_t)(n_seq + s) * dm.Hkv + hk) * hd + j] = b;
     }
@@ -194,16 +219,19 @@ __device__ __forceinline__ void merge(Soft& a, float m2, float l2, const float (
 
 constexpr float kEmpty = -1.0e30f;  // finite stand-in for "no position seen yet"
 
-// One workgroup (4 wavefronts) per (sequence, key-value head); G query heads share the rows.
+// One workgroup (8 wavefronts) per (sequence, key-value head); G query heads share the rows.
 // A row of HD elements is read by HD/8 lanes (16 bytes each); a wavefront covers 512/HD rows per
-// load and keeps one running softmax per row slot, merged at the end.
+// load, issues the K and V loads of kChunk such row groups together, and keeps one running
+// softmax per row slot (rescaled once per chunk), merged at the end.
+constexpr int kAttnWaves = 8, kChunk = 4;
 template <int HD, int G>
-__global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restrict__ q,
-                                                          const u32x4* __restrict__ kc,
-                                                          const u32x4* __restrict__ vc, Dims dm,
-                                                          int n_seq, int pos, u32x4* __restrict__ o_frag) {
+__global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(const float* __restrict__ q,
+                                                                     const u32x4* __restrict__ kc,
+                                                                     const u32x4* __restrict__ vc,
+                                                                     Dims dm, int n_seq, int pos,
+                                                                     u32x4* __restrict__ o_frag) {
     constexpr int LPR = HD / 8, RPW = 64 / LPR;
-    __shared__ float sm[4][G * LPR][10];
+    __shared__ float sm[kAttnWaves][G * LPR][10];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s = blockIdx.x / dm.Hkv, hk = blockIdx.x % dm.Hkv;
     const int sub = lane % LPR, slot = lane / LPR;
@@ -223,29 +251,58 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
 #pragma unroll
         for (int j = 0; j < 8; ++j) st[g].acc[j] = 0.f;
     }
-#pragma unroll 2
-    for (int p0 = wave * RPW; p0 <= pos; p0 += 4 * RPW) {
-        const int p = p0 + slot;
-        const bool valid = p <= pos;
-        const int pc = valid ? p : pos;
-        float kf[8], vf[8];
-        widen8(K[(size_t)pc * LPR], kf);
-        widen8(V[(size_t)pc * LPR], vf);
+    for (int p0 = wave * RPW * kChunk; p0 <= pos; p0 += kAttnWaves * RPW * kChunk) {
+        u32x4 kraw[kChunk], vraw[kChunk];
+        bool valid[kChunk];
+#pragma unroll
+        for (int c = 0; c < kChunk; ++c) {
+            const int p = p0 + c * RPW + slot;
+            valid[c] = p <= pos;
+            const int pc = valid[c] ? p : pos;
+            kraw[c] = K[(size_t)pc * LPR];
+            vraw[c] = V[(size_t)pc * LPR];
+        }
+        float sc[G][kChunk];
+#pragma unroll
+        for (int c = 0; c < kChunk; ++c) {
+            float kf[8];
+            widen8(kraw[c], kf);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float dot = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) dot = __builtin_fmaf(qr[g][j], kf[j], dot);
+#pragma unroll
+                for (int m = 1; m < LPR; m <<= 1) dot += __shfl_xor(dot, m, 64);
+                sc[g][c] = valid[c] ? dot : kEmpty;
+            }
+        }
+        float pr[G][kChunk];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            float dot = 0.f;
+            float mn = st[g].m;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) dot = __builtin_fmaf(qr[g][j], kf[j], dot);
+            for (int c = 0; c < kChunk; ++c) mn = fmaxf(mn, sc[g][c]);
+            const float sa = expf(st[g].m - mn);
+            float add = 0.f;
 #pragma unroll
-            for (int m = 1; m < LPR; m <<= 1) dot += __shfl_xor(dot, m, 64);
-            if (valid) {
-                const float mn = fmaxf(st[g].m, dot);
-                const float sa = expf(st[g].m - mn), pr = expf(dot - mn);
-                st[g].l = st[g].l * sa + pr;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) st[g].acc[j] = st[g].acc[j] * sa + pr * vf[j];
-                st[g].m = mn;
+            for (int c = 0; c < kChunk; ++c) {
+                pr[g][c] = valid[c] ? expf(sc[g][c] - mn) : 0.f;
+                add += pr[g][c];
             }
+            st[g].l = st[g].l * sa + add;
+            st[g].m = mn;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) st[g].acc[j] *= sa;
+        }
+#pragma unroll
+        for (int c = 0; c < kChunk; ++c) {
+            float vf[8];
+            widen8(vraw[c], vf);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) st[g].acc[j] = __builtin_fmaf(pr[g][c], vf[j], st[g].acc[j]);
         }
     }
     // row slots of the wavefront
@@ -279,7 +336,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
 #pragma unroll
         for (int j = 0; j < 8; ++j) t.acc[j] = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < kAttnWaves; ++w) {
             const float* e = sm[w][threadIdx.x];
             float a2[8];
 #pragma unroll
@@ -328,7 +385,7 @@ void launch_pack_weight(hipStream_t st, const void* w, int rows, int K, void* ou
 
 void launch_rmsnorm(hipStream_t st, const void* x, const void* g, int n_seq, int d, float eps,
                     void* a_frag) {
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3((n_seq + 3) / 4), dim3(256), 0, st, (const u32x4*)x,
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(n_seq), dim3(256), 0, st, (const u32x4*)x,
                        (const u32x4*)g, n_seq, d, eps, (u32x4*)a_frag);
 }
 
@@ -361,7 +418,8 @@ void launch_proj(hipStream_t st, const void* a_frag, const void* w_frag, int row
 void launch_qkv_finish(hipStream_t st, const float* part, int splits, int64_t split_stride,
                        const Dims& dm, int n_seq, int pos, const double* inv_freq, float* q,
                        void* k_cache, void* v_cache, void* new_rows) {
-    hipLaunchKernelGGL(qkv_finish_kernel, dim3(n_seq), dim3(256), 0, st, part, splits, split_stride, dm,
+    const int items = (dm.Hq + dm.Hkv) * (dm.hd / 2) + dm.Hkv * dm.hd;
+    hipLaunchKernelGGL(qkv_finish_kernel, dim3((items + 255) / 256, n_seq), dim3(256), 0, st, part, splits, split_stride, dm,
                        n_seq, pos, inv_freq, q, (uint16_t*)k_cache, (uint16_t*)v_cache,
                        (uint16_t*)new_rows);
 }
@@ -369,7 +427,7 @@ void launch_qkv_finish(hipStream_t st, const float* part, int splits, int64_t sp
 template <int HD>
 static int launch_attention_hd(hipStream_t st, const float* q, const void* kc, const void* vc,
                                const Dims& dm, int n_seq, int pos, void* o_frag) {
-    const dim3 grid(n_seq * dm.Hkv), block(256);
+    const dim3 grid(n_seq * dm.Hkv), block(kAttnWaves * 64);
     const u32x4* K = (const u32x4*)kc;
     const u32x4* V = (const u32x4*)vc;
     u32x4* O = (u32x4*)o_frag;

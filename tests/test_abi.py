@@ -38,7 +38,7 @@ def test_library_exports_every_attention_symbol():
     assert sorted(A.ATTN_EXPORTS) == names
     assert C.sizeof(A.MoeAttnConfig) == 8 * 4
     assert C.sizeof(A.MoeAttnBatch) == 4 * 4 + 4 * 8
-    assert C.sizeof(A.MoeAttnProfile) == 6 * 8
+    assert C.sizeof(A.MoeAttnProfile) == 12 * 8
     # host-only sizing: Mixtral-8x7B attention with two staged caches of 64 x 8 x 576 x 128 bf16
     cfg = A.MoeAttnConfig(4096, 32, 8, 128, 64, 576, 1e6, 1e-5)
     need = A.workspace_bytes(cfg)
