@@ -32,7 +32,7 @@ int pick_row_tile(int row_blocks);                 // row blocks per wavefront (
 int pick_splits(int row_blocks, int K, int n_out); // split-K factor the launcher should be given
 
 // Sums the split-K partials of the fused q|k|v projection, rotates q and k to position pos,
-// writes q (fp32, [n_seq, Hq, hd], already divided by sqrt(hd)), the new k and v rows as bf16
+// writes q (fp32, [n_seq, Hq, hd], already multiplied by log2(e)/sqrt(hd)), the new k and v rows as bf16
 // into the caches at position pos and into `new_rows` ([2, n_seq, Hkv, hd], may be null).
 void launch_qkv_finish(hipStream_t st, const float* part, int splits, int64_t split_stride,
                        const Dims& dm, int n_seq, int pos, const double* inv_freq, float* q,

@@ -11,6 +11,8 @@
 // a fixed order by the kernel that consumes them.  The attention core is bound by the cache
 // bytes: one workgroup per (sequence, key-value head) reads every K and V row once, 16 bytes
 // per lane, all query heads of the group sharing each row.
+#include <type_traits>
+
 #include "attn_kernels.h"
 
 namespace kattn {
@@ -182,7 +184,8 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(const float* __restrict
         sincosf(red, &sf, &c);
         const float r0 = a * c - b * sf, r1 = b * c + a * sf;
         if (h < dm.Hq) {
-            const float qscale = 1.0f / sqrtf((float)hd);
+            // 1/sqrt(hd) and log2(e) folded in: the attention kernel works with base-2 exponentials
+            const float qscale = 1.4426950408889634f / sqrtf((float)hd);
             q[((size_t)s * dm.Hq + h) * hd + j] = r0 * qscale;
             q[((size_t)s * dm.Hq + h) * hd + j + half] = r1 * qscale;
         } else {
@@ -205,12 +208,27 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(const float* __restrict
     }
 }
 
-struct Soft {  // running softmax of one (query head, 8-element slice)
+// Sum over the LPR (4, 8 or 16) consecutive lanes that share a row, by data-parallel-primitive
+// adds: lane pairs, quad halves, then the mirrored half row and the mirrored row (after the
+// first two steps every quad holds one value, so a mirror acts as the xor exchange).
+template <int LPR>
+__device__ __forceinline__ float row_sum(float v) {
+    auto dpp = [](float x, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xF, 0xF, false));
+    };
+    v += dpp(v, std::integral_constant<int, 0xB1>{});                  // quad_perm [1,0,3,2]
+    v += dpp(v, std::integral_constant<int, 0x4E>{});                  // quad_perm [2,3,0,1]
+    if (LPR > 4) v += dpp(v, std::integral_constant<int, 0x141>{});    // row_half_mirror
+    if (LPR > 8) v += dpp(v, std::integral_constant<int, 0x140>{});    // row_mirror
+    return v;
+}
+
+struct Soft {  // running softmax (base 2) of one (query head, 8-element slice)
     float m, l, acc[8];
 };
 __device__ __forceinline__ void merge(Soft& a, float m2, float l2, const float (&acc2)[8]) {
     const float mn = fmaxf(a.m, m2);
-    const float sa = expf(a.m - mn), sb = expf(m2 - mn);
+    const float sa = __builtin_amdgcn_exp2f(a.m - mn), sb = __builtin_amdgcn_exp2f(m2 - mn);
     a.l = a.l * sa + l2 * sb;
 #pragma unroll
     for (int j = 0; j < 8; ++j) a.acc[j] = a.acc[j] * sa + acc2[j] * sb;
@@ -219,13 +237,13 @@ __device__ __forceinline__ void merge(Soft& a, float m2, float l2, const float (
 
 constexpr float kEmpty = -1.0e30f;  // finite stand-in for "no position seen yet"
 
-// One workgroup (8 wavefronts) per (sequence, key-value head); G query heads share the rows.
+// One workgroup (4 wavefronts, four workgroups per compute unit) per (sequence, key-value head); G query heads share the rows.
 // A row of HD elements is read by HD/8 lanes (16 bytes each); a wavefront covers 512/HD rows per
 // load, issues the K and V loads of kChunk such row groups together, and keeps one running
 // softmax per row slot (rescaled once per chunk), merged at the end.
-constexpr int kAttnWaves = 8, kChunk = 4;
+constexpr int kAttnWaves = 4, kChunk = 2;
 template <int HD, int G>
-__global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(const float* __restrict__ q,
+__global__ __launch_bounds__(kAttnWaves * 64, 4) void attn_decode_kernel(const float* __restrict__ q,
                                                                      const u32x4* __restrict__ kc,
                                                                      const u32x4* __restrict__ vc,
                                                                      Dims dm, int n_seq, int pos,
@@ -272,8 +290,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(const floa
                 float dot = 0.f;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) dot = __builtin_fmaf(qr[g][j], kf[j], dot);
-#pragma unroll
-                for (int m = 1; m < LPR; m <<= 1) dot += __shfl_xor(dot, m, 64);
+                dot = row_sum<LPR>(dot);
                 sc[g][c] = valid[c] ? dot : kEmpty;
             }
         }
@@ -283,11 +300,11 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(const floa
             float mn = st[g].m;
 #pragma unroll
             for (int c = 0; c < kChunk; ++c) mn = fmaxf(mn, sc[g][c]);
-            const float sa = expf(st[g].m - mn);
+            const float sa = __builtin_amdgcn_exp2f(st[g].m - mn);
             float add = 0.f;
 #pragma unroll
             for (int c = 0; c < kChunk; ++c) {
-                pr[g][c] = valid[c] ? expf(sc[g][c] - mn) : 0.f;
+                pr[g][c] = valid[c] ? __builtin_amdgcn_exp2f(sc[g][c] - mn) : 0.f;
                 add += pr[g][c];
             }
             st[g].l = st[g].l * sa + add;

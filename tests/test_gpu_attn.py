@@ -134,3 +134,42 @@ def test_argument_errors():
     with pytest.raises(B.MoeError) as ei:
         A.workspace_bytes(A.MoeAttnConfig(200, 8, 2, 32, 4, 16, 1e4, 1e-5))
     assert ei.value.status == B.MOE_ERR_SHAPE
+
+
+def test_full_size_sampled_sequences():
+    """Mixtral-8x7B attention shape in the launch configuration the benchmark times (64 sequences
+    per batch, 512 cached positions, caches streamed from pinned host memory); the oracle checks a
+    sample of sequences one by one (rows of a batch are independent of each other)."""
+    w = I.scaled(I.ATTN_WORKLOADS["attn_mixtral8x7b_decode"], batch_seqs=(64, 64, 37), batch_pos=(512, 512, 575))
+    ws = I.gen_attn_weights(w, 0)
+    hs = [I.gen_attn_hidden(w, 0, b) for b in range(w.n_batches)]
+    caches = [I.gen_kv_cache(w, 0, b) for b in range(w.n_batches)]
+    ctx = A.AttnContext(A.config_for(w), DEV)
+    ctx.set_weights(*[ws[n].to(DEV) for n in ("norm", "wq", "wk", "wv", "wo")])
+    batches = []
+    for b in range(w.n_batches):
+        h_in = hs[b].clone().pin_memory()
+        batches.append(A.AttnBatch(caches[b][0].clone().pin_memory(), caches[b][1].clone().pin_memory(),
+                                   h_in, torch.zeros_like(h_in).pin_memory(), w.batch_pos[b]))
+    ctx.forward_group(batches)
+    ctx.synchronize()
+    raw = {k: I.as_raw(v) for k, v in ws.items()}
+    for b, rows in ((0, [0, 31, 63]), (1, [32]), (2, [0, 36])):
+        pos = w.batch_pos[b]
+        y, k2, v2 = R.attn_decode(I.as_f32(hs[b])[rows], raw["norm"], raw["wq"], raw["wk"], raw["wv"], raw["wo"],
+                                  I.as_raw(caches[b][0])[rows], I.as_raw(caches[b][1])[rows], pos,
+                                  w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, w.rms_eps)
+        got = batches[b].h_out.to(torch.float64).numpy()[rows]
+        err = np.abs(got - y) - (1e-2 + 2e-2 * np.abs(y))
+        assert err.max() <= 0, f"batch {b}: output off by {err.max()} beyond tolerance"
+        for name, g, o in (("K", batches[b].k_cache, k2), ("V", batches[b].v_cache, v2)):
+            gr, orow = widen(I.as_raw(g)[rows][:, :, pos, :]), widen(o[:, :, pos, :])
+            err = np.abs(gr - orow) - (1e-2 + 2e-2 * np.abs(orow))
+            assert err.max() <= 0, f"batch {b}: new {name} row off by {err.max()} beyond tolerance"
+    # properties that hold for every sequence: cache rows before pos untouched, outputs finite
+    for b in range(w.n_batches):
+        pos = w.batch_pos[b]
+        assert torch.equal(batches[b].k_cache[:, :, :pos], caches[b][0][:, :, :pos])
+        assert torch.equal(batches[b].v_cache[:, :, :pos], caches[b][1][:, :, :pos])
+        assert torch.isfinite(batches[b].h_out.float()).all()
+    ctx.close()
