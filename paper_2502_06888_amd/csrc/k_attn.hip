@@ -10,7 +10,10 @@
 // reduction is split across wavefronts until the chip is full and the partial sums are added in
 // a fixed order by the kernel that consumes them.  The attention core is bound by the cache
 // bytes: one workgroup per (sequence, key-value head) reads every K and V row once, 16 bytes
-// per lane, all query heads of the group sharing each row.
+// per lane, all query heads of the group sharing each row.  Cache rows are read with
+// non-temporal loads and the weights with ordinary ones: the layer's weights (tens of MB) are
+// read again for every batch of the group and fit the last-level cache, the caches of a batch are
+// read once and would only evict them.
 #include <type_traits>
 
 #include "attn_kernels.h"
@@ -124,7 +127,7 @@ __global__ __launch_bounds__(256) void proj_kernel(const u32x4* __restrict__ A,
     auto load = [&](u32x4(&wb)[C], u32x4(&ab)[C][NB], int s) {
 #pragma unroll
         for (int j = 0; j < C; ++j) {
-            wb[j] = __builtin_nontemporal_load(wp + (size_t)(s + j) * 64);
+            wb[j] = wp[(size_t)(s + j) * 64];
 #pragma unroll
             for (int b = 0; b < NB; ++b) ab[j][b] = ap[((size_t)b * S + s + j) * 64];
         }
@@ -277,8 +280,8 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attn_decode_kernel(const f
             const int p = p0 + c * RPW + slot;
             valid[c] = p <= pos;
             const int pc = valid[c] ? p : pos;
-            kraw[c] = K[(size_t)pc * LPR];
-            vraw[c] = V[(size_t)pc * LPR];
+            kraw[c] = __builtin_nontemporal_load(K + (size_t)pc * LPR);
+            vraw[c] = __builtin_nontemporal_load(V + (size_t)pc * LPR);
         }
         float sc[G][kChunk];
 #pragma unroll
