@@ -287,27 +287,25 @@ def bench_streamed(w, args):
 
 
 def attn_cpu_baseline(w, ws, hs, caches, budget_s: float = 12.0):
-    """The attention oracle on the host cores, on the first sequences of batch 0."""
+    """The attention oracle on the host cores: whole batches of the workload, in order, until the
+    time budget is used or the workload is done."""
     from oracle import attn_ref, ref
     from paper_2502_06888_amd import inputs as I
     raw = {k: I.as_raw(v) for k, v in ws.items()}
-    x, kc, vc = I.as_f32(hs[0]), I.as_raw(caches[0][0]), I.as_raw(caches[0][1])
     cores = ref.num_threads()
-
-    def run(n):
+    done, t = 0, 0.0
+    for b in range(w.n_batches):
+        x, kc, vc = I.as_f32(hs[b]), I.as_raw(caches[b][0]), I.as_raw(caches[b][1])
         t0 = time.perf_counter()
-        attn_ref.attn_decode(x[:n], raw["norm"], raw["wq"], raw["wk"], raw["wv"], raw["wo"], kc[:n], vc[:n],
-                             w.batch_pos[0], w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, w.rms_eps)
-        return time.perf_counter() - t0
-
-    probe = min(w.batch_seqs[0], cores)
-    t_probe = run(probe)
-    n = int(min(w.batch_seqs[0], max(probe, probe * budget_s / max(t_probe, 1e-3))))
-    n = max(probe, n // cores * cores)
-    t = run(n) if n != probe else t_probe
-    return {"value": n / t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {n} of {w.batch_seqs[0]} sequences of batch 0 of the same workload "
-                      f"(fp64 attention layer over {w.batch_pos[0]} cached positions), {t:.1f} s"}
+        attn_ref.attn_decode(x, raw["norm"], raw["wq"], raw["wk"], raw["wv"], raw["wo"], kc, vc,
+                             w.batch_pos[b], w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, w.rms_eps)
+        t += time.perf_counter() - t0
+        done += w.batch_seqs[b]
+        if t > budget_s:
+            break
+    return {"value": done / t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {done} of {w.n_tokens} sequences (whole batches) of the same workload, fp64 "
+                      f"attention layer over {w.batch_pos[0]} cached positions, {t:.1f} s"}
 
 
 def bench_attention(w, args):
@@ -336,6 +334,13 @@ def bench_attention(w, args):
         batches.append(A.AttnBatch(k, v, h_in, h_out, w.batch_pos[b]))
     steps = min(args.steps, 20 if w.kv_on_host else 200)
     warmup = min(args.warmup, 2 if w.kv_on_host else 20)
+    if args.calibrate_copy:       # a kernel of known traffic for counter runs
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        del src, dst
+        torch.cuda.synchronize()
     for _ in range(max(1, warmup)):
         ctx.forward_group(batches)
     ctx.synchronize()
@@ -346,15 +351,21 @@ def bench_attention(w, args):
     ctx.synchronize()
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) / steps
-    ctx.set_profiling(True)                      # separate passes: event timing of streams and kernels
+    ctx.set_profiling(1)                         # separate passes: event timing of the streams
     prof = []
     for _ in range(3):
         ctx.forward_group(batches)
         prof.append(ctx.profile())
-    ctx.set_profiling(False)
     pr = min(prof, key=lambda p: p.wall_s)
+    ctx.set_profiling(8)                         # kernels: 8 launches between each event pair
+    prof = []
+    for _ in range(3):
+        ctx.forward_group(batches)
+        prof.append(ctx.profile())
+    ctx.set_profiling(0)
+    pk = min(prof, key=lambda p: p.kernel_s[3])
     names = ["rmsnorm", "qkv_proj", "qkv_finish", "attn_decode", "out_proj", "out_finish"]
-    kern_us = {n: pr.kernel_s[i] / w.n_batches * 1e6 for i, n in enumerate(names)}
+    kern_us = {n: pk.kernel_s[i] / w.n_batches * 1e6 for i, n in enumerate(names)}
     dq, dkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
     kv_bytes = sum(2 * w.batch_seqs[b] * dkv * (w.batch_pos[b] + 1) * 2 for b in range(w.n_batches))
     attn_bytes = kv_bytes + sum(w.batch_seqs[b] * dq * (4 + 2) for b in range(w.n_batches))
@@ -372,7 +383,7 @@ def bench_attention(w, args):
                      "store_busy_ms": pr.store_busy_s * 1e3, "compute_busy_ms": pr.compute_busy_s * 1e3,
                      "bytes_loaded": pr.bytes_loaded, "bytes_stored": pr.bytes_stored},
     }
-    t_attn = pr.kernel_s[3] / w.n_batches
+    t_attn = pk.kernel_s[3] / w.n_batches
     out["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel",
                        "achieved": attn_bytes / w.n_batches / t_attn / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": attn_bytes / w.n_batches / t_attn / 1e9 / HBM_PEAK_GBS,

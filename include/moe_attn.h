@@ -109,7 +109,11 @@ moe_status moe_attn_set_weights(moe_attn_ctx* ctx, const void* g, const void* wq
  */
 moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const moe_attn_batch* batches);
 
-/* Profiling: when on, every forward_group call times its streams with events and synchronises. */
+/* Profiling: when on (1..64), every forward_group call times its streams with events and
+ * synchronises.  With on = n > 1 each kernel but the last (the residual, which may work in place)
+ * is launched n times back to back between its two events, same inputs and same outputs, so that
+ * kernel_s is free of the event pair's own cost; wall_s and compute_busy_s then include the
+ * repeats. */
 moe_status moe_attn_set_profiling(moe_attn_ctx* ctx, int32_t on);
 moe_status moe_attn_get_profile(moe_attn_ctx* ctx, moe_attn_profile* out);
 

@@ -114,8 +114,9 @@ class AttnContext:
                                   b.v_cache.data_ptr(), b.h_in.data_ptr(), b.h_out.data_ptr())
         _check(self.lib.moe_attn_forward_group(self.h, len(batches), arr), self.h)
 
-    def set_profiling(self, on: bool):
-        _check(self.lib.moe_attn_set_profiling(self.h, 1 if on else 0), self.h)
+    def set_profiling(self, level: int):
+        """0 off; n >= 1 on, kernels repeated n times between their events."""
+        _check(self.lib.moe_attn_set_profiling(self.h, int(level)), self.h)
 
     def profile(self) -> MoeAttnProfile:
         out = MoeAttnProfile()

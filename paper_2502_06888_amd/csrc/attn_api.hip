@@ -24,7 +24,7 @@ struct moe_attn_ctx {
     int64_t part_stride;
     bool has_weights;
     hipEvent_t entry, finish, loaded[2], done[2], stored[2];
-    bool profiling;
+    int profiling;  // 0 off, n >= 1: kernels launched n times between their events
     std::vector<hipEvent_t> ev;  // kEv per batch when profiling
     moe_attn_profile prof;
     bool prof_valid;
@@ -240,7 +240,8 @@ moe_status moe_attn_set_weights(moe_attn_ctx* ctx, const void* g, const void* wq
 
 moe_status moe_attn_set_profiling(moe_attn_ctx* ctx, int32_t on) {
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
-    ctx->profiling = on != 0;
+    if (on < 0 || on > 64) return fail(ctx, MOE_ERR_INVALID_ARG, "profiling level %d outside 0..64", on);
+    ctx->profiling = on;
     ctx->prof_valid = false;
     return MOE_OK;
 }
@@ -270,7 +271,8 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
             return fail(ctx, B.h_on_host ? MOE_ERR_NOT_PINNED : MOE_ERR_INVALID_ARG, "batch %d: hidden-state pointers are not %s memory", b, B.h_on_host ? "pinned host" : "device");
     }
     if (n_batches == 0) return MOE_OK;
-    const bool prof = ctx->profiling;
+    const bool prof = ctx->profiling > 0;
+    const int reps = prof ? ctx->profiling : 1;
     if (prof) {
         ctx->prof_valid = false;
         while (ctx->ev.size() < (size_t)n_batches * kEv) {
@@ -332,18 +334,19 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
         float* q = (float*)(w + ctx->o_q);
         const int nrb = (B.n_seq + kRowBlk - 1) / kRowBlk;
         const int n_qkv = (int)(dq + 2 * dkv);
-        launch_rmsnorm(st, x, w + ctx->o_g, B.n_seq, (int)d, c.rms_eps, w + ctx->o_ax);
+        for (int r = 0; r < reps; ++r) launch_rmsnorm(st, x, w + ctx->o_g, B.n_seq, (int)d, c.rms_eps, w + ctx->o_ax);
         HIP_TRY(ctx, mark(1));
         const int sp1 = pick_splits(nrb, (int)d, n_qkv);
-        launch_proj(st, w + ctx->o_ax, w + ctx->o_wqkv, nrb, (int)d, n_qkv, sp1, part, ctx->part_stride);
+        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ax, w + ctx->o_wqkv, nrb, (int)d, n_qkv, sp1, part, ctx->part_stride);
         HIP_TRY(ctx, mark(2));
-        launch_qkv_finish(st, part, sp1, ctx->part_stride, ctx->dm, B.n_seq, B.pos, (const double*)(w + ctx->o_freq), q, kc, vc, new_rows);
+        for (int r = 0; r < reps; ++r) launch_qkv_finish(st, part, sp1, ctx->part_stride, ctx->dm, B.n_seq, B.pos, (const double*)(w + ctx->o_freq), q, kc, vc, new_rows);
         HIP_TRY(ctx, mark(3));
-        if (launch_attention(st, q, kc, vc, ctx->dm, B.n_seq, B.pos, w + ctx->o_ao) != 0)
-            return fail(ctx, MOE_ERR_SHAPE, "no attention kernel for this head shape");
+        for (int r = 0; r < reps; ++r)
+            if (launch_attention(st, q, kc, vc, ctx->dm, B.n_seq, B.pos, w + ctx->o_ao) != 0)
+                return fail(ctx, MOE_ERR_SHAPE, "no attention kernel for this head shape");
         HIP_TRY(ctx, mark(4));
         const int sp2 = pick_splits(nrb, (int)dq, (int)d);
-        launch_proj(st, w + ctx->o_ao, w + ctx->o_wo, nrb, (int)dq, (int)d, sp2, part, ctx->part_stride);
+        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ao, w + ctx->o_wo, nrb, (int)dq, (int)d, sp2, part, ctx->part_stride);
         HIP_TRY(ctx, mark(5));
         launch_out_finish(st, part, sp2, ctx->part_stride, x, B.n_seq, (int)d, y);
         HIP_TRY(ctx, hipGetLastError());
@@ -394,7 +397,7 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
             p.compute_busy_s += ms * 1e-3;
             for (int i = 0; i < 6; ++i) {
                 HIP_TRY(ctx, hipEventElapsedTime(&ms, e[kEvKernel + i], e[kEvKernel + i + 1]));
-                p.kernel_s[i] += ms * 1e-3;
+                p.kernel_s[i] += ms * 1e-3 / (i < 5 ? reps : 1);
             }
         }
         p.bytes_loaded = bytes_loaded;
