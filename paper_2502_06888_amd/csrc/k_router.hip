@@ -21,10 +21,12 @@ struct Chunk;
 template <>
 struct Chunk<float> {
     static constexpr int V = 4;
-    static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
-        float4 q = *reinterpret_cast<const float4*>(p);
+    typedef float4 Raw;
+    static __device__ __forceinline__ Raw raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    static __device__ __forceinline__ void widen(const Raw q, float (&v)[4]) {
         v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
     }
+    static __device__ __forceinline__ void load(const float* p, float (&v)[4]) { widen(raw(p), v); }
 };
 
 struct bf16raw {
@@ -34,8 +36,10 @@ struct bf16raw {
 template <>
 struct Chunk<bf16raw> {
     static constexpr int V = 8;
-    static __device__ __forceinline__ void load(const bf16raw* p, float (&v)[8]) {
-        uint4 q = *reinterpret_cast<const uint4*>(p);
+    typedef uint4 Raw;
+    static __device__ __forceinline__ Raw raw(const bf16raw* p) { return *reinterpret_cast<const uint4*>(p); }
+    static __device__ __forceinline__ void load(const bf16raw* p, float (&v)[8]) { widen(raw(p), v); }
+    static __device__ __forceinline__ void widen(const Raw q, float (&v)[8]) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -54,6 +58,66 @@ __device__ __forceinline__ bool better(const Cand& a, const Cand& b) {
     if (a.e < 0) return false;
     if (b.e < 0) return true;
     return a.v > b.v || (a.v == b.v && a.e < b.e);
+}
+
+// Top-k by (logit desc, index asc) and the routing weights of one token; every lane holds in
+// mine[s] the logit of expert lane + 64 s.  One wavefront.
+__device__ __forceinline__ void select_and_write(const float (&mine)[4], int lane, int t, int E, int k,
+                                                 int renorm, int32_t* __restrict__ idx_out,
+                                                 float* __restrict__ w_out) {
+    bool taken[4] = {false, false, false, false};
+    float selv[kMaxTopK];
+    int sele[kMaxTopK];
+#pragma unroll
+    for (int j = 0; j < kMaxTopK; ++j) {
+        selv[j] = 0.f;
+        sele[j] = 0;
+        if (j < k) {
+            Cand best{0.f, -1};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int e = lane + 64 * s;
+                Cand c{mine[s], (e < E && !taken[s]) ? e : -1};
+                if (better(c, best)) best = c;
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) {
+                Cand o{__shfl_xor(best.v, m, 64), __shfl_xor(best.e, m, 64)};
+                if (better(o, best)) best = o;
+            }
+            best.v = __shfl(best.v, 0, 64);
+            best.e = __shfl(best.e, 0, 64);
+            selv[j] = best.v;
+            sele[j] = best.e;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                if (best.e == lane + 64 * s) taken[s] = true;
+        }
+    }
+
+    // routing weights: softmax over all experts, renormalised over the winners (or not)
+    const float mx = selv[0];
+    float den = 0.f;
+    if (renorm) {
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j)
+            if (j < k) den += expf(selv[j] - mx);
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            if (lane + 64 * s < E) den += expf(mine[s] - mx);
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) den += __shfl_xor(den, m, 64);
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j) {
+            if (j < k) {
+                idx_out[(size_t)t * k + j] = sele[j];
+                w_out[(size_t)t * k + j] = expf(selv[j] - mx) / den;
+            }
+        }
+    }
 }
 
 template <typename T>
@@ -126,60 +190,75 @@ __global__ __launch_bounds__(kRouterWaves * 64) void router_kernel(
         }
     }
 
-    // top-k by (logit desc, index asc): k rounds of a wavefront arg-max
-    bool taken[4] = {false, false, false, false};
-    float selv[kMaxTopK];
-    int sele[kMaxTopK];
-#pragma unroll
-    for (int j = 0; j < kMaxTopK; ++j) {
-        selv[j] = 0.f;
-        sele[j] = 0;
-        if (j < k) {
-            Cand best{0.f, -1};
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int e = lane + 64 * s;
-                Cand c{mine[s], (e < E && !taken[s]) ? e : -1};
-                if (better(c, best)) best = c;
-            }
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) {
-                Cand o{__shfl_xor(best.v, m, 64), __shfl_xor(best.e, m, 64)};
-                if (better(o, best)) best = o;
-            }
-            best.v = __shfl(best.v, 0, 64);
-            best.e = __shfl(best.e, 0, 64);
-            selv[j] = best.v;
-            sele[j] = best.e;
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                if (best.e == lane + 64 * s) taken[s] = true;
-        }
-    }
+    select_and_write(mine, lane, t, E, k, renorm, idx_out, w_out);
+}
 
-    // routing weights: softmax over all experts, renormalised over the winners (or not)
-    const float mx = selv[0];
-    float den = 0.f;
-    if (renorm) {
+
+// The same arithmetic with one workgroup per token: wavefront w scores experts w*kSG, w*kSG+1,
+// then (w+kSW)*kSG, ...; the token's row stays in registers (at most kSC vectors per lane) and
+// the loads of a group's gate rows are all in flight together.  Logits meet in LDS and the first
+// wavefront selects.  Used for small batch groups, where one wavefront per token leaves most
+// of the chip idle.  The summation order per (token, expert) is the one stated at the top.
+constexpr int kSW = 4;   // wavefronts per token
+constexpr int kSG = 2;   // experts scored together by a wavefront
+constexpr int kSC = 16;  // vectors of the row per lane, at most (template parameter SC: 2, 8 or 16)
+template <typename T, int SC>
+__global__ __launch_bounds__(kSW * 64) void router_split_kernel(
+    const T* __restrict__ X, const T* __restrict__ Wg, int N, int d, int E, int k, int renorm,
+    float* __restrict__ logits_out, int32_t* __restrict__ idx_out, float* __restrict__ w_out) {
+    constexpr int V = Chunk<T>::V;
+    __shared__ float slog[kMaxExperts];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x;
+    const int nchunk = d / V;
+    const int cpl = (nchunk + 63) / 64;
+    const T* xrow = X + (size_t)t * d;
+    typename Chunk<T>::Raw xr[SC];  // the token's row, as stored; lanes past the end re-read the last vector
 #pragma unroll
-        for (int j = 0; j < kMaxTopK; ++j)
-            if (j < k) den += expf(selv[j] - mx);
-    } else {
+    for (int q = 0; q < SC; ++q)
+        if (q < cpl) xr[q] = Chunk<T>::raw(xrow + (size_t)min(q * 64 + lane, nchunk - 1) * V);
+    for (int e0 = wave * kSG; e0 < E; e0 += kSW * kSG) {
+        // all gate vectors of the group are requested before the first multiply-add
+        typename Chunk<T>::Raw wr[kSG][SC];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            if (lane + 64 * s < E) den += expf(mine[s] - mx);
+        for (int j = 0; j < kSG; ++j) {
+            const int e = min(e0 + j, E - 1);  // clamped: the result of a surplus expert is dropped
 #pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) den += __shfl_xor(den, m, 64);
-    }
-    if (lane == 0) {
+            for (int q = 0; q < SC; ++q)
+                if (q < cpl) wr[j][q] = Chunk<T>::raw(Wg + (size_t)e * d + (size_t)min(q * 64 + lane, nchunk - 1) * V);
+        }
+        float acc[kSG];
 #pragma unroll
-        for (int j = 0; j < kMaxTopK; ++j) {
-            if (j < k) {
-                idx_out[(size_t)t * k + j] = sele[j];
-                w_out[(size_t)t * k + j] = expf(selv[j] - mx) / den;
+        for (int j = 0; j < kSG; ++j) {
+            acc[j] = 0.f;
+#pragma unroll
+            for (int q = 0; q < SC; ++q) {
+                if (q < cpl && q * 64 + lane < nchunk) {
+                    float wv[V], xv[V];
+                    Chunk<T>::widen(wr[j][q], wv);
+                    Chunk<T>::widen(xr[q], xv);
+#pragma unroll
+                    for (int i = 0; i < V; ++i) acc[j] = __builtin_fmaf(xv[i], wv[i], acc[j]);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kSG; ++j) {
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) acc[j] = acc[j] + __shfl_xor(acc[j], m, 64);
+            const int e = e0 + j;
+            if (e < E && lane == 0) {
+                slog[e] = acc[j];
+                if (logits_out != nullptr) logits_out[(size_t)t * E + e] = acc[j];
             }
         }
     }
+    __syncthreads();
+    if (wave != 0) return;
+    float mine[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) mine[s4] = lane + 64 * s4 < E ? slog[lane + 64 * s4] : 0.f;
+    select_and_write(mine, lane, t, E, k, renorm, idx_out, w_out);
 }
 
 }  // namespace
@@ -187,6 +266,21 @@ __global__ __launch_bounds__(kRouterWaves * 64) void router_kernel(
 void launch_router(hipStream_t st, int dtype, const void* x, const void* wg, const Shape& s,
                    float* logits_out, int32_t* idx_out, float* w_out) {
     if (s.N <= 0) return;
+    const int V = dtype == 0 ? 4 : 8;
+    const int cpl = (s.d / V + 63) / 64;
+    if (s.N <= 2048 && cpl <= kSC) {  // small batch group: one workgroup per token
+        dim3 grid(s.N), block(kSW * 64);
+#define KMOE_SPLIT(T, SC)                                                                              \
+    hipLaunchKernelGGL((router_split_kernel<T, SC>), grid, block, 0, st, (const T*)x, (const T*)wg, s.N, \
+                       s.d, s.E, s.k, s.renorm, logits_out, idx_out, w_out)
+        if (dtype == 0) {
+            if (cpl <= 2) KMOE_SPLIT(float, 2); else if (cpl <= 8) KMOE_SPLIT(float, 8); else KMOE_SPLIT(float, 16);
+        } else {
+            if (cpl <= 2) KMOE_SPLIT(bf16raw, 2); else if (cpl <= 8) KMOE_SPLIT(bf16raw, 8); else KMOE_SPLIT(bf16raw, 16);
+        }
+#undef KMOE_SPLIT
+        return;
+    }
     dim3 grid((s.N + kRouterWaves - 1) / kRouterWaves), block(kRouterWaves * 64);
     if (dtype == 0) {
         hipLaunchKernelGGL(router_kernel<float>, grid, block, 0, st, (const float*)x,
