@@ -41,6 +41,7 @@ typedef struct {
     int32_t head_dim;   /* 32, 64 or 128; n_q_heads*head_dim a multiple of 128 */
     int32_t max_seqs;   /* sequences per batch, at most */
     int32_t max_len;    /* capacity of every cache, in positions */
+    int32_t n_layers;   /* attention layers whose weights one context holds (>= 1) */
     float rope_theta;
     float rms_eps;
 } moe_attn_config;
@@ -71,8 +72,9 @@ typedef struct {
 } moe_attn_profile;
 
 /*
- * moe_attn_workspace_bytes -- host only, pure.  Device scratch a context needs (packed weights,
- * the two cache staging buffers, activations and partial sums).  MOE_ERR_SHAPE on unsupported
+ * moe_attn_workspace_bytes -- host only, pure.  Device scratch a context needs (the packed
+ * weights of n_layers layers, the two cache staging buffers shared by all layers, activations
+ * and partial sums).  MOE_ERR_SHAPE on unsupported
  * sizes, MOE_ERR_INVALID_ARG on null.
  */
 moe_status moe_attn_workspace_bytes(const moe_attn_config* cfg, int64_t* bytes_out);
@@ -89,25 +91,27 @@ moe_status moe_attn_create(const moe_attn_config* cfg, void* workspace_dev, int6
 void moe_attn_destroy(moe_attn_ctx* ctx);
 
 /*
- * moe_attn_set_weights -- packs the layer's weights into the workspace (device resident; the
+ * moe_attn_set_weights -- packs the weights of `layer` into the workspace (device resident; the
  * weight stream of Algorithm 1, load(layers[j+1]), is the caller's: call this for the next
  * attention layer while the expert layer computes).  Pointers are device addresses unless
  * on_host != 0 (then plain or pinned host memory; the call copies synchronously).  Enqueued on
  * the compute stream.
  */
-moe_status moe_attn_set_weights(moe_attn_ctx* ctx, const void* g, const void* wq, const void* wk,
-                                const void* wv, const void* wo, int32_t on_host);
+moe_status moe_attn_set_weights(moe_attn_ctx* ctx, int32_t layer, const void* g, const void* wq,
+                                const void* wk, const void* wv, const void* wo, int32_t on_host);
 
 /*
- * moe_attn_forward_group -- Algorithm 1, non-expert branch, for one decoding step: for batch
+ * moe_attn_forward_group -- Algorithm 1, non-expert branch, for one decoding step of `layer`
+ * (the caches of a batch are that layer's): for batch
  * b = 0..n_batches-1, wait for b's h and c on the load stream, start loading batch b+1 into
  * the other staging buffer, compute b, then store b's new cache row and hidden state on the
  * store stream.  Returns after enqueueing; results are valid once the compute stream is
  * synchronised (it is made to wait for the last store).  The batches array is read during the
- * call only.  Errors: MOE_ERR_INVALID_ARG (null, pos or n_seq out of range), MOE_ERR_STATE (no
- * weights), MOE_ERR_NOT_PINNED (a host pointer that is not pinned), MOE_ERR_HIP.
+ * call only.  Errors: MOE_ERR_INVALID_ARG (null, layer, pos or n_seq out of range), MOE_ERR_STATE
+ * (the layer has no weights), MOE_ERR_NOT_PINNED (a host pointer that is not pinned), MOE_ERR_HIP.
  */
-moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const moe_attn_batch* batches);
+moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_batches,
+                                  const moe_attn_batch* batches);
 
 /* Profiling: when on (1..64), every forward_group call times its streams with events and
  * synchronises.  With on = n > 1 each kernel but the last (the residual, which may work in place)

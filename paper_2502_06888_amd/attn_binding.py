@@ -19,7 +19,7 @@ ATTN_EXPORTS = ["moe_attn_workspace_bytes", "moe_attn_create", "moe_attn_destroy
 class MoeAttnConfig(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("max_seqs", C.c_int32), ("max_len", C.c_int32),
-                ("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+                ("n_layers", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float)]
 
 
 class MoeAttnBatch(C.Structure):
@@ -48,8 +48,8 @@ def load_library():
         lib.moe_attn_create.argtypes = [P(MoeAttnConfig), vp, i64, vp, vp, vp, P(vp)]
         lib.moe_attn_destroy.argtypes = [vp]
         lib.moe_attn_destroy.restype = None
-        lib.moe_attn_set_weights.argtypes = [vp] * 6 + [i32]
-        lib.moe_attn_forward_group.argtypes = [vp, i32, P(MoeAttnBatch)]
+        lib.moe_attn_set_weights.argtypes = [vp, i32] + [vp] * 5 + [i32]
+        lib.moe_attn_forward_group.argtypes = [vp, i32, i32, P(MoeAttnBatch)]
         lib.moe_attn_set_profiling.argtypes = [vp, i32]
         lib.moe_attn_get_profile.argtypes = [vp, P(MoeAttnProfile)]
         lib.moe_attn_last_error.argtypes = [vp]
@@ -101,18 +101,18 @@ class AttnContext:
                                         self.store.cuda_stream, C.byref(h)))
         self.h = h
 
-    def set_weights(self, g, wq, wk, wv, wo):
+    def set_weights(self, g, wq, wk, wv, wo, layer: int = 0):
         on_host = 0 if g.is_cuda else 1
-        _check(self.lib.moe_attn_set_weights(self.h, g.data_ptr(), wq.data_ptr(), wk.data_ptr(),
+        _check(self.lib.moe_attn_set_weights(self.h, layer, g.data_ptr(), wq.data_ptr(), wk.data_ptr(),
                                              wv.data_ptr(), wo.data_ptr(), on_host), self.h)
 
-    def forward_group(self, batches: Sequence[AttnBatch]):
+    def forward_group(self, batches: Sequence[AttnBatch], layer: int = 0):
         arr = (MoeAttnBatch * max(1, len(batches)))()
         for i, b in enumerate(batches):
             arr[i] = MoeAttnBatch(b.h_in.shape[0], b.pos, 0 if b.k_cache.is_cuda else 1,
                                   0 if b.h_in.is_cuda else 1, b.k_cache.data_ptr(),
                                   b.v_cache.data_ptr(), b.h_in.data_ptr(), b.h_out.data_ptr())
-        _check(self.lib.moe_attn_forward_group(self.h, len(batches), arr), self.h)
+        _check(self.lib.moe_attn_forward_group(self.h, layer, len(batches), arr), self.h)
 
     def set_profiling(self, level: int):
         """0 off; n >= 1 on, kernels repeated n times between their events."""
@@ -138,7 +138,7 @@ class AttnContext:
             pass
 
 
-def config_for(w, max_seqs=None) -> MoeAttnConfig:
+def config_for(w, max_seqs=None, n_layers: int = 1) -> MoeAttnConfig:
     """MoeAttnConfig of an ``inputs.AttnWorkload``."""
     return MoeAttnConfig(w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim,
-                         max_seqs or max(w.batch_seqs), w.max_len, w.rope_theta, w.rms_eps)
+                         max_seqs or max(w.batch_seqs), w.max_len, n_layers, w.rope_theta, w.rms_eps)

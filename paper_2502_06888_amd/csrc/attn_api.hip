@@ -19,10 +19,10 @@ struct moe_attn_ctx {
     hipStream_t compute, load, store;
     uint8_t* ws;
     // offsets into the workspace
-    size_t o_wqkv, o_wo, o_g, o_freq, o_ax, o_ao, o_part, o_q, o_kv[2][2], o_new[2], o_hin[2], o_hout[2], total;
+    size_t o_wqkv, o_wo, o_g, layer_stride, o_freq, o_ax, o_ao, o_part, o_q, o_kv[2][2], o_new[2], o_hin[2], o_hout[2], total;
     int rows_alloc;   // rows the activation buffers hold (multiple of 128)
     int64_t part_stride;
-    bool has_weights;
+    std::vector<char> has_weights;  // per layer
     hipEvent_t entry, finish, loaded[2], done[2], stored[2];
     int profiling;  // 0 off, n >= 1: kernels launched n times between their events
     std::vector<hipEvent_t> ev;  // kEv per batch when profiling
@@ -85,6 +85,7 @@ moe_status check_config(const moe_attn_config* c, std::string* why) {
     if (c->max_seqs <= 0 || c->max_seqs > 4096) return bad("max_seqs must be in 1..4096");
     if (c->max_len <= 0 || c->max_len > (1 << 20)) return bad("max_len must be in 1..2^20");
     if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return bad("rope_theta must be > 0 and rms_eps >= 0");
+    if (c->n_layers < 1 || c->n_layers > 1024) return bad("n_layers must be in 1..1024");
     return MOE_OK;
 }
 
@@ -99,9 +100,11 @@ void layout(moe_attn_ctx* c) {
         o += up256(bytes);
         return at;
     };
-    c->o_wqkv = take(n_qkv * d * 2);
+    c->o_wqkv = take(n_qkv * d * 2);  // layer 0; layer l at + l * layer_stride
     c->o_wo = take(d * dq * 2);
     c->o_g = take(d * 2);
+    c->layer_stride = o;
+    o *= (size_t)g.n_layers;
     c->o_freq = take((size_t)g.head_dim / 2 * sizeof(double));
     c->o_ax = take((size_t)c->rows_alloc * d * 2);
     c->o_ao = take((size_t)c->rows_alloc * dq * 2);
@@ -164,6 +167,7 @@ moe_status moe_attn_create(const moe_attn_config* cfg, void* workspace_dev, int6
         return fail(nullptr, MOE_ERR_INVALID_ARG, "workspace is not device memory");
     }
     c->ws = (uint8_t*)workspace_dev;
+    c->has_weights.assign(cfg->n_layers, 0);
     c->compute = (hipStream_t)compute_stream;
     c->load = (hipStream_t)load_stream;
     c->store = (hipStream_t)store_stream;
@@ -201,9 +205,11 @@ void moe_attn_destroy(moe_attn_ctx* c) {
     delete c;
 }
 
-moe_status moe_attn_set_weights(moe_attn_ctx* ctx, const void* g, const void* wq, const void* wk,
-                                const void* wv, const void* wo, int32_t on_host) {
+moe_status moe_attn_set_weights(moe_attn_ctx* ctx, int32_t layer, const void* g, const void* wq,
+                                const void* wk, const void* wv, const void* wo, int32_t on_host) {
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d outside 0..%d", layer, ctx->cfg.n_layers - 1);
+    const size_t lo = (size_t)layer * ctx->layer_stride;
     if (!g || !wq || !wk || !wv || !wo) return fail(ctx, MOE_ERR_INVALID_ARG, "null weight pointer");
     const moe_attn_config& c = ctx->cfg;
     const size_t d = c.d_model, dq = (size_t)c.n_q_heads * c.head_dim, dkv = (size_t)c.n_kv_heads * c.head_dim;
@@ -215,10 +221,10 @@ moe_status moe_attn_set_weights(moe_attn_ctx* ctx, const void* g, const void* wq
         const void* src;
         size_t rows, K;
         size_t dst_off;
-    } items[4] = {{wq, dq, d, ctx->o_wqkv},
-                  {wk, dkv, d, ctx->o_wqkv + dq * d * 2},
-                  {wv, dkv, d, ctx->o_wqkv + (dq + dkv) * d * 2},
-                  {wo, d, dq, ctx->o_wo}};
+    } items[4] = {{wq, dq, d, lo + ctx->o_wqkv},
+                  {wk, dkv, d, lo + ctx->o_wqkv + dq * d * 2},
+                  {wv, dkv, d, lo + ctx->o_wqkv + (dq + dkv) * d * 2},
+                  {wo, d, dq, lo + ctx->o_wo}};
     for (const Item& it : items) {
         const size_t bytes = it.rows * it.K * 2;
         const void* src = it.src;
@@ -233,8 +239,8 @@ moe_status moe_attn_set_weights(moe_attn_ctx* ctx, const void* g, const void* wq
         HIP_TRY(ctx, hipGetLastError());
         HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
     }
-    HIP_TRY(ctx, hipMemcpy(ctx->ws + ctx->o_g, g, d * 2, on_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice));
-    ctx->has_weights = true;
+    HIP_TRY(ctx, hipMemcpy(ctx->ws + lo + ctx->o_g, g, d * 2, on_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice));
+    ctx->has_weights[layer] = 1;
     return MOE_OK;
 }
 
@@ -253,10 +259,13 @@ moe_status moe_attn_get_profile(moe_attn_ctx* ctx, moe_attn_profile* out) {
     return MOE_OK;
 }
 
-moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const moe_attn_batch* batches) {
+moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_batches,
+                                  const moe_attn_batch* batches) {
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
     if (!batches || n_batches < 0) return fail(ctx, MOE_ERR_INVALID_ARG, "bad batches argument");
-    if (!ctx->has_weights) return fail(ctx, MOE_ERR_STATE, "moe_attn_set_weights has not been called");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d outside 0..%d", layer, ctx->cfg.n_layers - 1);
+    if (!ctx->has_weights[layer]) return fail(ctx, MOE_ERR_STATE, "moe_attn_set_weights has not been called for layer %d", layer);
+    const size_t lo = (size_t)layer * ctx->layer_stride;
     const moe_attn_config& c = ctx->cfg;
     const size_t d = c.d_model, hd = c.head_dim, dkv = (size_t)c.n_kv_heads * hd, dq = (size_t)c.n_q_heads * hd;
     for (int b = 0; b < n_batches; ++b) {
@@ -334,10 +343,10 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
         float* q = (float*)(w + ctx->o_q);
         const int nrb = (B.n_seq + kRowBlk - 1) / kRowBlk;
         const int n_qkv = (int)(dq + 2 * dkv);
-        for (int r = 0; r < reps; ++r) launch_rmsnorm(st, x, w + ctx->o_g, B.n_seq, (int)d, c.rms_eps, w + ctx->o_ax);
+        for (int r = 0; r < reps; ++r) launch_rmsnorm(st, x, w + lo + ctx->o_g, B.n_seq, (int)d, c.rms_eps, w + ctx->o_ax);
         HIP_TRY(ctx, mark(1));
         const int sp1 = pick_splits(nrb, (int)d, n_qkv);
-        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ax, w + ctx->o_wqkv, nrb, (int)d, n_qkv, sp1, part, ctx->part_stride);
+        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ax, w + lo + ctx->o_wqkv, nrb, (int)d, n_qkv, sp1, part, ctx->part_stride);
         HIP_TRY(ctx, mark(2));
         for (int r = 0; r < reps; ++r) launch_qkv_finish(st, part, sp1, ctx->part_stride, ctx->dm, B.n_seq, B.pos, (const double*)(w + ctx->o_freq), q, kc, vc, new_rows);
         HIP_TRY(ctx, mark(3));
@@ -346,7 +355,7 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t n_batches, const mo
                 return fail(ctx, MOE_ERR_SHAPE, "no attention kernel for this head shape");
         HIP_TRY(ctx, mark(4));
         const int sp2 = pick_splits(nrb, (int)dq, (int)d);
-        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ao, w + ctx->o_wo, nrb, (int)dq, (int)d, sp2, part, ctx->part_stride);
+        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ao, w + lo + ctx->o_wo, nrb, (int)dq, (int)d, sp2, part, ctx->part_stride);
         HIP_TRY(ctx, mark(5));
         launch_out_finish(st, part, sp2, ctx->part_stride, x, B.n_seq, (int)d, y);
         HIP_TRY(ctx, hipGetLastError());

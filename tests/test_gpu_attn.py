@@ -53,14 +53,15 @@ def check_group(w, batches, want):
                 f"batch {b}: new {name} row mean error {np.abs(gr - orow).mean() / rms:.2e} of rms"
 
 
-def run_group(w, on_host, layer=0, ctx=None):
+def run_group(w, on_host, layer=0, ctx=None, set_weights=True):
     ws = I.gen_attn_weights(w, layer)
     hs = [I.gen_attn_hidden(w, layer, b) for b in range(w.n_batches)]
     caches = [I.gen_kv_cache(w, layer, b) for b in range(w.n_batches)]
     own = ctx is None
     if own:
         ctx = A.AttnContext(A.config_for(w), DEV)
-    ctx.set_weights(*[ws[n].to(DEV) for n in ("norm", "wq", "wk", "wv", "wo")])
+    if set_weights:
+        ctx.set_weights(*[ws[n].to(DEV) for n in ("norm", "wq", "wk", "wv", "wo")], layer=layer)
     batches = []
     for b in range(w.n_batches):
         if on_host:
@@ -73,7 +74,7 @@ def run_group(w, on_host, layer=0, ctx=None):
             h_out = torch.zeros_like(h_in)
         batches.append(A.AttnBatch(k, v, h_in, h_out, w.batch_pos[b]))
     torch.cuda.synchronize()
-    ctx.forward_group(batches)
+    ctx.forward_group(batches, layer=layer)
     ctx.synchronize()
     torch.cuda.synchronize()
     check_group(w, batches, oracle_group(w, ws, hs, caches))
@@ -111,6 +112,22 @@ def test_context_reuse_with_shrinking_batches():
     ctx.close()
 
 
+def test_several_layers_in_one_context():
+    """Three layers' weights in one context, used out of order; inputs differ per layer."""
+    w = I.ATTN_WORKLOADS["attn_tiny"]
+    ctx = A.AttnContext(A.config_for(w, n_layers=3), DEV)
+    for layer in (2, 0, 1):
+        ws = I.gen_attn_weights(w, layer)
+        ctx.set_weights(*[ws[n].to(DEV) for n in ("norm", "wq", "wk", "wv", "wo")], layer=layer)
+    for layer in (1, 2, 0, 2):
+        run_group(w, on_host=(layer != 1), layer=layer, ctx=ctx, set_weights=False)
+    from paper_2502_06888_amd import binding as B
+    with pytest.raises(B.MoeError) as ei:
+        run_group(w, on_host=False, layer=3, ctx=ctx, set_weights=False)
+    assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    ctx.close()
+
+
 def test_argument_errors():
     from paper_2502_06888_amd import binding as B
     w = I.ATTN_WORKLOADS["attn_tiny"]
@@ -132,7 +149,7 @@ def test_argument_errors():
     ctx.synchronize()
     ctx.close()
     with pytest.raises(B.MoeError) as ei:
-        A.workspace_bytes(A.MoeAttnConfig(200, 8, 2, 32, 4, 16, 1e4, 1e-5))
+        A.workspace_bytes(A.MoeAttnConfig(200, 8, 2, 32, 4, 16, 1, 1e4, 1e-5))
     assert ei.value.status == B.MOE_ERR_SHAPE
 
 
