@@ -113,6 +113,16 @@ moe_status moe_attn_set_weights(moe_attn_ctx* ctx, int32_t layer, const void* g,
 moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_batches,
                                   const moe_attn_batch* batches);
 
+/*
+ * moe_attn_prefetch -- Algorithm 1, expert-layer branch, "load(c[i][j+1][0])": while the expert
+ * layer computes, start bringing the caches of the first batch of the next attention layer into
+ * staging buffer 0 (load stream; it first waits for the compute work enqueued so far).  The next
+ * moe_attn_forward_group whose first batch has the same caches, n_seq and pos uses them and
+ * copies only that batch's hidden state; any other first batch is loaded as usual.  No-op for
+ * device-resident caches.  Errors as for a batch of moe_attn_forward_group.
+ */
+moe_status moe_attn_prefetch(moe_attn_ctx* ctx, const moe_attn_batch* first);
+
 /* Profiling: when on (1..64), every forward_group call times its streams with events and
  * synchronises.  With on = n > 1 each kernel but the last (the residual, which may work in place)
  * is launched n times back to back between its two events, same inputs and same outputs, so that

@@ -13,7 +13,7 @@ from . import binding as B
 
 ATTN_EXPORTS = ["moe_attn_workspace_bytes", "moe_attn_create", "moe_attn_destroy",
                 "moe_attn_set_weights", "moe_attn_forward_group", "moe_attn_set_profiling",
-                "moe_attn_get_profile", "moe_attn_last_error"]
+                "moe_attn_get_profile", "moe_attn_last_error", "moe_attn_prefetch"]
 
 
 class MoeAttnConfig(C.Structure):
@@ -50,6 +50,7 @@ def load_library():
         lib.moe_attn_destroy.restype = None
         lib.moe_attn_set_weights.argtypes = [vp, i32] + [vp] * 5 + [i32]
         lib.moe_attn_forward_group.argtypes = [vp, i32, i32, P(MoeAttnBatch)]
+        lib.moe_attn_prefetch.argtypes = [vp, P(MoeAttnBatch)]
         lib.moe_attn_set_profiling.argtypes = [vp, i32]
         lib.moe_attn_get_profile.argtypes = [vp, P(MoeAttnProfile)]
         lib.moe_attn_last_error.argtypes = [vp]
@@ -106,12 +107,20 @@ class AttnContext:
         _check(self.lib.moe_attn_set_weights(self.h, layer, g.data_ptr(), wq.data_ptr(), wk.data_ptr(),
                                              wv.data_ptr(), wo.data_ptr(), on_host), self.h)
 
+    @staticmethod
+    def _marshal(b: AttnBatch) -> MoeAttnBatch:
+        return MoeAttnBatch(b.h_in.shape[0], b.pos, 0 if b.k_cache.is_cuda else 1,
+                            0 if b.h_in.is_cuda else 1, b.k_cache.data_ptr(),
+                            b.v_cache.data_ptr(), b.h_in.data_ptr(), b.h_out.data_ptr())
+
+    def prefetch(self, first: AttnBatch):
+        m = self._marshal(first)
+        _check(self.lib.moe_attn_prefetch(self.h, C.byref(m)), self.h)
+
     def forward_group(self, batches: Sequence[AttnBatch], layer: int = 0):
         arr = (MoeAttnBatch * max(1, len(batches)))()
         for i, b in enumerate(batches):
-            arr[i] = MoeAttnBatch(b.h_in.shape[0], b.pos, 0 if b.k_cache.is_cuda else 1,
-                                  0 if b.h_in.is_cuda else 1, b.k_cache.data_ptr(),
-                                  b.v_cache.data_ptr(), b.h_in.data_ptr(), b.h_out.data_ptr())
+            arr[i] = self._marshal(b)
         _check(self.lib.moe_attn_forward_group(self.h, layer, len(batches), arr), self.h)
 
     def set_profiling(self, level: int):

@@ -28,6 +28,8 @@ struct moe_attn_ctx {
     std::vector<hipEvent_t> ev;  // kEv per batch when profiling
     moe_attn_profile prof;
     bool prof_valid;
+    bool pre_valid;        // staging buffer 0 holds the caches of `pre` (moe_attn_prefetch)
+    moe_attn_batch pre;
     mutable std::string err;
 };
 
@@ -121,6 +123,19 @@ void layout(moe_attn_ctx* c) {
         c->o_hout[b] = take((size_t)g.max_seqs * d * 2);
     }
     c->total = o;
+}
+
+moe_status check_batch(const moe_attn_ctx* ctx, const moe_attn_batch& B, int b) {
+    const moe_attn_config& c = ctx->cfg;
+    if (B.n_seq < 1 || B.n_seq > c.max_seqs) return fail(ctx, MOE_ERR_INVALID_ARG, "batch %d: n_seq %d outside 1..max_seqs", b, B.n_seq);
+    if (B.pos < 0 || B.pos >= c.max_len) return fail(ctx, MOE_ERR_INVALID_ARG, "batch %d: pos %d outside 0..max_len-1", b, B.pos);
+    if (!B.k_cache || !B.v_cache || !B.h_in || !B.h_out) return fail(ctx, MOE_ERR_INVALID_ARG, "batch %d: null pointer", b);
+    const int want_kv = B.kv_on_host ? 1 : 2, want_h = B.h_on_host ? 1 : 2;
+    if (pointer_kind(B.k_cache) != want_kv || pointer_kind(B.v_cache) != want_kv)
+        return fail(ctx, B.kv_on_host ? MOE_ERR_NOT_PINNED : MOE_ERR_INVALID_ARG, "batch %d: cache pointers are not %s memory", b, B.kv_on_host ? "pinned host" : "device");
+    if (pointer_kind(B.h_in) != want_h || pointer_kind(B.h_out) != want_h)
+        return fail(ctx, B.h_on_host ? MOE_ERR_NOT_PINNED : MOE_ERR_INVALID_ARG, "batch %d: hidden-state pointers are not %s memory", b, B.h_on_host ? "pinned host" : "device");
+    return MOE_OK;
 }
 
 }  // namespace
@@ -259,6 +274,26 @@ moe_status moe_attn_get_profile(moe_attn_ctx* ctx, moe_attn_profile* out) {
     return MOE_OK;
 }
 
+moe_status moe_attn_prefetch(moe_attn_ctx* ctx, const moe_attn_batch* first) {
+    if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    if (!first) return fail(ctx, MOE_ERR_INVALID_ARG, "first is null");
+    moe_status bs = check_batch(ctx, *first, 0);
+    if (bs != MOE_OK) return bs;
+    ctx->pre_valid = false;
+    if (!first->kv_on_host || first->pos == 0) return MOE_OK;  // nothing to move
+    const moe_attn_config& c = ctx->cfg;
+    const size_t hd = c.head_dim, pitch = (size_t)c.max_len * hd * 2;
+    const size_t width = (size_t)first->pos * hd * 2, height = (size_t)first->n_seq * c.n_kv_heads;
+    // staging buffer 0 is free once everything enqueued on the compute stream so far has run
+    HIP_TRY(ctx, hipEventRecord(ctx->entry, ctx->compute));
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->load, ctx->entry, 0));
+    HIP_TRY(ctx, hipMemcpy2DAsync(ctx->ws + ctx->o_kv[0][0], pitch, first->k_cache, pitch, width, height, hipMemcpyHostToDevice, ctx->load));
+    HIP_TRY(ctx, hipMemcpy2DAsync(ctx->ws + ctx->o_kv[0][1], pitch, first->v_cache, pitch, width, height, hipMemcpyHostToDevice, ctx->load));
+    ctx->pre = *first;
+    ctx->pre_valid = true;
+    return MOE_OK;
+}
+
 moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_batches,
                                   const moe_attn_batch* batches) {
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
@@ -269,15 +304,8 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
     const moe_attn_config& c = ctx->cfg;
     const size_t d = c.d_model, hd = c.head_dim, dkv = (size_t)c.n_kv_heads * hd, dq = (size_t)c.n_q_heads * hd;
     for (int b = 0; b < n_batches; ++b) {
-        const moe_attn_batch& B = batches[b];
-        if (B.n_seq < 1 || B.n_seq > c.max_seqs) return fail(ctx, MOE_ERR_INVALID_ARG, "batch %d: n_seq %d outside 1..max_seqs", b, B.n_seq);
-        if (B.pos < 0 || B.pos >= c.max_len) return fail(ctx, MOE_ERR_INVALID_ARG, "batch %d: pos %d outside 0..max_len-1", b, B.pos);
-        if (!B.k_cache || !B.v_cache || !B.h_in || !B.h_out) return fail(ctx, MOE_ERR_INVALID_ARG, "batch %d: null pointer", b);
-        const int want_kv = B.kv_on_host ? 1 : 2, want_h = B.h_on_host ? 1 : 2;
-        if (pointer_kind(B.k_cache) != want_kv || pointer_kind(B.v_cache) != want_kv)
-            return fail(ctx, B.kv_on_host ? MOE_ERR_NOT_PINNED : MOE_ERR_INVALID_ARG, "batch %d: cache pointers are not %s memory", b, B.kv_on_host ? "pinned host" : "device");
-        if (pointer_kind(B.h_in) != want_h || pointer_kind(B.h_out) != want_h)
-            return fail(ctx, B.h_on_host ? MOE_ERR_NOT_PINNED : MOE_ERR_INVALID_ARG, "batch %d: hidden-state pointers are not %s memory", b, B.h_on_host ? "pinned host" : "device");
+        moe_status bs = check_batch(ctx, batches[b], b);
+        if (bs != MOE_OK) return bs;
     }
     if (n_batches == 0) return MOE_OK;
     const bool prof = ctx->profiling > 0;
@@ -301,12 +329,12 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
     HIP_TRY(ctx, hipStreamWaitEvent(sv, ctx->entry, 0));
     bool used_done[2] = {false, false}, used_stored[2] = {false, false};
 
-    auto issue_load = [&](int b) -> moe_status {
+    auto issue_load = [&](int b, bool caches_there) -> moe_status {
         const moe_attn_batch& B = batches[b];
         const int buf = b & 1;
         if (used_done[buf]) HIP_TRY(ctx, hipStreamWaitEvent(ld, ctx->done[buf], 0));
         if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvLoad], ld));
-        if (B.kv_on_host && B.pos > 0) {
+        if (B.kv_on_host && B.pos > 0 && !caches_there) {
             const size_t width = (size_t)B.pos * hd * 2, height = (size_t)B.n_seq * c.n_kv_heads;
             HIP_TRY(ctx, hipMemcpy2DAsync(w + ctx->o_kv[buf][0], pitch, B.k_cache, pitch, width, height, hipMemcpyHostToDevice, ld));
             HIP_TRY(ctx, hipMemcpy2DAsync(w + ctx->o_kv[buf][1], pitch, B.v_cache, pitch, width, height, hipMemcpyHostToDevice, ld));
@@ -321,13 +349,18 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
         return MOE_OK;
     };
 
-    moe_status rc = issue_load(0);
+    // the caches of the first batch may have been brought in ahead of the call
+    const moe_attn_batch& F = batches[0];
+    const bool pre = ctx->pre_valid && F.kv_on_host && ctx->pre.k_cache == F.k_cache && ctx->pre.v_cache == F.v_cache &&
+                     ctx->pre.n_seq == F.n_seq && ctx->pre.pos == F.pos;
+    ctx->pre_valid = false;
+    moe_status rc = issue_load(0, pre);
     if (rc != MOE_OK) return rc;
     for (int b = 0; b < n_batches; ++b) {
         const moe_attn_batch& B = batches[b];
         const int buf = b & 1;
         if (b + 1 < n_batches) {
-            rc = issue_load(b + 1);
+            rc = issue_load(b + 1, false);
             if (rc != MOE_OK) return rc;
         }
         HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->loaded[buf], 0));

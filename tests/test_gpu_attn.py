@@ -53,7 +53,7 @@ def check_group(w, batches, want):
                 f"batch {b}: new {name} row mean error {np.abs(gr - orow).mean() / rms:.2e} of rms"
 
 
-def run_group(w, on_host, layer=0, ctx=None, set_weights=True):
+def run_group(w, on_host, layer=0, ctx=None, set_weights=True, prefetch=None):
     ws = I.gen_attn_weights(w, layer)
     hs = [I.gen_attn_hidden(w, layer, b) for b in range(w.n_batches)]
     caches = [I.gen_kv_cache(w, layer, b) for b in range(w.n_batches)]
@@ -74,6 +74,8 @@ def run_group(w, on_host, layer=0, ctx=None, set_weights=True):
             h_out = torch.zeros_like(h_in)
         batches.append(A.AttnBatch(k, v, h_in, h_out, w.batch_pos[b]))
     torch.cuda.synchronize()
+    if prefetch is not None:
+        ctx.prefetch(batches[prefetch])
     ctx.forward_group(batches, layer=layer)
     ctx.synchronize()
     torch.cuda.synchronize()
@@ -125,6 +127,23 @@ def test_several_layers_in_one_context():
     with pytest.raises(B.MoeError) as ei:
         run_group(w, on_host=False, layer=3, ctx=ctx, set_weights=False)
     assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    ctx.close()
+
+
+def test_prefetch_of_the_first_batch():
+    """The first batch's caches brought in ahead of the call (and a prefetch of some other batch,
+    which the call must ignore): same results; the call then loads fewer bytes."""
+    w = I.ATTN_WORKLOADS["attn_tiny"]
+    ctx = A.AttnContext(A.config_for(w), DEV)
+    ctx.set_profiling(1)
+    run_group(w, on_host=True, ctx=ctx)
+    plain = ctx.profile().bytes_loaded
+    run_group(w, on_host=True, ctx=ctx, prefetch=0)
+    ahead = ctx.profile().bytes_loaded
+    run_group(w, on_host=True, ctx=ctx, prefetch=2)
+    other = ctx.profile().bytes_loaded
+    assert plain - ahead == w.kv_bytes(0) and other == plain
+    run_group(w, on_host=False, ctx=ctx, prefetch=0)   # device-resident caches: nothing to move
     ctx.close()
 
 
