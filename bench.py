@@ -110,9 +110,42 @@ def planner_report(ctx, w, xs, ys, K, compute, torch, B):
     hot, cold = order[:K], order[K:]
     t_c_hot = sum(last["t_c_expert_s"][e] for e in hot)
     t_c_q = [last["t_c_expert_s"][e] for e in cold]
-    n_min = B.moe_plan_batches(0.0, last["t_c_gate_group_s"] / n, t_c_hot, t_c_q, 0.0, 0.0, last["t_io_expert_s"], K)
-    return {"layer": 0, "tokens_per_batch": tpb, "K": K, "n_min": n_min, "sweep": rows,
-            "note": "t_c_A = t_IO_A = t_IO_G = 0: no attention in this build, gate resident"}
+    n_min_moe = B.moe_plan_batches(0.0, last["t_c_gate_group_s"] / n, t_c_hot, t_c_q, 0.0, 0.0, last["t_io_expert_s"], K)
+    # t_c_A: the attention layer of one batch (the batch's tokens as sequences, 512 cached
+    # positions, caches in HBM, weights resident: t_IO_A = 0), measured with the library's events
+    t_c_A = measure_attention_batch(w, tpb, torch)
+    n_min = B.moe_plan_batches(t_c_A, last["t_c_gate_group_s"] / n, t_c_hot, t_c_q, 0.0, 0.0, last["t_io_expert_s"], K)
+    return {"layer": 0, "tokens_per_batch": tpb, "K": K, "n_min": n_min, "n_min_without_attention": n_min_moe,
+            "t_c_A_us": t_c_A * 1e6, "sweep": rows,
+            "note": "t_IO_A = t_IO_G = 0: attention weights and gate resident; t_c_A from the attention "
+                    "layer with d_model/128 query heads, 8 key-value heads of 128, 512 cached positions"}
+
+
+def measure_attention_batch(w, n_seq, torch, pos: int = 512) -> float:
+    """Kernel time of the attention layer for one batch of the workload's model width."""
+    from paper_2502_06888_amd import attn_binding as A
+    from paper_2502_06888_amd import inputs as I
+    hq = w.d_model // 128
+    aw = I.AttnWorkload("plan_attn", w.d_model, hq, 8 if hq % 8 == 0 and hq <= 64 else hq, 128, (n_seq,) * 2, (pos,) * 2,
+                        pos + 64, kv_on_host=False, seed=w.seed)
+    ctx = A.AttnContext(A.config_for(aw), "cuda:0")
+    ws = I.gen_attn_weights(aw, 0)
+    ctx.set_weights(*[ws[k].to("cuda:0") for k in ("norm", "wq", "wk", "wv", "wo")])
+    batches = []
+    for b in range(aw.n_batches):
+        k, v = [t.to("cuda:0") for t in I.gen_kv_cache(aw, 0, b)]
+        h = I.gen_attn_hidden(aw, 0, b).to("cuda:0")
+        batches.append(A.AttnBatch(k, v, h, torch.empty_like(h), pos))
+    ctx.forward_group(batches)
+    ctx.synchronize()
+    ctx.set_profiling(1)
+    best = None
+    for _ in range(5):
+        ctx.forward_group(batches)
+        t = ctx.profile().compute_busy_s / aw.n_batches
+        best = t if best is None else min(best, t)
+    ctx.close()
+    return best
 
 
 def fp16_intermediate_variant(w, data, args, torch, B):

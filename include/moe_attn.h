@@ -36,7 +36,7 @@ typedef struct moe_attn_ctx moe_attn_ctx; /* opaque, library-owned */
 
 typedef struct {
     int32_t d_model;    /* multiple of 128, at most 8192 */
-    int32_t n_q_heads;  /* n_q_heads / n_kv_heads in {1, 2, 4, 8} */
+    int32_t n_q_heads;  /* a multiple of n_kv_heads, at most 8 times it */
     int32_t n_kv_heads;
     int32_t head_dim;   /* 32, 64 or 128; n_q_heads*head_dim a multiple of 128 */
     int32_t max_seqs;   /* sequences per batch, at most */

@@ -81,7 +81,7 @@ moe_status check_config(const moe_attn_config* c, std::string* why) {
     if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return bad("head_dim must be 32, 64 or 128");
     if (c->n_kv_heads <= 0 || c->n_q_heads <= 0 || c->n_q_heads % c->n_kv_heads != 0) return bad("n_q_heads must be a multiple of n_kv_heads");
     const int g = c->n_q_heads / c->n_kv_heads;
-    if (g != 1 && g != 2 && g != 4 && g != 8) return bad("n_q_heads / n_kv_heads must be 1, 2, 4 or 8");
+    if (g > 8) return bad("n_q_heads / n_kv_heads must be at most 8");
     if ((c->n_q_heads * c->head_dim) % 128 != 0) return bad("n_q_heads*head_dim must be a multiple of 128");
     if ((c->n_kv_heads * c->head_dim) % 32 != 0) return bad("n_kv_heads*head_dim must be a multiple of 32");
     if (c->max_seqs <= 0 || c->max_seqs > 4096) return bad("max_seqs must be in 1..4096");

@@ -452,10 +452,10 @@ static int launch_attention_hd(hipStream_t st, const float* q, const void* kc, c
     const u32x4* V = (const u32x4*)vc;
     u32x4* O = (u32x4*)o_frag;
     switch (dm.Hq / dm.Hkv) {
-        case 1: hipLaunchKernelGGL((attn_decode_kernel<HD, 1>), grid, block, 0, st, q, K, V, dm, n_seq, pos, O); return 0;
-        case 2: hipLaunchKernelGGL((attn_decode_kernel<HD, 2>), grid, block, 0, st, q, K, V, dm, n_seq, pos, O); return 0;
-        case 4: hipLaunchKernelGGL((attn_decode_kernel<HD, 4>), grid, block, 0, st, q, K, V, dm, n_seq, pos, O); return 0;
-        case 8: hipLaunchKernelGGL((attn_decode_kernel<HD, 8>), grid, block, 0, st, q, K, V, dm, n_seq, pos, O); return 0;
+#define KATTN_CASE(G) \
+    case G: hipLaunchKernelGGL((attn_decode_kernel<HD, G>), grid, block, 0, st, q, K, V, dm, n_seq, pos, O); return 0;
+        KATTN_CASE(1) KATTN_CASE(2) KATTN_CASE(3) KATTN_CASE(4) KATTN_CASE(5) KATTN_CASE(6) KATTN_CASE(7) KATTN_CASE(8)
+#undef KATTN_CASE
     }
     return -1;
 }

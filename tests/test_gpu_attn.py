@@ -89,7 +89,8 @@ def test_tiny_group_matches_oracle(on_host):
     run_group(I.ATTN_WORKLOADS["attn_tiny"], on_host)
 
 
-@pytest.mark.parametrize("hd,hq,hkv", [(32, 8, 8), (64, 4, 2), (128, 8, 1), (128, 2, 1)])
+@pytest.mark.parametrize("hd,hq,hkv", [(32, 8, 8), (64, 4, 2), (128, 8, 1), (128, 2, 1), (128, 6, 1), (64, 6, 2),
+                                       (32, 20, 4), (128, 7, 1)])
 def test_head_shapes(hd, hq, hkv):
     w = I.scaled(I.ATTN_WORKLOADS["attn_tiny"], head_dim=hd, n_q_heads=hq, n_kv_heads=hkv,
                  d_model=256, batch_seqs=(33, 2), batch_pos=(70, 3), max_len=80, seed=3)
