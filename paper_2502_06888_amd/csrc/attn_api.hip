@@ -324,14 +324,23 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
     int64_t bytes_loaded = 0, bytes_stored = 0;
 
     // the staging buffers may still be read by work enqueued earlier on the compute stream
-    HIP_TRY(ctx, hipEventRecord(ctx->entry, st));
-    HIP_TRY(ctx, hipStreamWaitEvent(ld, ctx->entry, 0));
-    HIP_TRY(ctx, hipStreamWaitEvent(sv, ctx->entry, 0));
-    bool used_done[2] = {false, false}, used_stored[2] = {false, false};
+    // a batch that lives on the device needs neither stream: no event is recorded or waited for
+    // on its behalf (a group that is all on the device is a plain run of kernels)
+    auto on_device = [&](int b) { return !batches[b].kv_on_host && !batches[b].h_on_host; };
+    bool any_host = false;
+    for (int b = 0; b < n_batches; ++b) any_host = any_host || !on_device(b);
+    if (any_host || prof) {
+        HIP_TRY(ctx, hipEventRecord(ctx->entry, st));
+        HIP_TRY(ctx, hipStreamWaitEvent(ld, ctx->entry, 0));
+        HIP_TRY(ctx, hipStreamWaitEvent(sv, ctx->entry, 0));
+    }
+    bool used_done[2] = {false, false}, used_stored[2] = {false, false}, used_loaded[2] = {false, false};
 
     auto issue_load = [&](int b, bool caches_there) -> moe_status {
         const moe_attn_batch& B = batches[b];
         const int buf = b & 1;
+        used_loaded[buf] = false;
+        if (on_device(b) && !prof) return MOE_OK;
         if (used_done[buf]) HIP_TRY(ctx, hipStreamWaitEvent(ld, ctx->done[buf], 0));
         if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvLoad], ld));
         if (B.kv_on_host && B.pos > 0 && !caches_there) {
@@ -346,6 +355,7 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
         }
         if (prof) HIP_TRY(ctx, hipEventRecord(ctx->ev[b * kEv + kEvLoad + 1], ld));
         HIP_TRY(ctx, hipEventRecord(ctx->loaded[buf], ld));
+        used_loaded[buf] = true;
         return MOE_OK;
     };
 
@@ -363,8 +373,8 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
             rc = issue_load(b + 1, false);
             if (rc != MOE_OK) return rc;
         }
-        HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->loaded[buf], 0));
-        if (used_stored[buf]) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->stored[buf], 0));
+        if (used_loaded[buf]) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->loaded[buf], 0));
+        if (used_stored[buf] && !on_device(b)) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->stored[buf], 0));
         auto mark = [&](int i) -> hipError_t { return prof ? hipEventRecord(ctx->ev[b * kEv + kEvKernel + i], st) : hipSuccess; };
         HIP_TRY(ctx, mark(0));
         const void* x = B.h_on_host ? (const void*)(w + ctx->o_hin[buf]) : B.h_in;
@@ -393,8 +403,10 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
         launch_out_finish(st, part, sp2, ctx->part_stride, x, B.n_seq, (int)d, y);
         HIP_TRY(ctx, hipGetLastError());
         HIP_TRY(ctx, mark(6));
-        HIP_TRY(ctx, hipEventRecord(ctx->done[buf], st));
-        used_done[buf] = true;
+        if (any_host) {  // a later batch may load into this staging buffer
+            HIP_TRY(ctx, hipEventRecord(ctx->done[buf], st));
+            used_done[buf] = true;
+        }
 
         if (B.kv_on_host || B.h_on_host) {
             HIP_TRY(ctx, hipStreamWaitEvent(sv, ctx->done[buf], 0));
@@ -420,7 +432,7 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
     }
     for (int buf = 0; buf < 2; ++buf)
         if (used_stored[buf]) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->stored[buf], 0));
-    HIP_TRY(ctx, hipEventRecord(ctx->finish, st));
+    if (prof) HIP_TRY(ctx, hipEventRecord(ctx->finish, st));
     if (prof) {
         HIP_TRY(ctx, hipStreamSynchronize(st));
         HIP_TRY(ctx, hipStreamSynchronize(ld));

@@ -64,7 +64,8 @@ def run_group(w, on_host, layer=0, ctx=None, set_weights=True, prefetch=None):
         ctx.set_weights(*[ws[n].to(DEV) for n in ("norm", "wq", "wk", "wv", "wo")], layer=layer)
     batches = []
     for b in range(w.n_batches):
-        if on_host:
+        host_b = on_host[b % len(on_host)] if isinstance(on_host, (tuple, list)) else on_host
+        if host_b:
             k, v = caches[b][0].clone().pin_memory(), caches[b][1].clone().pin_memory()
             h_in = hs[b].clone().pin_memory()
             h_out = torch.zeros_like(h_in).pin_memory()
@@ -103,6 +104,17 @@ def test_ragged_rows_and_several_row_tiles():
                  batch_seqs=(130, 1, 64), batch_pos=(9, 255, 128), max_len=256, seed=5)
     run_group(w, on_host=False)
     run_group(w, on_host=True)
+
+
+def test_group_mixing_host_and_device_batches():
+    """Batches whose caches live on the host next to batches that live on the device, in both
+    alternations and with a run of device batches between two host batches."""
+    w = I.scaled(I.ATTN_WORKLOADS["attn_tiny"], batch_seqs=(4, 7, 2, 9, 3, 5), batch_pos=(11, 30, 0, 47, 8, 21), seed=11)
+    ctx = A.AttnContext(A.config_for(w), DEV)
+    run_group(w, on_host=(True, False), ctx=ctx)
+    run_group(w, on_host=(False, True), ctx=ctx)
+    run_group(w, on_host=(True, False, False, False, True, False), ctx=ctx)
+    ctx.close()
 
 
 def test_context_reuse_with_shrinking_batches():
