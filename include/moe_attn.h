@@ -42,6 +42,9 @@ typedef struct {
     int32_t max_seqs;   /* sequences per batch, at most */
     int32_t max_len;    /* capacity of every cache, in positions */
     int32_t n_layers;   /* attention layers whose weights one context holds (>= 1) */
+    int32_t max_group_seqs; /* 0, or the sequences of a whole batch group at most: a group whose
+                           batches all live on the device and whose sequences fit is run with
+                           one launch per kernel, the projection weights read once for all */
     float rope_theta;
     float rms_eps;
 } moe_attn_config;
@@ -105,7 +108,8 @@ moe_status moe_attn_set_weights(moe_attn_ctx* ctx, int32_t layer, const void* g,
  * (the caches of a batch are that layer's): for batch
  * b = 0..n_batches-1, wait for b's h and c on the load stream, start loading batch b+1 into
  * the other staging buffer, compute b, then store b's new cache row and hidden state on the
- * store stream.  Returns after enqueueing; results are valid once the compute stream is
+ * store stream.  (A group that is entirely on the device and fits max_group_seqs needs no such
+ * order and is computed in one pass, see moe_attn_config.)  Returns after enqueueing; results are valid once the compute stream is
  * synchronised (it is made to wait for the last store).  The batches array is read during the
  * call only.  Errors: MOE_ERR_INVALID_ARG (null, layer, pos or n_seq out of range), MOE_ERR_STATE
  * (the layer has no weights), MOE_ERR_NOT_PINNED (a host pointer that is not pinned), MOE_ERR_HIP.

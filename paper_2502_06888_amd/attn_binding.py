@@ -19,7 +19,8 @@ ATTN_EXPORTS = ["moe_attn_workspace_bytes", "moe_attn_create", "moe_attn_destroy
 class MoeAttnConfig(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("max_seqs", C.c_int32), ("max_len", C.c_int32),
-                ("n_layers", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+                ("n_layers", C.c_int32), ("max_group_seqs", C.c_int32), ("rope_theta", C.c_float),
+                ("rms_eps", C.c_float)]
 
 
 class MoeAttnBatch(C.Structure):
@@ -147,7 +148,9 @@ class AttnContext:
             pass
 
 
-def config_for(w, max_seqs=None, n_layers: int = 1) -> MoeAttnConfig:
-    """MoeAttnConfig of an ``inputs.AttnWorkload``."""
+def config_for(w, max_seqs=None, n_layers: int = 1, grouped: bool = True) -> MoeAttnConfig:
+    """MoeAttnConfig of an ``inputs.AttnWorkload``; ``grouped`` sizes the buffers for the whole
+    batch group so that device-resident groups run in one pass."""
     return MoeAttnConfig(w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim,
-                         max_seqs or max(w.batch_seqs), w.max_len, n_layers, w.rope_theta, w.rms_eps)
+                         max_seqs or max(w.batch_seqs), w.max_len, n_layers,
+                         w.n_tokens if grouped else 0, w.rope_theta, w.rms_eps)

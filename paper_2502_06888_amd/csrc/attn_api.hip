@@ -21,7 +21,8 @@ struct moe_attn_ctx {
     // offsets into the workspace
     size_t o_wqkv, o_wo, o_g, layer_stride, o_freq, o_ax, o_ao, o_part, o_q, o_kv[2][2], o_new[2], o_hin[2], o_hout[2], total;
     int rows_alloc;   // rows the activation buffers hold (multiple of 128)
-    int64_t part_stride;
+    int part_rows;    // rows x splits the partial-sum buffer holds
+    size_t widest;    // columns of the widest projection
     std::vector<char> has_weights;  // per layer
     hipEvent_t entry, finish, loaded[2], done[2], stored[2];
     int profiling;  // 0 off, n >= 1: kernels launched n times between their events
@@ -88,6 +89,7 @@ moe_status check_config(const moe_attn_config* c, std::string* why) {
     if (c->max_len <= 0 || c->max_len > (1 << 20)) return bad("max_len must be in 1..2^20");
     if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return bad("rope_theta must be > 0 and rms_eps >= 0");
     if (c->n_layers < 1 || c->n_layers > 1024) return bad("n_layers must be in 1..1024");
+    if (c->max_group_seqs < 0 || c->max_group_seqs > 65536) return bad("max_group_seqs must be in 0..65536");
     return MOE_OK;
 }
 
@@ -95,7 +97,8 @@ void layout(moe_attn_ctx* c) {
     const moe_attn_config& g = c->cfg;
     const size_t d = g.d_model, dq = (size_t)g.n_q_heads * g.head_dim, dkv = (size_t)g.n_kv_heads * g.head_dim;
     const size_t n_qkv = dq + 2 * dkv;
-    c->rows_alloc = ((g.max_seqs + 127) / 128) * 128;
+    const int most = g.max_group_seqs > g.max_seqs ? g.max_group_seqs : g.max_seqs;
+    c->rows_alloc = ((most + 127) / 128) * 128;
     size_t o = 0;
     auto take = [&](size_t bytes) {
         size_t at = o;
@@ -110,10 +113,10 @@ void layout(moe_attn_ctx* c) {
     c->o_freq = take((size_t)g.head_dim / 2 * sizeof(double));
     c->o_ax = take((size_t)c->rows_alloc * d * 2);
     c->o_ao = take((size_t)c->rows_alloc * dq * 2);
-    const size_t widest = n_qkv > d ? n_qkv : d;
-    c->part_stride = (int64_t)c->rows_alloc * (int64_t)widest;
-    c->o_part = take((size_t)kMaxSplit * c->part_stride * 4);
-    c->o_q = take((size_t)g.max_seqs * dq * 4);
+    c->widest = n_qkv > d ? n_qkv : d;
+    c->part_rows = c->rows_alloc > kMaxSplit * 128 ? c->rows_alloc : kMaxSplit * 128;
+    c->o_part = take((size_t)c->part_rows * c->widest * 4);
+    c->o_q = take((size_t)c->rows_alloc * dq * 4);
     const size_t cache = (size_t)g.max_seqs * dkv * g.max_len * 2;
     for (int b = 0; b < 2; ++b) {
         c->o_kv[b][0] = take(cache);
@@ -231,7 +234,7 @@ moe_status moe_attn_set_weights(moe_attn_ctx* ctx, int32_t layer, const void* g,
     HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
     // row-major staging: the partial-sum buffer is idle here and large enough for any one matrix
     uint8_t* stage = ctx->ws + ctx->o_part;
-    const size_t stage_bytes = (size_t)kMaxSplit * ctx->part_stride * 4;
+    const size_t stage_bytes = (size_t)ctx->part_rows * ctx->widest * 4;
     struct Item {
         const void* src;
         size_t rows, K;
@@ -359,14 +362,80 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
         return MOE_OK;
     };
 
+    // the six kernels of the layer for the rows of `tab`; profiling events go to slot `slot`
+    auto launch_layer = [&](const GroupTab& tab, int slot) -> moe_status {
+        auto mark = [&](int i) -> hipError_t { return prof ? hipEventRecord(ctx->ev[slot * kEv + kEvKernel + i], st) : hipSuccess; };
+        float* part = (float*)(w + ctx->o_part);
+        float* q = (float*)(w + ctx->o_q);
+        const int rows = tab.row0[tab.n];
+        const int nrb = (rows + kRowBlk - 1) / kRowBlk;
+        const int rows_pad = ((rows + 127) / 128) * 128;  // the row tile of a projection is at most 128 rows
+        const int n_qkv = (int)(dq + 2 * dkv);
+        auto splits_for = [&](int K, int n_out) {
+            int sp = pick_splits(nrb, K, n_out);
+            while (sp > 1 && sp * rows_pad > ctx->part_rows) sp /= 2;
+            return sp;
+        };
+        const int64_t stride = (int64_t)rows_pad * (int64_t)ctx->widest;
+        HIP_TRY(ctx, mark(0));
+        for (int r = 0; r < reps; ++r) launch_rmsnorm(st, tab, w + lo + ctx->o_g, (int)d, c.rms_eps, w + ctx->o_ax);
+        HIP_TRY(ctx, mark(1));
+        const int sp1 = splits_for((int)d, n_qkv);
+        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ax, w + lo + ctx->o_wqkv, nrb, (int)d, n_qkv, sp1, part, stride);
+        HIP_TRY(ctx, mark(2));
+        for (int r = 0; r < reps; ++r) launch_qkv_finish(st, part, sp1, stride, ctx->dm, tab, (const double*)(w + ctx->o_freq), q);
+        HIP_TRY(ctx, mark(3));
+        for (int r = 0; r < reps; ++r)
+            if (launch_attention(st, q, ctx->dm, tab, w + ctx->o_ao) != 0)
+                return fail(ctx, MOE_ERR_SHAPE, "no attention kernel for this head shape");
+        HIP_TRY(ctx, mark(4));
+        const int sp2 = splits_for((int)dq, (int)d);
+        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ao, w + lo + ctx->o_wo, nrb, (int)dq, (int)d, sp2, part, stride);
+        HIP_TRY(ctx, mark(5));
+        launch_out_finish(st, part, sp2, stride, tab, (int)d);
+        HIP_TRY(ctx, hipGetLastError());
+        HIP_TRY(ctx, mark(6));
+        return MOE_OK;
+    };
+
+    // A group that lives on the device needs no per-batch order: the weights are shared across
+    // its batches as the expert layer shares an expert's (one pass over the projection weights
+    // for all rows of the group, one launch of each kernel), provided the rows fit the buffers.
+    int total_rows = 0;
+    for (int b = 0; b < n_batches; ++b) total_rows += batches[b].n_seq;
+    const bool grouped = !any_host && n_batches <= kMaxGroup && total_rows <= ctx->rows_alloc;
+    const int n_units = grouped ? 1 : n_batches;
+    if (grouped) {
+        GroupTab tab{};
+        tab.n = n_batches;
+        for (int b = 0; b < n_batches; ++b) {
+            tab.row0[b + 1] = tab.row0[b] + batches[b].n_seq;
+            tab.pos[b] = batches[b].pos;
+            tab.h_in[b] = batches[b].h_in;
+            tab.h_out[b] = batches[b].h_out;
+            tab.kc[b] = batches[b].k_cache;
+            tab.vc[b] = batches[b].v_cache;
+            tab.new_rows[b] = nullptr;
+        }
+        ctx->pre_valid = false;
+        if (prof) {
+            HIP_TRY(ctx, hipEventRecord(ctx->ev[kEvLoad], ld));
+            HIP_TRY(ctx, hipEventRecord(ctx->ev[kEvLoad + 1], ld));
+            HIP_TRY(ctx, hipEventRecord(ctx->ev[kEvStore], sv));
+            HIP_TRY(ctx, hipEventRecord(ctx->ev[kEvStore + 1], sv));
+        }
+        moe_status grc = launch_layer(tab, 0);
+        if (grc != MOE_OK) return grc;
+    }
+
     // the caches of the first batch may have been brought in ahead of the call
     const moe_attn_batch& F = batches[0];
     const bool pre = ctx->pre_valid && F.kv_on_host && ctx->pre.k_cache == F.k_cache && ctx->pre.v_cache == F.v_cache &&
                      ctx->pre.n_seq == F.n_seq && ctx->pre.pos == F.pos;
     ctx->pre_valid = false;
-    moe_status rc = issue_load(0, pre);
+    moe_status rc = grouped ? MOE_OK : issue_load(0, pre);
     if (rc != MOE_OK) return rc;
-    for (int b = 0; b < n_batches; ++b) {
+    for (int b = 0; b < (grouped ? 0 : n_batches); ++b) {
         const moe_attn_batch& B = batches[b];
         const int buf = b & 1;
         if (b + 1 < n_batches) {
@@ -375,34 +444,18 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
         }
         if (used_loaded[buf]) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->loaded[buf], 0));
         if (used_stored[buf] && !on_device(b)) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->stored[buf], 0));
-        auto mark = [&](int i) -> hipError_t { return prof ? hipEventRecord(ctx->ev[b * kEv + kEvKernel + i], st) : hipSuccess; };
-        HIP_TRY(ctx, mark(0));
-        const void* x = B.h_on_host ? (const void*)(w + ctx->o_hin[buf]) : B.h_in;
-        void* y = B.h_on_host ? (void*)(w + ctx->o_hout[buf]) : B.h_out;
-        void* kc = B.kv_on_host ? (void*)(w + ctx->o_kv[buf][0]) : B.k_cache;
-        void* vc = B.kv_on_host ? (void*)(w + ctx->o_kv[buf][1]) : B.v_cache;
-        void* new_rows = B.kv_on_host ? (void*)(w + ctx->o_new[buf]) : nullptr;
-        float* part = (float*)(w + ctx->o_part);
-        float* q = (float*)(w + ctx->o_q);
-        const int nrb = (B.n_seq + kRowBlk - 1) / kRowBlk;
-        const int n_qkv = (int)(dq + 2 * dkv);
-        for (int r = 0; r < reps; ++r) launch_rmsnorm(st, x, w + lo + ctx->o_g, B.n_seq, (int)d, c.rms_eps, w + ctx->o_ax);
-        HIP_TRY(ctx, mark(1));
-        const int sp1 = pick_splits(nrb, (int)d, n_qkv);
-        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ax, w + lo + ctx->o_wqkv, nrb, (int)d, n_qkv, sp1, part, ctx->part_stride);
-        HIP_TRY(ctx, mark(2));
-        for (int r = 0; r < reps; ++r) launch_qkv_finish(st, part, sp1, ctx->part_stride, ctx->dm, B.n_seq, B.pos, (const double*)(w + ctx->o_freq), q, kc, vc, new_rows);
-        HIP_TRY(ctx, mark(3));
-        for (int r = 0; r < reps; ++r)
-            if (launch_attention(st, q, kc, vc, ctx->dm, B.n_seq, B.pos, w + ctx->o_ao) != 0)
-                return fail(ctx, MOE_ERR_SHAPE, "no attention kernel for this head shape");
-        HIP_TRY(ctx, mark(4));
-        const int sp2 = pick_splits(nrb, (int)dq, (int)d);
-        for (int r = 0; r < reps; ++r) launch_proj(st, w + ctx->o_ao, w + lo + ctx->o_wo, nrb, (int)dq, (int)d, sp2, part, ctx->part_stride);
-        HIP_TRY(ctx, mark(5));
-        launch_out_finish(st, part, sp2, ctx->part_stride, x, B.n_seq, (int)d, y);
-        HIP_TRY(ctx, hipGetLastError());
-        HIP_TRY(ctx, mark(6));
+        GroupTab tab{};
+        tab.n = 1;
+        tab.row0[0] = 0;
+        tab.row0[1] = B.n_seq;
+        tab.pos[0] = B.pos;
+        tab.h_in[0] = B.h_on_host ? (const void*)(w + ctx->o_hin[buf]) : B.h_in;
+        tab.h_out[0] = B.h_on_host ? (void*)(w + ctx->o_hout[buf]) : B.h_out;
+        tab.kc[0] = B.kv_on_host ? (void*)(w + ctx->o_kv[buf][0]) : B.k_cache;
+        tab.vc[0] = B.kv_on_host ? (void*)(w + ctx->o_kv[buf][1]) : B.v_cache;
+        tab.new_rows[0] = B.kv_on_host ? (void*)(w + ctx->o_new[buf]) : nullptr;
+        rc = launch_layer(tab, b);
+        if (rc != MOE_OK) return rc;
         if (any_host) {  // a later batch may load into this staging buffer
             HIP_TRY(ctx, hipEventRecord(ctx->done[buf], st));
             used_done[buf] = true;
@@ -441,7 +494,7 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
         float ms = 0.f;
         HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->entry, ctx->finish));
         p.wall_s = ms * 1e-3;
-        for (int b = 0; b < n_batches; ++b) {
+        for (int b = 0; b < n_units; ++b) {
             hipEvent_t* e = &ctx->ev[(size_t)b * kEv];
             HIP_TRY(ctx, hipEventElapsedTime(&ms, e[kEvLoad], e[kEvLoad + 1]));
             p.load_busy_s += ms * 1e-3;

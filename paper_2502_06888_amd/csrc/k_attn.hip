@@ -42,6 +42,13 @@ __device__ __forceinline__ size_t frag_piece(int row, int chunk, int S) {
     return ((size_t)(row >> 5) * S + (chunk >> 1)) * 64 + (row & 31) + 32 * (chunk & 1);
 }
 
+// Batch that owns activation row `row` (the table has at most kMaxGroup entries).
+__device__ __forceinline__ int find_batch(const GroupTab& tab, int row) {
+    int b = 0;
+    while (b + 1 < tab.n && row >= tab.row0[b + 1]) ++b;
+    return b;
+}
+
 __global__ __launch_bounds__(256) void pack_weight_kernel(const u32x4* __restrict__ w, int rows, int K,
                                                           u32x4* __restrict__ out) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -56,12 +63,12 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const u32x4* __restric
 // One workgroup per row; a thread keeps its 16-byte pieces of the row in registers between the
 // sum of squares and the scaling (rows of up to 256 * 8 * kNormPieces elements).
 constexpr int kNormPieces = 4;
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const u32x4* __restrict__ x,
-                                                      const u32x4* __restrict__ g, int n_seq, int d,
+__global__ __launch_bounds__(256) void rmsnorm_kernel(GroupTab tab, const u32x4* __restrict__ g, int d,
                                                       float eps, u32x4* __restrict__ a) {
     __shared__ float part[4];
     const int row = blockIdx.x, nch = d / 8, S = d / 16;
-    const u32x4* xr = x + (size_t)row * nch;
+    const int bt = find_batch(tab, row);
+    const u32x4* xr = (const u32x4*)tab.h_in[bt] + (size_t)(row - tab.row0[bt]) * nch;
     u32x4 xv[kNormPieces], gv[kNormPieces];
 #pragma unroll
     for (int i = 0; i < kNormPieces; ++i) {
@@ -160,17 +167,20 @@ __global__ __launch_bounds__(256) void proj_kernel(const u32x4* __restrict__ A,
 
 // One thread per rotated pair of q or k, or per element of v, of one sequence.
 __global__ __launch_bounds__(256) void qkv_finish_kernel(const float* __restrict__ part, int splits,
-                                                         int64_t split_stride, Dims dm, int n_seq,
-                                                         int pos, const double* __restrict__ inv_freq,
-                                                         float* __restrict__ q, uint16_t* __restrict__ kc,
-                                                         uint16_t* __restrict__ vc,
-                                                         uint16_t* __restrict__ new_rows) {
-    const int s = blockIdx.y, hd = dm.hd, half = hd / 2;
+                                                         int64_t split_stride, Dims dm, GroupTab tab,
+                                                         const double* __restrict__ inv_freq,
+                                                         float* __restrict__ q) {
+    const int row_g = blockIdx.y, hd = dm.hd, half = hd / 2;
+    const int bt = find_batch(tab, row_g);
+    const int s = row_g - tab.row0[bt], n_seq = tab.row0[bt + 1] - tab.row0[bt], pos = tab.pos[bt];
+    uint16_t* kc = (uint16_t*)tab.kc[bt];
+    uint16_t* vc = (uint16_t*)tab.vc[bt];
+    uint16_t* new_rows = (uint16_t*)tab.new_rows[bt];
     const int dq = dm.Hq * hd, dkv = dm.Hkv * hd, n_out = dq + 2 * dkv;
     const int n_pairs = (dm.Hq + dm.Hkv) * half;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n_pairs + dkv) return;
-    const float* row = part + (size_t)s * n_out;
+    const float* row = part + (size_t)row_g * n_out;
     auto total = [&](int col) {
         float a = 0.f;
         for (int sp = 0; sp < splits; ++sp) a += row[(size_t)sp * split_stride + col];
@@ -189,8 +199,8 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(const float* __restrict
         if (h < dm.Hq) {
             // 1/sqrt(hd) and log2(e) folded in: the attention kernel works with base-2 exponentials
             const float qscale = 1.4426950408889634f / sqrtf((float)hd);
-            q[((size_t)s * dm.Hq + h) * hd + j] = r0 * qscale;
-            q[((size_t)s * dm.Hq + h) * hd + j + half] = r1 * qscale;
+            q[((size_t)row_g * dm.Hq + h) * hd + j] = r0 * qscale;
+            q[((size_t)row_g * dm.Hq + h) * hd + j + half] = r1 * qscale;
         } else {
             const int hk = h - dm.Hq;
             const uint16_t b0 = (uint16_t)bf_bits(r0), b1 = (uint16_t)bf_bits(r1);
@@ -247,23 +257,23 @@ constexpr float kEmpty = -1.0e30f;  // finite stand-in for "no position seen yet
 constexpr int kAttnWaves = 4, kChunk = 2;
 template <int HD, int G>
 __global__ __launch_bounds__(kAttnWaves * 64, 4) void attn_decode_kernel(const float* __restrict__ q,
-                                                                     const u32x4* __restrict__ kc,
-                                                                     const u32x4* __restrict__ vc,
-                                                                     Dims dm, int n_seq, int pos,
+                                                                     Dims dm, GroupTab tab,
                                                                      u32x4* __restrict__ o_frag) {
     constexpr int LPR = HD / 8, RPW = 64 / LPR;
     __shared__ float sm[kAttnWaves][G * LPR][10];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int s = blockIdx.x / dm.Hkv, hk = blockIdx.x % dm.Hkv;
+    const int row_g = blockIdx.x / dm.Hkv, hk = blockIdx.x % dm.Hkv;
+    const int bt = find_batch(tab, row_g);
+    const int s = row_g - tab.row0[bt], pos = tab.pos[bt];
     const int sub = lane % LPR, slot = lane / LPR;
     float qr[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) qr[g][j] = q[((size_t)s * dm.Hq + hk * G + g) * HD + sub * 8 + j];
+        for (int j = 0; j < 8; ++j) qr[g][j] = q[((size_t)row_g * dm.Hq + hk * G + g) * HD + sub * 8 + j];
     const size_t base = ((size_t)s * dm.Hkv + hk) * dm.max_len * LPR + sub;
-    const u32x4* K = kc + base;
-    const u32x4* V = vc + base;
+    const u32x4* K = (const u32x4*)tab.kc[bt] + base;
+    const u32x4* V = (const u32x4*)tab.vc[bt] + base;
     Soft st[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -370,17 +380,19 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attn_decode_kernel(const f
         o.z = pack2(t.acc[4] * inv, t.acc[5] * inv);
         o.w = pack2(t.acc[6] * inv, t.acc[7] * inv);
         const int chunk = ((hk * G + g) * HD) / 8 + sb;
-        o_frag[frag_piece(s, chunk, dm.Hq * HD / 16)] = o;
+        o_frag[frag_piece(row_g, chunk, dm.Hq * HD / 16)] = o;
     }
 }
 
 __global__ __launch_bounds__(256) void out_finish_kernel(const float* __restrict__ part, int splits,
-                                                         int64_t split_stride, const u32x4* __restrict__ x,
-                                                         int n_seq, int d, u32x4* __restrict__ y) {
+                                                         int64_t split_stride, GroupTab tab, int d) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;  // 8 consecutive elements
-    if (i >= (size_t)n_seq * d / 8) return;
+    const int nch = d / 8;
+    if (i >= (size_t)tab.row0[tab.n] * nch) return;
+    const int row = (int)(i / nch), bt = find_batch(tab, row);
+    const size_t at = (size_t)(row - tab.row0[bt]) * nch + i % nch;
     float f[8];
-    widen8(x[i], f);
+    widen8(((const u32x4*)tab.h_in[bt])[at], f);
     for (int sp = 0; sp < splits; ++sp) {
         const float4* p = reinterpret_cast<const float4*>(part + (size_t)sp * split_stride + i * 8);
         const float4 a = p[0], b = p[1];
@@ -392,7 +404,7 @@ __global__ __launch_bounds__(256) void out_finish_kernel(const float* __restrict
     o.y = pack2(f[2], f[3]);
     o.z = pack2(f[4], f[5]);
     o.w = pack2(f[6], f[7]);
-    y[i] = o;
+    ((u32x4*)tab.h_out[bt])[at] = o;
 }
 
 }  // namespace
@@ -403,10 +415,9 @@ void launch_pack_weight(hipStream_t st, const void* w, int rows, int K, void* ou
                        (const u32x4*)w, rows, K, (u32x4*)out);
 }
 
-void launch_rmsnorm(hipStream_t st, const void* x, const void* g, int n_seq, int d, float eps,
-                    void* a_frag) {
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(n_seq), dim3(256), 0, st, (const u32x4*)x,
-                       (const u32x4*)g, n_seq, d, eps, (u32x4*)a_frag);
+void launch_rmsnorm(hipStream_t st, const GroupTab& tab, const void* g, int d, float eps, void* a_frag) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(tab.row0[tab.n]), dim3(256), 0, st, tab, (const u32x4*)g, d, eps,
+                       (u32x4*)a_frag);
 }
 
 int pick_row_tile(int row_blocks) { return row_blocks >= 3 ? 4 : row_blocks == 2 ? 2 : 1; }
@@ -436,45 +447,40 @@ void launch_proj(hipStream_t st, const void* a_frag, const void* w_frag, int row
 }
 
 void launch_qkv_finish(hipStream_t st, const float* part, int splits, int64_t split_stride,
-                       const Dims& dm, int n_seq, int pos, const double* inv_freq, float* q,
-                       void* k_cache, void* v_cache, void* new_rows) {
+                       const Dims& dm, const GroupTab& tab, const double* inv_freq, float* q) {
     const int items = (dm.Hq + dm.Hkv) * (dm.hd / 2) + dm.Hkv * dm.hd;
-    hipLaunchKernelGGL(qkv_finish_kernel, dim3((items + 255) / 256, n_seq), dim3(256), 0, st, part, splits, split_stride, dm,
-                       n_seq, pos, inv_freq, q, (uint16_t*)k_cache, (uint16_t*)v_cache,
-                       (uint16_t*)new_rows);
+    hipLaunchKernelGGL(qkv_finish_kernel, dim3((items + 255) / 256, tab.row0[tab.n]), dim3(256), 0, st, part,
+                       splits, split_stride, dm, tab, inv_freq, q);
 }
 
 template <int HD>
-static int launch_attention_hd(hipStream_t st, const float* q, const void* kc, const void* vc,
-                               const Dims& dm, int n_seq, int pos, void* o_frag) {
-    const dim3 grid(n_seq * dm.Hkv), block(kAttnWaves * 64);
-    const u32x4* K = (const u32x4*)kc;
-    const u32x4* V = (const u32x4*)vc;
+static int launch_attention_hd(hipStream_t st, const float* q, const Dims& dm, const GroupTab& tab,
+                               void* o_frag) {
+    const dim3 grid(tab.row0[tab.n] * dm.Hkv), block(kAttnWaves * 64);
     u32x4* O = (u32x4*)o_frag;
     switch (dm.Hq / dm.Hkv) {
 #define KATTN_CASE(G) \
-    case G: hipLaunchKernelGGL((attn_decode_kernel<HD, G>), grid, block, 0, st, q, K, V, dm, n_seq, pos, O); return 0;
+    case G: hipLaunchKernelGGL((attn_decode_kernel<HD, G>), grid, block, 0, st, q, dm, tab, O); return 0;
         KATTN_CASE(1) KATTN_CASE(2) KATTN_CASE(3) KATTN_CASE(4) KATTN_CASE(5) KATTN_CASE(6) KATTN_CASE(7) KATTN_CASE(8)
 #undef KATTN_CASE
     }
     return -1;
 }
 
-int launch_attention(hipStream_t st, const float* q, const void* k_cache, const void* v_cache,
-                     const Dims& dm, int n_seq, int pos, void* o_frag) {
+int launch_attention(hipStream_t st, const float* q, const Dims& dm, const GroupTab& tab, void* o_frag) {
     switch (dm.hd) {
-        case 32: return launch_attention_hd<32>(st, q, k_cache, v_cache, dm, n_seq, pos, o_frag);
-        case 64: return launch_attention_hd<64>(st, q, k_cache, v_cache, dm, n_seq, pos, o_frag);
-        case 128: return launch_attention_hd<128>(st, q, k_cache, v_cache, dm, n_seq, pos, o_frag);
+        case 32: return launch_attention_hd<32>(st, q, dm, tab, o_frag);
+        case 64: return launch_attention_hd<64>(st, q, dm, tab, o_frag);
+        case 128: return launch_attention_hd<128>(st, q, dm, tab, o_frag);
     }
     return -1;
 }
 
 void launch_out_finish(hipStream_t st, const float* part, int splits, int64_t split_stride,
-                       const void* x, int n_seq, int d, void* y) {
-    const size_t n = (size_t)n_seq * d / 8;
+                       const GroupTab& tab, int d) {
+    const size_t n = (size_t)tab.row0[tab.n] * d / 8;
     hipLaunchKernelGGL(out_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, splits,
-                       split_stride, (const u32x4*)x, n_seq, d, (u32x4*)y);
+                       split_stride, tab, d);
 }
 
 }  // namespace kattn

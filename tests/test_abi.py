@@ -36,11 +36,11 @@ def test_library_exports_every_attention_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in moe_attn.h but not exported"
     assert sorted(A.ATTN_EXPORTS) == names
-    assert C.sizeof(A.MoeAttnConfig) == 9 * 4
+    assert C.sizeof(A.MoeAttnConfig) == 10 * 4
     assert C.sizeof(A.MoeAttnBatch) == 4 * 4 + 4 * 8
     assert C.sizeof(A.MoeAttnProfile) == 12 * 8
     # host-only sizing: Mixtral-8x7B attention with two staged caches of 64 x 8 x 576 x 128 bf16
-    cfg = A.MoeAttnConfig(4096, 32, 8, 128, 64, 576, 1, 1e6, 1e-5)
+    cfg = A.MoeAttnConfig(4096, 32, 8, 128, 64, 576, 1, 0, 1e6, 1e-5)
     need = A.workspace_bytes(cfg)
     cache = 64 * 8 * 576 * 128 * 2
     weights = (4096 + 2 * 1024) * 4096 * 2 + 4096 * 4096 * 2

@@ -90,6 +90,16 @@ def test_tiny_group_matches_oracle(on_host):
     run_group(I.ATTN_WORKLOADS["attn_tiny"], on_host)
 
 
+def test_device_group_batch_by_batch():
+    """A context not sized for the whole group (max_group_seqs = 0) runs a device-resident group
+    batch by batch; sized for it, in one pass.  Both against the oracle."""
+    w = I.ATTN_WORKLOADS["attn_tiny"]
+    for grouped in (False, True):
+        ctx = A.AttnContext(A.config_for(w, grouped=grouped), DEV)
+        run_group(w, on_host=False, ctx=ctx)
+        ctx.close()
+
+
 @pytest.mark.parametrize("hd,hq,hkv", [(32, 8, 8), (64, 4, 2), (128, 8, 1), (128, 2, 1), (128, 6, 1), (64, 6, 2),
                                        (32, 20, 4), (128, 7, 1)])
 def test_head_shapes(hd, hq, hkv):
@@ -181,7 +191,7 @@ def test_argument_errors():
     ctx.synchronize()
     ctx.close()
     with pytest.raises(B.MoeError) as ei:
-        A.workspace_bytes(A.MoeAttnConfig(200, 8, 2, 32, 4, 16, 1, 1e4, 1e-5))
+        A.workspace_bytes(A.MoeAttnConfig(200, 8, 2, 32, 4, 16, 1, 0, 1e4, 1e-5))
     assert ei.value.status == B.MOE_ERR_SHAPE
 
 
