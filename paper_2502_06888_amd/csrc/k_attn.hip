@@ -111,41 +111,48 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(GroupTab tab, const u32x4*
     }
 }
 
-// One wavefront per (column block of 32 outputs, split of the reduction, row tile of NB blocks).
-template <int NB>
-__global__ __launch_bounds__(256) void proj_kernel(const u32x4* __restrict__ A,
+// One wavefront per (U column blocks of 32 outputs, split of the reduction, row tile of NB
+// blocks): every activation fragment it loads feeds U MFMAs, every weight fragment NB.
+template <int NB, int U>
+__global__ __launch_bounds__(256, 2) void proj_kernel(const u32x4* __restrict__ A,
                                                    const u32x4* __restrict__ W, float* __restrict__ out,
                                                    int S, int CB, int splits, int n_rt, int n_out,
                                                    int64_t split_stride) {
     const int lane = threadIdx.x & 63;
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (w >= CB * splits * n_rt) return;
-    const int cb = w % CB, sp = (w / CB) % splits, rt = w / (CB * splits);
+    const int CG = CB / U;  // column groups (host-checked: U divides CB)
+    if (w >= CG * splits * n_rt) return;
+    const int cg = w % CG, sp = (w / CG) % splits, rt = w / (CG * splits);
     const int SS = S / splits;  // a multiple of 8 (host-checked)
-    const u32x4* wp = W + ((size_t)cb * S + (size_t)sp * SS) * 64 + lane;
+    const u32x4* wp = W + ((size_t)cg * U * S + (size_t)sp * SS) * 64 + lane;
     const u32x4* ap = A + ((size_t)rt * NB * S + (size_t)sp * SS) * 64 + lane;
-    constexpr int C = 4;
-    f32x16 acc[NB];
+    constexpr int C = U == 1 ? 4 : 2;
+    f32x16 acc[U][NB];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
-    u32x4 w0[C], w1[C], a0[C][NB], a1[C][NB];
-    auto load = [&](u32x4(&wb)[C], u32x4(&ab)[C][NB], int s) {
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[u][b][r] = 0.f;
+    u32x4 w0[C][U], w1[C][U], a0[C][NB], a1[C][NB];
+    auto load = [&](u32x4(&wb)[C][U], u32x4(&ab)[C][NB], int s) {
 #pragma unroll
         for (int j = 0; j < C; ++j) {
-            wb[j] = wp[(size_t)(s + j) * 64];
+#pragma unroll
+            for (int u = 0; u < U; ++u) wb[j][u] = wp[((size_t)u * S + s + j) * 64];
 #pragma unroll
             for (int b = 0; b < NB; ++b) ab[j][b] = ap[((size_t)b * S + s + j) * 64];
         }
     };
-    auto mac = [&](const u32x4(&wb)[C], const u32x4(&ab)[C][NB]) {
+    auto mac = [&](const u32x4(&wb)[C][U], const u32x4(&ab)[C][NB]) {
 #pragma unroll
         for (int j = 0; j < C; ++j)
 #pragma unroll
             for (int b = 0; b < NB; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ab[j][b]), as_bf16x8(wb[j]),
-                                                                 acc[b], 0, 0, 0);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    acc[u][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ab[j][b]), as_bf16x8(wb[j][u]),
+                                                                        acc[u][b], 0, 0, 0);
     };
     load(w0, a0, 0);
     for (int s = 0; s < SS; s += 2 * C) {
@@ -155,14 +162,17 @@ __global__ __launch_bounds__(256) void proj_kernel(const u32x4* __restrict__ A,
         mac(w1, a1);
     }
     float* o = out + (size_t)sp * split_stride;
-    const int col = cb * 32 + (lane & 31);
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int u = 0; u < U; ++u) {
+        const int col = (cg * U + u) * 32 + (lane & 31);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const size_t row = (size_t)(rt * NB + b) * kRowBlk + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
-            o[row * n_out + col] = acc[b][r];
-        }
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const size_t row = (size_t)(rt * NB + b) * kRowBlk + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
+                o[row * n_out + col] = acc[u][b][r];
+            }
+    }
 }
 
 // One thread per rotated pair of q or k, or per element of v, of one sequence.
@@ -422,11 +432,16 @@ void launch_rmsnorm(hipStream_t st, const GroupTab& tab, const void* g, int d, f
 
 int pick_row_tile(int row_blocks) { return row_blocks >= 3 ? 4 : row_blocks == 2 ? 2 : 1; }
 
+// Column blocks per wavefront: two once a row tile is full (128 rows), where the activation
+// fragments re-read from L2 are what the kernel moves most of.
+static int pick_col_units(int row_blocks, int n_out) { return row_blocks >= 4 && (n_out / 32) % 2 == 0 ? 2 : 1; }
+
 int pick_splits(int row_blocks, int K, int n_out) {
-    const int S = K / 16, CB = n_out / 32;
+    const int U = pick_col_units(row_blocks, n_out);
+    const int S = K / 16, CG = n_out / 32 / U;
     const int nb = pick_row_tile(row_blocks), n_rt = (row_blocks + nb - 1) / nb;
     int splits = 1;
-    while (splits < kMaxSplit && CB * n_rt * splits < 1024 && S % (splits * 2 * 8) == 0) splits *= 2;
+    while (splits < kMaxSplit && CG * n_rt * splits < (U == 2 ? 768 : 1024) && S % (splits * 2 * 8) == 0) splits *= 2;
     return splits;
 }
 
@@ -434,16 +449,19 @@ void launch_proj(hipStream_t st, const void* a_frag, const void* w_frag, int row
                  int n_out, int splits, float* out, int64_t split_stride) {
     const int S = K / 16, CB = n_out / 32;
     const int nb = pick_row_tile(row_blocks), n_rt = (row_blocks + nb - 1) / nb;
-    const int waves = CB * splits * n_rt;
+    const int U = pick_col_units(row_blocks, n_out);
+    const int waves = CB / U * splits * n_rt;
     const dim3 grid((waves + 3) / 4), block(256);
     const u32x4* A = (const u32x4*)a_frag;
     const u32x4* W = (const u32x4*)w_frag;
-    if (nb == 4)
-        hipLaunchKernelGGL(proj_kernel<4>, grid, block, 0, st, A, W, out, S, CB, splits, n_rt, n_out, split_stride);
+    if (nb == 4 && U == 2)
+        hipLaunchKernelGGL((proj_kernel<4, 2>), grid, block, 0, st, A, W, out, S, CB, splits, n_rt, n_out, split_stride);
+    else if (nb == 4)
+        hipLaunchKernelGGL((proj_kernel<4, 1>), grid, block, 0, st, A, W, out, S, CB, splits, n_rt, n_out, split_stride);
     else if (nb == 2)
-        hipLaunchKernelGGL(proj_kernel<2>, grid, block, 0, st, A, W, out, S, CB, splits, n_rt, n_out, split_stride);
+        hipLaunchKernelGGL((proj_kernel<2, 1>), grid, block, 0, st, A, W, out, S, CB, splits, n_rt, n_out, split_stride);
     else
-        hipLaunchKernelGGL(proj_kernel<1>, grid, block, 0, st, A, W, out, S, CB, splits, n_rt, n_out, split_stride);
+        hipLaunchKernelGGL((proj_kernel<1, 1>), grid, block, 0, st, A, W, out, S, CB, splits, n_rt, n_out, split_stride);
 }
 
 void launch_qkv_finish(hipStream_t st, const float* part, int splits, int64_t split_stride,
