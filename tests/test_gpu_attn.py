@@ -127,6 +127,26 @@ def test_group_mixing_host_and_device_batches():
     ctx.close()
 
 
+@pytest.mark.parametrize("n_batches", [64, 66])
+def test_many_small_batches(n_batches):
+    """64 batches is the most one pass over a device-resident group takes; 66 fall back to the
+    batch-by-batch loop.  One or two sequences per batch, positions all different."""
+    seqs = tuple(1 + (b % 2) for b in range(n_batches))
+    pos = tuple((7 * b) % 47 for b in range(n_batches))
+    w = I.scaled(I.ATTN_WORKLOADS["attn_tiny"], batch_seqs=seqs, batch_pos=pos, seed=13)
+    run_group(w, on_host=False)
+
+
+def test_empty_group_and_full_cache():
+    w = I.scaled(I.ATTN_WORKLOADS["attn_tiny"], batch_seqs=(8,), batch_pos=(47,), seed=17)   # last free position
+    ctx = A.AttnContext(A.config_for(w), DEV)
+    run_group(w, on_host=True, ctx=ctx)
+    run_group(w, on_host=False, ctx=ctx)
+    ctx.forward_group([])            # nothing to do, no error
+    ctx.synchronize()
+    ctx.close()
+
+
 def test_context_reuse_with_shrinking_batches():
     big = I.scaled(I.ATTN_WORKLOADS["attn_tiny"], batch_seqs=(8, 8, 8, 8, 8), batch_pos=(40, 41, 42, 43, 44), seed=7)
     small = I.scaled(big, batch_seqs=(3, 2), batch_pos=(5, 0), seed=8)
