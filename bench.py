@@ -585,7 +585,7 @@ def main():
                    "n_experts": w.n_experts, "top_k": w.top_k, "n_batches": w.n_batches,
                    "tokens": w.n_tokens, "experts": "resident in HBM", "weight_bits": args.weight_bits,
                    "n_active": n_active,
-                   "h_format": {0: "bf16 pair", 1: "bf16", 2: "bf16 pair", 3: "fp16"}[args.h_planes],
+                   "h_format": "f32" if w.dtype == "f32" else {0: "bf16 pair", 1: "bf16", 2: "bf16 pair", 3: "fp16"}[args.h_planes],
                    "tokens_per_expert": counts},
         "roofline": roofline,
         "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()},
