@@ -252,3 +252,44 @@ def test_full_size_sampled_sequences():
         assert torch.equal(batches[b].v_cache[:, :, :pos], caches[b][1][:, :, :pos])
         assert torch.isfinite(batches[b].h_out.float()).all()
     ctx.close()
+
+
+def test_full_size_one_pass_group():
+    """The benchmark's device-resident configuration (8 batches x 64 sequences, 512 cached
+    positions, caches in HBM, the whole group in one pass); sampled sequences against the oracle,
+    properties on all."""
+    w = I.ATTN_WORKLOADS["attn_mixtral8x7b_decode_hbm"]
+    ws = I.gen_attn_weights(w, 0)
+    hs = [I.gen_attn_hidden(w, 0, b) for b in range(w.n_batches)]
+    caches = [I.gen_kv_cache(w, 0, b) for b in range(w.n_batches)]
+    ctx = A.AttnContext(A.config_for(w), DEV)
+    ctx.set_weights(*[ws[n].to(DEV) for n in ("norm", "wq", "wk", "wv", "wo")])
+    group_in = torch.cat(hs).to(DEV)                 # hidden states of the group as one tensor
+    group_out = torch.zeros_like(group_in)
+    batches, r0 = [], 0
+    for b in range(w.n_batches):
+        n = w.batch_seqs[b]
+        batches.append(A.AttnBatch(caches[b][0].to(DEV), caches[b][1].to(DEV), group_in[r0:r0 + n],
+                                   group_out[r0:r0 + n], w.batch_pos[b]))
+        r0 += n
+    ctx.forward_group(batches)
+    ctx.synchronize()
+    raw = {k: I.as_raw(v) for k, v in ws.items()}
+    for b, rows in ((0, [0, 63]), (3, [17]), (7, [62])):
+        pos = w.batch_pos[b]
+        y, k2, v2 = R.attn_decode(I.as_f32(hs[b])[rows], raw["norm"], raw["wq"], raw["wk"], raw["wv"], raw["wo"],
+                                  I.as_raw(caches[b][0])[rows], I.as_raw(caches[b][1])[rows], pos,
+                                  w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, w.rms_eps)
+        got = batches[b].h_out.cpu().to(torch.float64).numpy()[rows]
+        err = np.abs(got - y) - (1e-2 + 2e-2 * np.abs(y))
+        assert err.max() <= 0, f"batch {b}: output off by {err.max()} beyond tolerance"
+        for name, g, o in (("K", batches[b].k_cache, k2), ("V", batches[b].v_cache, v2)):
+            gr, orow = widen(I.as_raw(g[rows].cpu())[:, :, pos, :]), widen(o[:, :, pos, :])
+            err = np.abs(gr - orow) - (1e-2 + 2e-2 * np.abs(orow))
+            assert err.max() <= 0, f"batch {b}: new {name} row off by {err.max()} beyond tolerance"
+    for b in range(w.n_batches):
+        pos = w.batch_pos[b]
+        assert torch.equal(batches[b].k_cache[:, :, :pos].cpu(), caches[b][0][:, :, :pos])
+        assert torch.equal(batches[b].v_cache[:, :, :pos].cpu(), caches[b][1][:, :, :pos])
+    assert torch.isfinite(group_out.float()).all() and (group_out != 0).any(dim=1).all()
+    ctx.close()
