@@ -171,7 +171,7 @@ void ko_dispatch(const int32_t *idx, int N, int k, int E, const int32_t *batch_o
     for (int a = 0; a < A; ++a) counts[idx[a]]++;
     offsets[0] = 0;
     for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + counts[e];
-    int32_t *seen = (int32_t *)calloc((size_t)E, sizeof(int32_t));
+    int32_t *seen = (int32_t *)calloc((size_t)(E > 0 ? E : 1), sizeof(int32_t));
     for (int a = 0; a < A; ++a) {
         int e = idx[a];
         inv_perm[a] = offsets[e] + seen[e];
