@@ -168,3 +168,35 @@ def test_corr_rank_matches_oracle_on_cpu():
             assert np.array_equal(np.asarray(got_s).view(np.uint64), want_s.view(np.uint64))
     got_e, _ = B.corr_rank(np.zeros((4, 4), dtype=int).tolist(), [1, 2, 3, 4], 2)
     assert got_e == []                                     # empty table: nothing to prefetch
+
+
+@pytest.mark.parametrize("kw", [
+    dict(d_model=200), dict(d_model=8320), dict(head_dim=48), dict(n_q_heads=6, n_kv_heads=4),
+    dict(n_q_heads=18, n_kv_heads=2), dict(n_kv_heads=0), dict(max_seqs=0), dict(max_len=0),
+    dict(n_layers=0), dict(max_group_seqs=-1), dict(rope_theta=0.0), dict(rms_eps=-1.0),
+    dict(n_q_heads=3, n_kv_heads=3, head_dim=32),   # n_q_heads*head_dim not a multiple of 128
+])
+def test_attention_config_rejections(kw):
+    from paper_2502_06888_amd import attn_binding as A
+    base = dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, max_seqs=64, max_len=576,
+                n_layers=1, max_group_seqs=0, rope_theta=1e6, rms_eps=1e-5)
+    assert A.workspace_bytes(A.MoeAttnConfig(**base)) > 0
+    base.update(kw)
+    with pytest.raises(B.MoeError) as ei:
+        A.workspace_bytes(A.MoeAttnConfig(**base))
+    assert ei.value.status == B.MOE_ERR_SHAPE and ei.value.message
+
+
+def test_attention_null_arguments():
+    from paper_2502_06888_amd import attn_binding as A
+    lib = A.load_library()
+    n = C.c_int64(0)
+    cfg = A.MoeAttnConfig(4096, 32, 8, 128, 64, 576, 1, 0, 1e6, 1e-5)
+    assert lib.moe_attn_workspace_bytes(None, C.byref(n)) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_attn_workspace_bytes(C.byref(cfg), None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_attn_forward_group(None, 0, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_attn_set_weights(None, 0, None, None, None, None, None, 0) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_attn_prefetch(None, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_attn_set_profiling(None, 1) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_attn_last_error(None)            # the calling thread's message
+    lib.moe_attn_destroy(None)                      # no-op
