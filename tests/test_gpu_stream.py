@@ -189,3 +189,33 @@ def test_measure_reports_times_and_leaves_the_context_usable():
     assert m["t_io_expert_s"] == 0.0
     assert np.array_equal(y.to(torch.float32).cpu().numpy(), want[0]["y"])
     ctx.close()
+
+
+@pytest.mark.parametrize("name,prefetch_k", [("mixtral8x22b_stream", 2), ("finegrained_stream", 6)])
+def test_full_size_streamed_stack_sampled_outputs(name, prefetch_k):
+    """The two streamed workloads at their full layer shapes and token counts, driven the way the
+    benchmark drives them (prefetch of the previous layer's busiest experts, on-demand copies for
+    the rest, a window of two layers), cut to two layers of the stack; routing bit-exact for
+    all tokens, outputs of sampled tokens against the oracle, bytes over the link as counted."""
+    w = I.scaled(I.WORKLOADS[name], n_layers=2)
+    layers, noise = [], None
+    for l in range(w.n_layers):
+        data, noise = I.gen_layer(w, l, noise, threads=16)
+        layers.append(data)
+    ctx = H.make_ctx(w)
+    for l, data in enumerate(layers):
+        H.place_layer(ctx, w, l, data, streamed=True)
+    ctx.reset_stats()
+    got = streamed_pass(ctx, w, layers, prefetch_k)
+    tokens = np.sort(np.random.Generator(np.random.PCG64(9)).choice(w.n_tokens, 6, replace=False)).astype(np.int32)
+    n_active_total = 0
+    for l, data in enumerate(layers):
+        y, counts, n_active = got[l]
+        want = H.oracle_layer(w, data, w.batch_offsets, tokens=tokens)
+        assert np.array_equal(counts, want.disp.counts), f"layer {l}: counts differ"
+        assert n_active == want.disp.n_active
+        H.check_output(y, want.y, w.dtype, tokens=tokens)
+        n_active_total += n_active
+    st = ctx.stats()
+    assert st["bytes_h2d"] == ctx.plan.expert_bytes * (n_active_total + st["n_prefetch_unused"])
+    ctx.close()
