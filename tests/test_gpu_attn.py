@@ -293,3 +293,27 @@ def test_full_size_one_pass_group():
         assert torch.equal(batches[b].v_cache[:, :, :pos].cpu(), caches[b][1][:, :, :pos])
     assert torch.isfinite(group_out.float()).all() and (group_out != 0).any(dim=1).all()
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_seeded_sweep_of_attention_shapes(seed):
+    """Head shapes, group sizes, widths, batch structures and positions drawn from a seeded
+    generator; caches on the host, on the device, or mixed."""
+    g = np.random.Generator(np.random.PCG64(2000 + seed))
+    hd = int(g.choice([32, 64, 128]))
+    per128 = 128 // hd                       # query heads come in multiples that make Hq*hd % 128 == 0
+    group = int(g.integers(1, 9))
+    hkv_unit = per128 // np.gcd(per128, group) if per128 > 1 else 1
+    hkv = int(hkv_unit * g.integers(1, 3))
+    hq = hkv * group
+    if (hq * hd) % 128 != 0 or (hkv * hd) % 32 != 0:
+        pytest.skip("draw outside the supported head shapes")
+    d = int(g.integers(1, 5)) * 128
+    nb = int(g.integers(1, 6))
+    max_len = int(g.integers(8, 200))
+    seqs = tuple(int(v) for v in g.integers(1, 40, size=nb))
+    pos = tuple(int(v) for v in g.integers(0, max_len, size=nb))
+    w = I.AttnWorkload(f"asweep{seed}", d, hq, hkv, hd, seqs, pos, max_len, rope_theta=float(g.choice([1e4, 1e6])),
+                       seed=seed)
+    where = [True, False, (True, False), (False, True)][seed % 4]
+    run_group(w, on_host=where)

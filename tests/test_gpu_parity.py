@@ -254,3 +254,28 @@ def test_fp16_option_refuses_weights_beyond_the_fp16_range():
     ctx.set_expert(0, 0, data.w1[0].to(dev), data.w3[0].to(dev), data.w2[0].to(dev))   # in range: fine
     ctx.close()
 
+
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_seeded_sweep_of_small_configurations(seed):
+    """Shapes drawn from a seeded generator: widths and expert sizes that are not powers of two,
+    1..40 experts, top-k up to 8, shared experts, empty and one-token batches, skewed routing; both
+    precisions.  Each draw goes through the same routing (bit-exact) and output checks."""
+    g = np.random.Generator(np.random.PCG64(1000 + seed))
+    bf16 = bool(seed % 4 != 3)
+    step = 64 if bf16 else 4
+    d = int(g.integers(2, 9)) * step * (1 if bf16 else 8)
+    f = int(g.integers(2, 13)) * step * (1 if bf16 else 8)
+    E = int(g.integers(1, 41))
+    k = int(g.integers(1, min(E, 8) + 1))
+    S = int(g.integers(0, 3))
+    nb = int(g.integers(1, 7))
+    sizes = [int(v) for v in g.integers(0, 90, size=nb)]
+    if seed % 5 == 0:
+        sizes[int(g.integers(0, nb))] = 1
+    if sum(sizes) == 0:
+        sizes[0] = 3
+    w = I.Workload(f"sweep{seed}", "bf16" if bf16 else "f32", d, f, E, k, n_shared=S,
+                   batch_tokens=tuple(sizes), zipf_s=1.1 if seed % 2 else 0.0, seed=seed,
+                   w_std=float(1.1 / (d * f) ** 0.25))
+    run_case(w)
