@@ -219,3 +219,43 @@ def test_full_size_streamed_stack_sampled_outputs(name, prefetch_k):
     st = ctx.stats()
     assert st["bytes_h2d"] == ctx.plan.expert_bytes * (n_active_total + st["n_prefetch_unused"])
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", list(range(6)))
+def test_seeded_sweep_of_streamed_stacks(seed):
+    """Stack depth, window, expert count, top-k, shared experts, batch structure and the number
+    of prefetched experts drawn from a seeded generator; streamed == resident bit for bit on two
+    passes, bytes over the link as counted."""
+    g = np.random.Generator(np.random.PCG64(3000 + seed))
+    E = int(g.integers(2, 17))
+    k = int(g.integers(1, min(E, 4) + 1))
+    n_layers = int(g.integers(2, 6))
+    window = int(g.integers(1, min(n_layers, 3) + 1))
+    nb = int(g.integers(1, 5))
+    sizes = tuple(int(v) for v in g.integers(0, 60, size=nb))
+    if sum(sizes) == 0:
+        sizes = (5,) + sizes[1:]
+    w = I.Workload(f"ssweep{seed}", "bf16", int(g.integers(2, 5)) * 64, int(g.integers(2, 7)) * 64, E, k,
+                   n_shared=int(g.integers(0, 2)), n_layers=n_layers, batch_tokens=sizes, streamed=True,
+                   window_layers=window, zipf_s=1.1 if seed % 2 else 0.0, corr=0.6 if seed % 2 else 0.0,
+                   seed=seed, w_std=0.08)
+    layers = gen_stack(w)
+    want = resident_reference(w, layers)
+    ctx = H.make_ctx(w)
+    for l, data in enumerate(layers):
+        H.place_layer(ctx, w, l, data, streamed=True)
+    ctx.window.fill_(0xFF)
+    torch.cuda.synchronize()
+    ctx.reset_stats()
+    # a window of one layer has no room for guesses about the next one
+    prefetch_k = int(g.integers(0, E + 1)) if window > 1 else 0
+    n_active_total = 0
+    for rep in range(2):
+        got = streamed_pass(ctx, w, layers, prefetch_k, delay_compute=bool(seed % 3 == 0))
+        for l in range(w.n_layers):
+            y, counts, n_active = got[l]
+            assert np.array_equal(y, want[l]["y"]), f"pass {rep} layer {l}: streamed != resident"
+            n_active_total += n_active
+    st = ctx.stats()
+    assert st["bytes_h2d"] == ctx.plan.expert_bytes * (n_active_total + st["n_prefetch_unused"])
+    ctx.close()
