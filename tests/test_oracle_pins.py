@@ -60,6 +60,12 @@ def test_logit_order_lane_ownership(V):
     x[0, 64 * V] = 1.0
     assert ref.gate_logits_f32(x, w, V)[0, 0] == 0.0
     assert ref.gate_logits_f64(x, w)[0, 0] == 1.0
+    # elements 0 and 1 share a 16-byte vector, hence a lane: lane 0 folds 2^24 then 1 (lost to
+    # rounding), lane 1 holds -2^24, the total is 0; were lanes to own single elements, the 1 would
+    # sit in a lane of its own and survive
+    x = np.zeros((1, d), np.float32)
+    x[0, 0], x[0, 1], x[0, V] = 2.0**24, 1.0, -(2.0**24)
+    assert ref.gate_logits_f32(x, w, V)[0, 0] == 0.0
     # within one lane the order is increasing i: (1 then 2^24) and (2^24 then 1) agree
     # here, but (2^24, 1, 1): ((2^24+1)->2^24)+1 -> 2^24, whereas 1+1 first gives 2^24+2.
     d3 = 64 * V * 3
