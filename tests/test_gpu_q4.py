@@ -145,3 +145,21 @@ def test_q4_context_refuses_plain_weights_and_vice_versa():
         ctx.set_expert_q4(0, 0, q4)
     assert ei.value.status == B.MOE_ERR_STATE
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_seeded_sweep_of_q4_configurations(seed):
+    """Widths, expert sizes (multiples of the group of 64), expert counts, top-k, shared experts and
+    batch structures drawn from a seeded generator, experts as 4-bit codes."""
+    g = np.random.Generator(np.random.PCG64(4000 + seed))
+    d = int(g.integers(2, 9)) * 64
+    f = int(g.integers(2, 11)) * 64
+    E = int(g.integers(1, 25))
+    k = int(g.integers(1, min(E, 6) + 1))
+    nb = int(g.integers(1, 6))
+    sizes = [int(v) for v in g.integers(0, 120, size=nb)]
+    if sum(sizes) == 0:
+        sizes[0] = 2
+    w = I.Workload(f"q4sweep{seed}", "bf16", d, f, E, k, n_shared=int(g.integers(0, 3)), batch_tokens=tuple(sizes),
+                   zipf_s=1.1 if seed % 2 else 0.0, seed=seed, w_std=float(1.1 / (d * f) ** 0.25))
+    run_case(w)
