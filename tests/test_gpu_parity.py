@@ -163,6 +163,23 @@ def test_plain_bf16_intermediate_option(mixtral_layer):
     assert np.all(err <= 2e-2 + 2e-2 * np.abs(want.y))
 
 
+def test_full_size_outputs_do_not_depend_on_token_order_or_batch_cut(mixtral_layer):
+    """Properties that hold at any size: a token's output depends on its own row and its own
+    experts only.  Permuting the tokens of the decode layer permutes the outputs bit for bit, and
+    cutting the same tokens into other batches (which changes the batches-per-expert counts and
+    with them the execution order) leaves every output bit unchanged."""
+    w, data, ctx = mixtral_layer
+    base = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
+    perm = np.random.Generator(np.random.PCG64(11)).permutation(w.n_tokens)
+    shuffled = H.gpu_layer(ctx, w, 0, data.x[torch.from_numpy(perm)], w.batch_offsets)
+    assert np.array_equal(shuffled["y"].view(np.uint32), base["y"][perm].view(np.uint32))
+    assert np.array_equal(shuffled["idx"], base["idx"][perm])
+    other_cut = np.array([0, 1, 2, 300, 300, 511, 512], dtype=np.int32)
+    recut = H.gpu_layer(ctx, w, 0, data.x, other_cut)
+    assert np.array_equal(recut["y"].view(np.uint32), base["y"].view(np.uint32))
+    assert np.array_equal(recut["counts"], base["counts"]) and np.array_equal(recut["perm"], base["perm"])
+
+
 def test_mixtral_prefill_full_size_sampled_outputs(mixtral_layer):
     wd, data, ctx = mixtral_layer
     w = I.WORKLOADS["mixtral8x7b_prefill"]
