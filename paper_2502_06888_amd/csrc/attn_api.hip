@@ -403,7 +403,8 @@ moe_status moe_attn_forward_group(moe_attn_ctx* ctx, int32_t layer, int32_t n_ba
     // for all rows of the group, one launch of each kernel), provided the rows fit the buffers.
     int total_rows = 0;
     for (int b = 0; b < n_batches; ++b) total_rows += batches[b].n_seq;
-    const bool grouped = !any_host && n_batches <= kMaxGroup && total_rows <= ctx->rows_alloc;
+    const int group_cap = c.max_group_seqs > c.max_seqs ? c.max_group_seqs : c.max_seqs;  // as configured, not as padded
+    const bool grouped = !any_host && n_batches <= kMaxGroup && total_rows <= group_cap;
     const int n_units = grouped ? 1 : n_batches;
     if (grouped) {
         GroupTab tab{};
