@@ -148,15 +148,19 @@ def measure_attention_batch(w, n_seq, torch, pos: int = 512) -> float:
     return best
 
 
-def fp16_intermediate_variant(w, data, args, torch, B):
-    """The same step with the opt-in H format (h_planes = 3: H and W2 as fp16 in the down
-    projection, same tolerance); reported beside the headline, which keeps the all-bf16 default."""
+H_FORMATS = {1: "bf16", 2: "bf16 pair", 3: "fp16", 4: "bf16 + e5m2 remainder"}
+
+
+def h_format_variant(w, data, args, torch, B, h_planes: int):
+    """The same step with an opt-in H format (h_planes = 4: rounding remainder of H in 8 bits on
+    the 8-bit MFMA; h_planes = 3: H and W2 as fp16 in the down projection; same tolerance),
+    reported beside the headline, which keeps the all-bf16 default."""
     dev = torch.device("cuda:0")
     compute = torch.cuda.Stream()
     cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
                         w.n_batches, B.MOE_BF16, 1)
     ctx = B.MoeContext(cfg, compute)
-    ctx.set_tuning(0, 3, 0)
+    ctx.set_tuning(0, h_planes, 0)
     ctx.set_gate(0, data.wg.to(dev))
     for e in range(w.n_experts + w.n_shared):
         ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
@@ -177,7 +181,7 @@ def fp16_intermediate_variant(w, data, args, torch, B):
         ctx.route(0, x, bo); ctx.layer_forward(0, x, y)
         prof = ctx.profile()
     ctx.close()
-    return {"h_format": "fp16", "steps": steps, "ms_per_step": ms,
+    return {"h_format": H_FORMATS[h_planes], "steps": steps, "ms_per_step": ms,
             "value": w.n_tokens / (ms * 1e-3), "unit": "tokens/s",
             "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()}}
 
@@ -585,7 +589,7 @@ def main():
                    "n_experts": w.n_experts, "top_k": w.top_k, "n_batches": w.n_batches,
                    "tokens": w.n_tokens, "experts": "resident in HBM", "weight_bits": args.weight_bits,
                    "n_active": n_active,
-                   "h_format": "f32" if w.dtype == "f32" else {0: "bf16 pair", 1: "bf16", 2: "bf16 pair", 3: "fp16"}[args.h_planes],
+                   "h_format": "f32" if w.dtype == "f32" else H_FORMATS[args.h_planes or 2],
                    "tokens_per_expert": counts},
         "roofline": roofline,
         "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()},
@@ -596,7 +600,8 @@ def main():
     ctx.close()
     if (w.dtype == "bf16" and not q4 and args.h_planes == 0 and not args.calibrate_copy
             and not args.no_variants):
-        out["opt_in_fp16_intermediate"] = fp16_intermediate_variant(w, data, args, torch, B)
+        out["opt_in_e5m2_remainder"] = h_format_variant(w, data, args, torch, B, 4)
+        out["opt_in_fp16_intermediate"] = h_format_variant(w, data, args, torch, B, 3)
     if not args.no_cpu_baseline and not q4:
         out["cpu_baseline"] = cpu_baseline(w, data)
     print(json.dumps(out))

@@ -217,10 +217,17 @@ moe_status moe_reset_stats(moe_ctx* ctx);
 
 /*
  * moe_set_tuning -- knobs, 0 keeps the current value.  split_k: split of the down projection's
- * reduction (auto by default).  h_planes (bf16 only): 2 (default) carries the intermediate
- * H = silu(X W1^T) .* (X W3^T) between the two GEMMs as a pair of bf16 numbers (value and
- * rounding remainder), which keeps the layer inside the 1e-2 absolute tolerance at d_ff = 14336;
- * 1 stores plain bf16 H (one third fewer MFMA operations, about twice the output error).
+ * reduction (auto by default).  h_planes (bf16 only) is the format of the intermediate
+ * H = silu(X W1^T) .* (X W3^T) between the two GEMMs.  2 (default) carries it as a pair of bf16
+ * numbers (value and rounding remainder, both multiplied with W2 on the bf16 MFMA), which keeps
+ * the layer inside the 1e-2 absolute tolerance at d_ff = 14336.  1 stores plain bf16 H (no
+ * remainder: about twice the output error).  4 (opt-in, bf16 experts only) carries the remainder
+ * in 8 bits instead (e5m2, nearest even, clamped to its finite range) and multiplies it with the
+ * W2 fragment converted to e5m2 in registers on the 8-bit MFMA (fp32 accumulate), the value plane
+ * staying on the bf16 MFMA: three quarters of the pair's MFMA time.  The remainder is 2^-9 of the
+ * value and its product is then good to about 2^-3, so the error H contributes is about 0.07 of
+ * plain bf16's (the pair: 2^-8 of it): inside the absolute tolerance while the outputs' typical
+ * magnitude stays below about 10, which is why it is not the default.
  * 3 (opt-in, bf16 experts only) carries H as fp16 (11 significant bits, saturating at 65504) and
  * multiplies it with W2 converted to fp16 on an fp16 MFMA: the accuracy of the pair at the cost
  * of the single plane.  The conversion of W2 happens at placement, so h_planes must be set to 3

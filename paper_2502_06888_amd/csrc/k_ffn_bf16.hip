@@ -28,6 +28,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte unit as a first-class value
 typedef const __attribute__((address_space(1))) u32x4* gptr;  // global (HBM) address space
 
@@ -54,11 +57,22 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float v) {
 // One LDS stage holds, per row block, SX reduction steps of 16 for PL planes of the activations
 // (SX * PL == 8): SX = 8, PL = 1 normally; SX = 4, PL = 2 when H is carried as a bf16 pair
 // (value + rounding remainder) through the down projection.
+//
+// R8 (H as bf16 value + 8-bit remainder, down projection only): a stage is one group of four
+// reduction steps; per row block it holds the four bf16 value fragments (unit j*64 + lane) and,
+// behind the value fragments of all row blocks, the group's remainders: 8 bytes per lane and
+// step in e5m2, [step][lane], 128 units per row block.  The eight dwords of a lane over the four
+// steps are its operand of one 32x32x64 8-bit MFMA; the weight operand is the lane's four bf16
+// fragments of the same steps converted to e5m2 in registers, so both operands assign the same
+// reduction index to the same (lane half, byte) and no data moves between lanes.
+constexpr int kR8BlkUnits = 4 * 64 + 128;       // live 16-byte units of a row block per R8 stage
+constexpr int kR8LoBase = kTileBlks * 4 * 64;   // first remainder unit of an R8 stage in LDS
 struct TileCtx {
     gptr wbase;      // weight stream of this wavefront's first unit (+lane), 64 units per step
     size_t ustride;  // 16-byte units between the streams of consecutive output units
     gptr actbase;    // packed activations at the tile's first row block (plane 0)
     size_t plane;    // units between activation planes
+    size_t lo_off;   // R8: units from actbase to the tile's remainders (nks/4 * 128 units per row block)
     u32x4* lds;
     int nks;         // reduction steps of 16 in the whole reduction
     int k0, k1;      // reduction steps of this workgroup: [k0, k1), k0 a multiple of SX
@@ -84,9 +98,49 @@ __device__ __forceinline__ void load_x(const TileCtx& c, u32x4 (&xr)[PASSES], in
     }
 }
 
-// When PASSES * T fits one LDS buffer the stores need no guard.
+// R8 stage loads.  Unit u = b * kR8BlkUnits + r of a stage is a value unit (r < 256) or a
+// remainder unit; either way its address is a per-thread offset fixed for the tile plus the
+// group index times a stride (256 units between the value fragments of consecutive groups, 128
+// between their remainders), so the loop computes one multiply-add per load and never branches.
 template <int PASSES, int T>
+struct R8Map {
+    uint32_t off[PASSES];   // units from actbase at group 0
+    uint32_t step[PASSES];  // units per group
+    __device__ __forceinline__ void init(const TileCtx& c) {
+        const int live_units = c.nblk * kR8BlkUnits;
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            int u = (int)threadIdx.x + p * T;
+            u = u < live_units ? u : 0;
+            const int b = u / kR8BlkUnits, r = u % kR8BlkUnits;
+            const bool value = r < 256;
+            off[p] = value ? (uint32_t)(b * c.nks * 64 + r)
+                           : (uint32_t)(c.lo_off + (size_t)b * c.nks * 32 + (size_t)(r - 256));
+            step[p] = value ? 256u : 128u;
+        }
+    }
+};
+template <int PASSES, int T>
+__device__ __forceinline__ void load_x_r8(const TileCtx& c, const R8Map<PASSES, T>& m,
+                                          u32x4 (&xr)[PASSES], int kbase) {
+    const uint32_t group = (uint32_t)(min(kbase, c.nks - 4) >> 2);  // past the end: the last group again
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) xr[p] = c.actbase[m.off[p] + group * m.step[p]];
+}
+
+// When PASSES * T fits one LDS buffer the stores need no guard.
+template <int PASSES, int T, int R8 = 0>
 __device__ __forceinline__ void store_x(const TileCtx& c, const u32x4 (&xr)[PASSES], int buf) {
+    if (R8) {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int u = (int)threadIdx.x + p * T;
+            const int b = u / kR8BlkUnits, r = u % kR8BlkUnits;
+            if (PASSES * T <= kTileBlks * kR8BlkUnits || u < kTileBlks * kR8BlkUnits)
+                c.lds[buf * kBufUnits + (r < 256 ? b * 256 + r : kR8LoBase + b * 128 + (r - 256))] = xr[p];
+        }
+        return;
+    }
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int u = (int)threadIdx.x + p * T;
@@ -171,6 +225,97 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
     }
 }
 
+// ---- R8: bf16 value plane + 8-bit (e5m2) remainder plane ---------------------------------------
+
+// The lane's bf16 weight fragment of one step as e5m2 (nearest even): dwords 2j, 2j+1 of the
+// 8-bit operand of the group.
+__device__ __forceinline__ void to_e5m2(const u32x4 w, int j, i32x8& q) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        // the dwords are copied to scalars first: a bit cast applied directly to an element of a
+        // vector value reads element 0 with this compiler
+        const uint32_t w0 = w[2 * h], w1 = w[2 * h + 1];
+        i16x2 v = {0, 0};
+        v = __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(v, __builtin_bit_cast(bf16x2, w0), 1.0f, false);
+        v = __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(v, __builtin_bit_cast(bf16x2, w1), 1.0f, true);
+        q[2 * j + h] = __builtin_bit_cast(int, v);
+    }
+}
+
+// Remainder products of one group for all row blocks: acc[u][b] += lo_b . e5m2(W) over 64
+// reduction indices, one 32x32x64 MFMA each (rows = tokens, cols = output columns).
+template <int NB, int U>
+__device__ __forceinline__ void lo_mfma(const u32x4* stage, const i32x8 (&wq)[U], f32x16 (&acc)[U][NB]) {
+    const int lane = threadIdx.x & 63;
+    const u32x2* lo = reinterpret_cast<const u32x2*>(stage + kR8LoBase) + lane;
+    u32x2 v[2][4];  // the operand of the next row block is read while this one multiplies
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[0][j] = lo[j * 64];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (b + 1 < NB) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[(b + 1) & 1][j] = lo[(b + 1) * 256 + j * 64];
+        }
+        const u32x2(&c)[4] = v[b & 1];
+        const i32x8 xa = {(int)c[0][0], (int)c[0][1], (int)c[1][0], (int)c[1][1],
+                          (int)c[2][0], (int)c[2][1], (int)c[3][0], (int)c[3][1]};
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            acc[u][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xa, wq[u], acc[u][b], 1, 1, 0, 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (b + 1 < NB) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
+    }
+}
+
+// A whole R8 stage: the value MFMAs of the four steps as in stage_mfma (SX = 4, one plane); each
+// step's weight fragment is converted to e5m2 before its ring slot is reloaded; the remainder
+// MFMAs of the group follow.  `stage` is the LDS buffer (no lane offset).
+template <int NB, int U, int D>
+__device__ __forceinline__ void stage_mfma_r8(const u32x4* stage, u32x4 (&w)[4][U], gptr wnext,
+                                              size_t ustride, f32x16 (&acc)[U][NB]) {
+    constexpr int NF = NB * 4;
+    constexpr int DD = D < NF ? D : NF;
+    const u32x4* L = stage + (threadIdx.x & 63);
+    u32x4 win[DD];
+    i32x8 wq[U];
+#define KMOE_FRAG_AT(t) L[(((t) % NB) * 4 + (t) / NB) * 64]
+#pragma unroll
+    for (int t = 0; t < DD; ++t) win[t] = KMOE_FRAG_AT(t);
+#pragma unroll
+    for (int t = 0; t < NF; ++t) {
+        const int j = t / NB, b = t % NB;
+        const bf16x8 xa = as_bf16x8(win[t % DD]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u][b] = mfma<1>(as_bf16x8(w[j][u]), xa, acc[u][b]);
+        if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
+        if (b == NB - 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                to_e5m2(w[j][u], j, wq[u]);
+                w[j][u] = load_stream(wnext + (size_t)u * ustride + (size_t)j * 64);
+            }
+        }
+    }
+#undef KMOE_FRAG_AT
+    __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
+#pragma unroll
+    for (int t = 0; t < NF; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
+        if (t + DD < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (t % NB == NB - 1) {
+            __builtin_amdgcn_sched_group_barrier(0x002, 4 * U, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, U, 0);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    lo_mfma<NB, U>(stage, wq, acc);
+}
+
 // Register budget of one shape: the weight ring is RING steps deep (U KiB per step in flight
 // per wavefront), the activation look-ahead DX stages.
 template <int NB, int WAVES, int U>
@@ -181,10 +326,10 @@ struct Shape2 {
 
 // Registers of the software pipeline of one tile pass: the weight ring (RS stages of SX steps,
 // U units) and the activations in flight to LDS (DX stages ahead).
-template <int NB, int WAVES, int U, int SX>
+template <int NB, int WAVES, int U, int SX, int R8 = 0>
 struct Pipe {
     static constexpr int T = WAVES * 64;
-    static constexpr int PASSES = (NB * kBlkStageUnits + T - 1) / T;
+    static constexpr int PASSES = (NB * (R8 ? kR8BlkUnits : kBlkStageUnits) + T - 1) / T;
     static constexpr int RS = Shape2<NB, WAVES, U>::RING / SX;
     // Activation look-ahead in stages.  The memory counter retires loads in issue order, so the
     // wait for a stage's activations (before they are stored to LDS) also waits for every
@@ -197,6 +342,14 @@ struct Pipe {
     static_assert(RS >= 1 && G % RS == 0 && G % DX == 0, "group must cycle ring and look-ahead");
     u32x4 wr[RS][SX][U];
     u32x4 xr[DX][PASSES];
+    R8Map<R8 ? PASSES : 1, T> r8;  // R8 only
+    template <int PL>
+    __device__ __forceinline__ void load(const TileCtx& c, int slot, int kbase) {
+        if constexpr (R8)
+            load_x_r8<PASSES, T>(c, r8, xr[slot], kbase);
+        else
+            load_x<PASSES, T, SX, PL>(c, xr[slot], kbase);
+    }
 };
 
 // Issue the loads that open a pass: activations of the first DX stages and the whole weight
@@ -204,12 +357,12 @@ struct Pipe {
 // loop head are the same on entry and on the back edge.  Nothing is waited for here: a
 // workgroup calls this for its next pass before the epilogue of the current one, so the
 // memory latency of the ring fill hides behind the epilogue.
-template <int NB, int WAVES, int U, int SX, int PL>
-__device__ __forceinline__ void open_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX>& pp) {
-    using P = Pipe<NB, WAVES, U, SX>;
+template <int NB, int WAVES, int U, int SX, int PL, int R8 = 0>
+__device__ __forceinline__ void open_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX, R8>& pp) {
+    using P = Pipe<NB, WAVES, U, SX, R8>;
 #pragma unroll
     for (int i = 0; i < P::G; ++i) {
-        if (i < P::DX) load_x<P::PASSES, P::T, SX, PL>(c, pp.xr[i], c.k0 + i * SX);
+        if (i < P::DX) pp.template load<PL>(c, i, c.k0 + i * SX);
         if (i < P::RS) {
 #pragma unroll
             for (int j = 0; j < SX; ++j)  // past the end: re-read the last step (in bounds, unused)
@@ -223,11 +376,11 @@ __device__ __forceinline__ void open_pass(const TileCtx& c, Pipe<NB, WAVES, U, S
 
 // One pass over the reduction range of the tile for the U units of every wavefront; the pass
 // must have been opened.  On return all LDS reads of the pass are behind a barrier.
-template <int MODE, int NB, int WAVES, int U, int SX, int PL, int HT = 0>
-__device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX>& pp,
+template <int MODE, int NB, int WAVES, int U, int SX, int PL, int HT = 0, int R8 = 0>
+__device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX, R8>& pp,
                                          f32x16 (&acc)[U][NB]) {
-    static_assert(SX * PL == kFragsPerBlk, "stage geometry");
-    using P = Pipe<NB, WAVES, U, SX>;
+    static_assert(R8 ? (SX == 4 && PL == 1 && MODE == 1 && HT == 0) : SX * PL == kFragsPerBlk, "stage geometry");
+    using P = Pipe<NB, WAVES, U, SX, R8>;
     constexpr int T = P::T, PASSES = P::PASSES, RS = P::RS, DX = P::DX, G = P::G;
     constexpr int D = 3;
     const int lane = threadIdx.x & 63;
@@ -239,7 +392,7 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[u][b][i] = 0.f;
 
-    store_x<PASSES, T>(c, pp.xr[0], 0);
+    store_x<PASSES, T, R8>(c, pp.xr[0], 0);
     __syncthreads();
 
     int k = c.k0, buf = 0;
@@ -249,13 +402,17 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int kk = k + g * SX;
-            load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
+            pp.template load<PL>(c, g % DX, kk + DX * SX);
             __builtin_amdgcn_sched_barrier(0);
             const u32x4* L = c.lds + buf * kBufUnits + lane;
-            stage_mfma<MODE, NB, U, SX, PL, D, HT>(L, pp.wr[g % RS],
-                                               c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc);
+            if constexpr (R8)
+                stage_mfma_r8<NB, U, D>(c.lds + buf * kBufUnits, pp.wr[g % RS],
+                                        c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc);
+            else
+                stage_mfma<MODE, NB, U, SX, PL, D, HT>(L, pp.wr[g % RS],
+                                                   c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc);
             __builtin_amdgcn_sched_barrier(0);
-            store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
+            store_x<PASSES, T, R8>(c, pp.xr[(g + 1) % DX], buf ^ 1);
             __syncthreads();
             buf ^= 1;
         }
@@ -268,12 +425,17 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
             if (kk < c.k1) {  // uniform over the workgroup
                 const bool more = kk + SX < c.k1;
                 if (kk + DX * SX < c.k1)
-                    load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
+                    pp.template load<PL>(c, g % DX, kk + DX * SX);
                 const u32x4* L = c.lds + buf * kBufUnits + lane;
+                i32x8 wq[U];  // R8 only (its stages are always whole groups)
 #pragma unroll
                 for (int j = 0; j < SX; ++j) {
                     if (kk + j < c.k1) {
                         step_mfma<MODE, NB, U, SX, PL, D, HT>(L, j, pp.wr[g % RS][j], acc);
+                        if constexpr (R8) {
+#pragma unroll
+                            for (int u = 0; u < U; ++u) to_e5m2(pp.wr[g % RS][j][u], j, wq[u]);
+                        }
                         if (kk + RS * SX + j < c.k1) {
 #pragma unroll
                             for (int u = 0; u < U; ++u)
@@ -283,7 +445,8 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
                         }
                     }
                 }
-                if (more) store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
+                if constexpr (R8) lo_mfma<NB, U>(c.lds + buf * kBufUnits, wq, acc);
+                if (more) store_x<PASSES, T, R8>(c, pp.xr[(g + 1) % DX], buf ^ 1);
                 __syncthreads();
                 buf ^= 1;
             }
@@ -368,6 +531,25 @@ __device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U
                 if (a.h_planes == 2)
                     __builtin_nontemporal_store(u32x4{lo[0], lo[1], lo[2], lo[3]},
                                                 hp + at + (size_t)a.h_plane_units);
+                if (a.h_planes == 4) {  // remainder as e5m2 (nearest even, clamped to its finite range)
+                    float r[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float gv = acc[u][b][i];
+                        const float h = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][i + 8];
+                        const float hv = __uint_as_float((hi[i / 2] >> (16 * (i % 2))) << 16);
+                        r[i] = __builtin_fminf(__builtin_fmaxf(h - hv, -57344.f), 57344.f);
+                    }
+                    uint32_t r8[2];
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2) {
+                        int v = __builtin_amdgcn_cvt_pk_bf8_f32(r[4 * h2], r[4 * h2 + 1], 0, false);
+                        v = __builtin_amdgcn_cvt_pk_bf8_f32(r[4 * h2 + 2], r[4 * h2 + 3], v, true);
+                        r8[h2] = (uint32_t)v;
+                    }
+                    u32x2* lp = reinterpret_cast<u32x2*>(hp + (size_t)a.h_plane_units);
+                    __builtin_nontemporal_store(u32x2{r8[0], r8[1]}, lp + at);
+                }
             }
         }
     }
@@ -404,27 +586,28 @@ __device__ __forceinline__ void store_down(const FfnArgs& a, const f32x16 (&acc)
 // streams U real units, wunit = min(unit0, n_units - U) onwards, so that every load stays in
 // bounds, and stores only those it owns (wunit + u >= unit0).  The loads that open pass p + 1 are
 // issued before the epilogue of pass p.
-template <int MODE, int NB, int WAVES, int U, int PL, int HT = 0>
+template <int MODE, int NB, int WAVES, int U, int PL, int HT = 0, int R8 = 0>
 __device__ __forceinline__ void run_tile(const FfnArgs& a, TileCtx c, gptr wsection, int n_units,
                                          int grp, int passes, int hblk0, int sp) {
-    constexpr int SX = 8 / PL;
+    constexpr int SX = R8 ? 4 : 8 / PL;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    Pipe<NB, WAVES, U, SX> pp;
+    Pipe<NB, WAVES, U, SX, R8> pp;
     f32x16 acc[U][NB];
     auto first_unit = [&](int p) { return ((grp * passes + p) * WAVES + wave) * U; };
     auto live = [&](int p) { return p < passes && (grp * passes + p) * WAVES * U < n_units; };
     int unit0 = first_unit(0);
     int wunit = min(unit0, n_units - U);
     c.wbase = wsection + (size_t)wunit * c.ustride + lane;
-    open_pass<NB, WAVES, U, SX, PL>(c, pp);
+    if constexpr (R8) pp.r8.init(c);
+    open_pass<NB, WAVES, U, SX, PL, R8>(c, pp);
     for (int p = 0; live(p); ++p) {  // uniform over the workgroup
-        run_pass<MODE, NB, WAVES, U, SX, PL, HT>(c, pp, acc);
+        run_pass<MODE, NB, WAVES, U, SX, PL, HT, R8>(c, pp, acc);
         const int done_wunit = wunit, done_unit0 = unit0;
         if (live(p + 1)) {
             unit0 = first_unit(p + 1);
             wunit = min(unit0, n_units - U);
             c.wbase = wsection + (size_t)wunit * c.ustride + lane;
-            open_pass<NB, WAVES, U, SX, PL>(c, pp);
+            open_pass<NB, WAVES, U, SX, PL, R8>(c, pp);
         }
         if (MODE == 0)
             store_up<NB, U>(a, acc, c.nblk, done_wunit, done_unit0, hblk0);
@@ -464,7 +647,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
 #undef CALL
 }
 
-template <int WAVES, int U, int PL, int HT = 0>
+template <int WAVES, int U, int PL, int HT = 0, int R8 = 0>
 __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups, int passes) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, a.split_k);
@@ -478,14 +661,15 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     c.ustride = (size_t)c.nks * 64;
     c.actbase = as_global(a.act) + (size_t)hblk0 * c.nks * 64;
     c.plane = (size_t)a.h_plane_units;
+    c.lo_off = (size_t)a.h_plane_units - (size_t)hblk0 * c.nks * 32;  // plane + hblk0*nks*32 - hblk0*nks*64
     c.lds = lds;
-    constexpr int SX = 8 / PL;
+    constexpr int SX = R8 ? 4 : 8 / PL;
     const int nstage = (c.nks + SX - 1) / SX;
     c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
     c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
     c.nblk = nblk;
 #define CALL(NB) \
-    run_tile<1, NB, WAVES, U, PL, HT>(a, c, as_global(blob + (size_t)a.d * a.f * 4), a.d / 32, w.grp, passes, hblk0, w.sp)
+    run_tile<1, NB, WAVES, U, PL, HT, R8>(a, c, as_global(blob + (size_t)a.d * a.f * 4), a.d / 32, w.grp, passes, hblk0, w.sp)
     NB_SWITCH(CALL)
 #undef CALL
 }
@@ -724,13 +908,13 @@ void launch_up(hipStream_t st, const FfnArgs& a) {
                        n_groups, passes);
 }
 
-template <int WAVES, int U, int PL, int HT = 0>
+template <int WAVES, int U, int PL, int HT = 0, int R8 = 0>
 void launch_down(hipStream_t st, const FfnArgs& a) {
     const int runs = (a.d / 32 + WAVES * U - 1) / (WAVES * U);
     const int passes = a.passes > 0 ? a.passes : pick_passes((int64_t)a.est_tiles * runs * a.split_k);
     const int n_groups = (runs + passes - 1) / passes;
     const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((ffn_down_kernel<WAVES, U, PL, HT>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
+    hipLaunchKernelGGL((ffn_down_kernel<WAVES, U, PL, HT, R8>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
                        st, a, n_groups, passes);
 }
 
@@ -756,6 +940,8 @@ int ffn_configure() {
     if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 2>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 1, 0, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1, 0, 1>);
     return (int)e;
 }
 
@@ -797,7 +983,9 @@ void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
         if (two) launch_down<4, 2, 1, 1>(st, a); else launch_down<8, 1, 1, 1>(st, a);
         return;
     }
-    if (a.h_planes == 2) {
+    if (a.h_planes == 4) {  // bf16 value + e5m2 remainder
+        if (two) launch_down<4, 2, 1, 0, 1>(st, a); else launch_down<8, 1, 1, 0, 1>(st, a);
+    } else if (a.h_planes == 2) {
         if (two) launch_down<4, 2, 2>(st, a); else launch_down<8, 1, 2>(st, a);
     } else {
         if (two) launch_down<4, 2, 1>(st, a); else launch_down<8, 1, 1>(st, a);

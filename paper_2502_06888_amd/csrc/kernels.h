@@ -91,8 +91,9 @@ struct FfnArgs {
     int32_t max_tiles;           // tiles the grid was sized for
     int32_t est_tiles;           // tiles the host expects to be live (launch-shape heuristic)
     int32_t d, f;
-    int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder); 3: H (and W2) as fp16
-    int64_t h_plane_units;       // 16-byte units between the two planes of H
+    int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder); 3: H (and W2) as fp16;
+                                 // 4: H as bf16 value + e5m2 remainder (f a multiple of 64)
+    int64_t h_plane_units;       // 16-byte units between the value plane and the remainder plane of H
     int32_t variant;             // kernel shape (waves per workgroup x units per wave); 0 = default
     int32_t passes;              // runs of units per workgroup (0 = chosen from the tile estimate)
     int32_t full_tiles;          // host estimate: most tiles are full (more than 160 rows per expert)

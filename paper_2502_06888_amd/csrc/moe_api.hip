@@ -180,7 +180,8 @@ struct moe_ctx {
     std::vector<HostTile> h_tiles;  // per expert id (E+S)
     int split_k_user = 0;
     int variant = 0;   // kernel shape selector of the bf16 FFN (0 = default)
-    int h_planes = 2;  // bf16 path: carry H as value + rounding remainder (2) or as plain bf16 (1)
+    int h_planes = 2;  // bf16 path, format of H between the projections: 1 plain bf16, 2 bf16 pair (default),
+                       // 3 fp16, 4 bf16 + e5m2 remainder
     // correlation-aware prefetcher
     bool corr_on = false;      // predictions allowed
     bool corr_learn = false;   // moe_route adds transitions to the table
@@ -194,6 +195,10 @@ struct moe_ctx {
 };
 
 namespace {
+
+// The 8-bit remainder format of H (h_planes 4) exists in the kernels for bf16 weights only (d_ff
+// is a multiple of 64, one group of the 8-bit MFMA, in every bf16 configuration).
+bool r8_applies(const moe_config& c) { return c.dtype == MOE_BF16 && c.weight_bits != 4; }
 
 moe_status fail(const moe_ctx* ctx, moe_status s, const char* fmt, ...) {
     char buf[512];
@@ -1178,7 +1183,9 @@ moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32
     if (variant < -1 || variant > 49) return fail(ctx, MOE_ERR_INVALID_ARG, "variant out of range");
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
     if (split_k < 0 || split_k > 64) return fail(ctx, MOE_ERR_INVALID_ARG, "split_k out of range");
-    if (h_planes < 0 || h_planes > 3) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1, 2 or 3");
+    if (h_planes < 0 || h_planes > 4) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1, 2, 3 or 4");
+    if (h_planes == 4 && !r8_applies(ctx->cfg))
+        return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes 4 (bf16 H + 8-bit remainder) needs bf16 experts");
     if (h_planes == 3 && (ctx->cfg.dtype != MOE_BF16 || ctx->cfg.weight_bits == 4))
         return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes 3 (fp16 H) needs bf16 experts");
     ctx->split_k_user = split_k;

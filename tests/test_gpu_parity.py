@@ -163,6 +163,46 @@ def test_plain_bf16_intermediate_option(mixtral_layer):
     assert np.all(err <= 2e-2 + 2e-2 * np.abs(want.y))
 
 
+def test_remainder_formats_of_the_intermediate_agree_at_full_size(mixtral_layer):
+    """The rounding remainder of H as a second bf16 plane (h_planes = 2, the default) and as 8
+    bits on the 8-bit MFMA (h_planes = 4, opt-in): both inside the tolerance on the sampled
+    tokens, and within it of each other everywhere."""
+    w, data, ctx = mixtral_layer
+    tokens = np.arange(5, w.n_tokens, 29).astype(np.int32)
+    want = H.oracle_layer(w, data, w.batch_offsets, tokens=tokens)
+    ys = {}
+    try:
+        for hp in (2, 4):
+            ctx.set_tuning(h_planes=hp)
+            got = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
+            H.check_routing(got, want, w.n_experts)
+            H.check_output(got["y"], want.y, w.dtype, tokens)
+            ys[hp] = got["y"]
+    finally:
+        ctx.set_tuning(h_planes=2)
+    assert np.all(np.abs(ys[2] - ys[4]) <= 1e-2 + 2e-2 * np.abs(ys[2]))
+    assert (ys[2] != ys[4]).mean() < 0.2             # most outputs round to the same bf16
+
+
+@pytest.mark.parametrize("w", [
+    SMALL,
+    I.scaled(SMALL, name="one_group", d_model=128, d_ff=64, batch_tokens=(5,)),
+    I.scaled(SMALL, name="ragged_192", d_model=128, d_ff=192, batch_tokens=(33, 1, 17, 300)),
+    I.scaled(SMALL, name="many_rows", d_model=256, d_ff=320, batch_tokens=(700, 3)),
+], ids=lambda w: w.name)
+def test_remainder_formats_on_small_shapes(w):
+    """Each H format that carries a remainder, chosen explicitly, against the oracle: one group
+    of 64, a reduction that ends inside the pipeline's look-ahead, tiles of every row-block class."""
+    data, _ = I.gen_layer(w, 0)
+    ctx = H.make_ctx(w)
+    H.place_layer(ctx, w, 0, data)
+    for hp in (2, 4):
+        for split_k, variant in ((1, 1), (3, 1), (2, 3)):   # 8 wavefronts x 1 unit, 4 x 2
+            ctx.set_tuning(split_k, hp, variant)
+            run_case(w, data=data, ctx=ctx)
+    ctx.close()
+
+
 def test_full_size_outputs_do_not_depend_on_token_order_or_batch_cut(mixtral_layer):
     """Properties that hold at any size: a token's output depends on its own row and its own
     experts only.  Permuting the tokens of the decode layer permutes the outputs bit for bit, and

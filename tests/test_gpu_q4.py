@@ -138,6 +138,10 @@ def test_q4_context_refuses_plain_weights_and_vice_versa():
     with pytest.raises(B.MoeError) as ei:
         ctx.set_expert(0, 0, data.w1[0].to(dev), data.w3[0].to(dev), data.w2[0].to(dev))
     assert ei.value.status == B.MOE_ERR_STATE
+    for h_planes in (3, 4):                          # H formats of the bf16-weight kernels only
+        with pytest.raises(B.MoeError) as ei:
+            ctx.set_tuning(0, h_planes, 0)
+        assert ei.value.status == B.MOE_ERR_INVALID_ARG
     ctx.close()
     ctx = H.make_ctx(w)
     q4 = tuple(tuple(t.to(dev) for t in trip) for trip in I.gen_expert_q4(w, 0, 0))
