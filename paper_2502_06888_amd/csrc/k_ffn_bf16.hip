@@ -85,6 +85,26 @@ struct TileCtx {
 // live MFMA reads.
 template <int PASSES, int T, int SX, int PL>
 __device__ __forceinline__ void load_x(const TileCtx& c, u32x4 (&xr)[PASSES], int kbase) {
+    if constexpr (T % 64 == 0 && kBlkStageUnits % 64 == 0) {
+        // A wavefront's 64 units of one pass are one fragment: (row block, plane, step) is the
+        // same for all its lanes, so everything but the lane offset is scalar arithmetic and the
+        // load takes a scalar base.  (Computed per lane, the 16 passes of the four-wavefront
+        // shape cost a hundred vector instructions per stage and forty registers, whose spills
+        // are reloaded before the loop and then waited for in every stage.)
+        const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
+        const int live_frags = c.nblk * (kBlkStageUnits / 64);
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            int fr = wave + p * (T / 64);  // fragment of the stage; past the live part: fragment 0
+            fr = fr < live_frags ? fr : 0;
+            const int b = fr / (kBlkStageUnits / 64), r = fr % (kBlkStageUnits / 64);
+            const int pl = r / SX, j = r % SX;
+            const int ks = min(kbase + j, c.nks - 1);
+            const size_t at = (size_t)pl * c.plane + ((size_t)b * c.nks + ks) * 64;  // uniform
+            xr[p] = (c.actbase + at)[lane];
+        }
+        return;
+    }
     const int live_units = c.nblk * kBlkStageUnits;
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
@@ -192,15 +212,23 @@ __device__ __forceinline__ void step_mfma(const u32x4* L, int j, const u32x4 (&w
 // each ring slot is reloaded right after the last MFMA that reads it.  Order pinned: D reads,
 // then per fragment U MFMAs and one read (while any are left) and, after the last fragment of a
 // step, the U reloads of that step's slot.
-template <int MODE, int NB, int U, int SX, int PL, int D, int HT = 0>
+template <int MODE, int NB, int U, int SX, int PL, int D, int HT, int PASSES, int T, int DX>
 __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gptr wnext,
-                                           size_t ustride, f32x16 (&acc)[U][NB]) {
+                                           size_t ustride, f32x16 (&acc)[U][NB],
+                                           u32x4* next_buf, const u32x4 (&xs)[PASSES]) {
     constexpr int NS = NB * PL;   // fragments per step
     constexpr int NF = NS * SX;   // fragments per stage
     constexpr int DD = D < NF ? D : NF;
+    // The activations of the next stage go to the other LDS buffer between the MFMAs instead of
+    // in one burst before the barrier (a burst of PASSES KiB per wavefront keeps the LDS write
+    // port, and with one wavefront per SIMD the matrix cores, busy doing nothing else).  With a
+    // look-ahead of one stage their loads were issued at the top of this stage, so the stores
+    // start at its middle; with more they can start at once.
+    constexpr int S0 = DX == 1 ? NF / 2 : 0;
     u32x4 win[DD];
     // fragment t of the stage: step t / NS, (row block, plane) t % NS
 #define KMOE_FRAG_AT(t) L[(((t) % NS) * SX + (t) / NS) * 64]
+#define KMOE_STORE_AT(p) (S0 + ((p) * (NF - S0)) / PASSES)
 #pragma unroll
     for (int t = 0; t < DD; ++t) win[t] = KMOE_FRAG_AT(t);
 #pragma unroll
@@ -210,19 +238,30 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
 #pragma unroll
         for (int u = 0; u < U; ++u) acc[u][b] = mfma<MODE, HT>(as_bf16x8(w[j][u]), xa, acc[u][b]);
         if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            if (KMOE_STORE_AT(p) == t) {
+                const int u = (int)threadIdx.x + p * T;
+                if (PASSES * T <= kBufUnits || u < kBufUnits) next_buf[u] = xs[p];
+            }
+        }
         if (t % NS == NS - 1) {
 #pragma unroll
             for (int u = 0; u < U; ++u) w[j][u] = load_stream(wnext + (size_t)u * ustride + (size_t)j * 64);
         }
     }
-#undef KMOE_FRAG_AT
     __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
 #pragma unroll
     for (int t = 0; t < NF; ++t) {
         __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
         if (t + DD < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p)
+            if (KMOE_STORE_AT(p) == t) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
         if (t % NS == NS - 1) __builtin_amdgcn_sched_group_barrier(0x020, U, 0);
     }
+#undef KMOE_FRAG_AT
+#undef KMOE_STORE_AT
 }
 
 // ---- R8: bf16 value plane + 8-bit (e5m2) remainder plane ---------------------------------------
@@ -409,10 +448,11 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
                 stage_mfma_r8<NB, U, D>(c.lds + buf * kBufUnits, pp.wr[g % RS],
                                         c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc);
             else
-                stage_mfma<MODE, NB, U, SX, PL, D, HT>(L, pp.wr[g % RS],
-                                                   c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc);
+                stage_mfma<MODE, NB, U, SX, PL, D, HT, PASSES, T, DX>(
+                    L, pp.wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc,
+                    c.lds + (buf ^ 1) * kBufUnits, pp.xr[(g + 1) % DX]);
             __builtin_amdgcn_sched_barrier(0);
-            store_x<PASSES, T, R8>(c, pp.xr[(g + 1) % DX], buf ^ 1);
+            if constexpr (R8) store_x<PASSES, T, R8>(c, pp.xr[(g + 1) % DX], buf ^ 1);
             __syncthreads();
             buf ^= 1;
         }
@@ -460,7 +500,14 @@ struct Wg {
 };
 
 // XCD-aware map from the hardware workgroup id (dealt round-robin to the 8 XCDs) to a logical
-// id such that each XCD walks a contiguous range of (tile, split, group) items.
+// id such that each XCD walks a contiguous range of (tile, split, group) items.  Two orders of
+// that range.  Small tiles (an expert is one tile; the weights are read once whatever the
+// order): all items of a tile, then the next tile, so the tile's activations stay in the XCD's
+// L2.  Full tiles (an expert spans many tiles and each of them streams the expert's weights
+// again): panels of kPanelTiles tiles x kPanelCols items, so that the workgroups an XCD runs at
+// the same time share both the activations of a few tiles and a few weight streams, and most
+// weight reads are L2 hits behind the first workgroup of a column.
+constexpr int kPanelTiles = 4, kPanelCols = 8;
 __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) {
     Wg w;
     const int ntile = *a.tile_count;
@@ -471,8 +518,20 @@ __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) 
     const int seq = id / kXcd;
     const int L = (id % kXcd) * per_xcd + seq;
     w.live = seq < per_xcd && L < live;
-    w.tile = (a.tile_first ? *a.tile_first : 0) + L / per_tile;
-    const int r = L % per_tile;
+    int tile, r;
+    if (a.full_tiles) {
+        const int pt = a.panel ? 1 << (a.panel - 1) : kPanelTiles, pc = a.panel ? max(1, 32 >> (a.panel - 1)) : kPanelCols;
+        const int panel_items = pt * per_tile;
+        const int tp = L / panel_items, l = L - tp * panel_items;
+        const int rows = max(1, min(pt, ntile - tp * pt));  // the last panel may be short (ids past the end: 1)
+        const int cb = l / (rows * pc), m = l - cb * rows * pc;
+        tile = tp * pt + m % rows;
+        r = cb * pc + m / rows;  // < per_tile: the last column block holds rows * (its width) items
+    } else {
+        tile = L / per_tile;
+        r = L % per_tile;
+    }
+    w.tile = (a.tile_first ? *a.tile_first : 0) + tile;
     w.sp = r / n_groups;
     w.grp = r % n_groups;
     return w;
@@ -590,7 +649,7 @@ template <int MODE, int NB, int WAVES, int U, int PL, int HT = 0, int R8 = 0>
 __device__ __forceinline__ void run_tile(const FfnArgs& a, TileCtx c, gptr wsection, int n_units,
                                          int grp, int passes, int hblk0, int sp) {
     constexpr int SX = R8 ? 4 : 8 / PL;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
     Pipe<NB, WAVES, U, SX, R8> pp;
     f32x16 acc[U][NB];
     auto first_unit = [&](int p) { return ((grp * passes + p) * WAVES + wave) * U; };
@@ -827,7 +886,7 @@ __device__ __forceinline__ void run_tile_q4(const FfnArgs& a, TileCtx c, const u
                                             const uint8_t* sz_section, int n_units, int grp,
                                             int hblk0, int sp) {
     constexpr int SX = 8 / PL;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int unit0 = grp * WAVES + wave;
     const int wunit = min(unit0, n_units - 1);
     const size_t quads = (size_t)c.nks / 4;
