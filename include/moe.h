@@ -235,8 +235,9 @@ moe_status moe_reset_stats(moe_ctx* ctx);
  * to fp16 subnormals (absolute error at most 2^-25) and fails with MOE_ERR_SHAPE on larger ones.
  * moe_layer_forward returns MOE_ERR_STATE when the experts were placed for another H format.
  * variant: launch shape of the bf16 expert kernels, ones digit: 1 = 8 wavefronts x 1 output unit,
- * 2 = 7 x 1, 3 = 4 x 2 (0 = chosen by tile size); tens digit: passes per workgroup (0 = default);
- * -1 selects the defaults again.
+ * 2 = 7 x 1, 3 = 4 x 2 (0 = chosen by tile size); tens digit p (1..6): on full tiles the workgroups
+ * an XCD runs together cover 2^(p-1) tiles x 32/2^(p-1) unit groups (0 = 4 x 8); -1 selects the
+ * defaults again.
  */
 moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant);
 

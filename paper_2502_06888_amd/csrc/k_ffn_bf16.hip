@@ -83,40 +83,37 @@ struct TileCtx {
 // Lanes past the live part of the tile re-read unit 0, steps past the end of the reduction
 // re-read the last step: both in bounds, and what is then stored lands in LDS slots that no
 // live MFMA reads.
+// Where the units of a stage come from.  The workgroup is whole wavefronts of 64 and a row
+// block's stage part is a multiple of 64 units, so the 64 units a wavefront loads in one pass are
+// one fragment: (row block, plane, step) is the same for all its lanes and everything but the
+// lane offset is scalar, computed once per tile.  (Computed per lane and per stage, the 16 passes
+// of the four-wavefront shape cost a hundred vector instructions per stage and forty registers,
+// whose spills are reloaded before the loop and then waited for in every stage.)
 template <int PASSES, int T, int SX, int PL>
-__device__ __forceinline__ void load_x(const TileCtx& c, u32x4 (&xr)[PASSES], int kbase) {
-    if constexpr (T % 64 == 0 && kBlkStageUnits % 64 == 0) {
-        // A wavefront's 64 units of one pass are one fragment: (row block, plane, step) is the
-        // same for all its lanes, so everything but the lane offset is scalar arithmetic and the
-        // load takes a scalar base.  (Computed per lane, the 16 passes of the four-wavefront
-        // shape cost a hundred vector instructions per stage and forty registers, whose spills
-        // are reloaded before the loop and then waited for in every stage.)
-        const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
-        const int live_frags = c.nblk * (kBlkStageUnits / 64);
+struct XMap {
+    static_assert(T % 64 == 0 && kBlkStageUnits % 64 == 0, "a pass of a wavefront is one fragment");
+    size_t base[PASSES];  // units from actbase to (row block, plane) of pass p at step 0, uniform
+    int step[PASSES];     // step of the stage, uniform
+    __device__ __forceinline__ void init(const TileCtx& c) {
+        const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+        const int live = c.nblk * (kBlkStageUnits / 64);
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
             int fr = wave + p * (T / 64);  // fragment of the stage; past the live part: fragment 0
-            fr = fr < live_frags ? fr : 0;
+            fr = fr < live ? fr : 0;
             const int b = fr / (kBlkStageUnits / 64), r = fr % (kBlkStageUnits / 64);
-            const int pl = r / SX, j = r % SX;
-            const int ks = min(kbase + j, c.nks - 1);
-            const size_t at = (size_t)pl * c.plane + ((size_t)b * c.nks + ks) * 64;  // uniform
-            xr[p] = (c.actbase + at)[lane];
+            base[p] = (size_t)(r / SX) * c.plane + (size_t)b * c.nks * 64;
+            step[p] = r % SX;
         }
-        return;
     }
-    const int live_units = c.nblk * kBlkStageUnits;
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-        int u = (int)threadIdx.x + p * T;
-        u = u < live_units ? u : 0;
-        const int b = u / kBlkStageUnits, r = u % kBlkStageUnits;
-        const int pl = r / (SX * 64);
-        const int j = (r / 64) % SX;
-        const int ks = min(kbase + j, c.nks - 1);
-        xr[p] = c.actbase[(size_t)pl * c.plane + ((size_t)b * c.nks + ks) * 64 + (r & 63)];
+    // CLAMP: steps past the end of the reduction re-read the last step; the steady state never
+    // gets there and skips the test.
+    template <bool CLAMP>
+    __device__ __forceinline__ u32x4 load(const TileCtx& c, int p, int kbase) const {
+        const int ks = CLAMP ? min(kbase + step[p], c.nks - 1) : kbase + step[p];
+        return (c.actbase + base[p] + (size_t)ks * 64)[threadIdx.x & 63];
     }
-}
+};
 
 // R8 stage loads.  Unit u = b * kR8BlkUnits + r of a stage is a value unit (r < 256) or a
 // remainder unit; either way its address is a per-thread offset fixed for the tile plus the
@@ -215,20 +212,26 @@ __device__ __forceinline__ void step_mfma(const u32x4* L, int j, const u32x4 (&w
 template <int MODE, int NB, int U, int SX, int PL, int D, int HT, int PASSES, int T, int DX>
 __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gptr wnext,
                                            size_t ustride, f32x16 (&acc)[U][NB],
-                                           u32x4* next_buf, const u32x4 (&xs)[PASSES]) {
+                                           u32x4* next_buf, const u32x4 (&xs)[PASSES],
+                                           const TileCtx& c, const XMap<PASSES, T, SX, PL>& xm,
+                                           int kload, u32x4 (&xl)[PASSES]) {
     constexpr int NS = NB * PL;   // fragments per step
     constexpr int NF = NS * SX;   // fragments per stage
     constexpr int DD = D < NF ? D : NF;
-    // The activations of the next stage go to the other LDS buffer between the MFMAs instead of
-    // in one burst before the barrier (a burst of PASSES KiB per wavefront keeps the LDS write
-    // port, and with one wavefront per SIMD the matrix cores, busy doing nothing else).  With a
-    // look-ahead of one stage their loads were issued at the top of this stage, so the stores
-    // start at its middle; with more they can start at once.
+    // The traffic of the activations rides between the MFMAs: with one wavefront per SIMD every
+    // instruction issued ahead of the first MFMA of a stage, and every burst that holds a port,
+    // is time the matrix cores idle.  xl (the stage at reduction step kload) is loaded from
+    // memory one pass per fragment, xs (the next stage) goes to the other LDS buffer the same
+    // way.  With a look-ahead of one stage xl and xs are the same registers: loads in the first
+    // quarter of the stage, stores in its second half; otherwise both spread over the stage.
+    constexpr int L1 = DX == 1 ? (NF / 4 > PASSES ? NF / 4 : PASSES) : NF;
     constexpr int S0 = DX == 1 ? NF / 2 : 0;
     u32x4 win[DD];
     // fragment t of the stage: step t / NS, (row block, plane) t % NS
 #define KMOE_FRAG_AT(t) L[(((t) % NS) * SX + (t) / NS) * 64]
+#define KMOE_LOAD_AT(p) (((p) * L1) / PASSES)
 #define KMOE_STORE_AT(p) (S0 + ((p) * (NF - S0)) / PASSES)
+    static_assert(PASSES <= NF / 2, "one pass per fragment at most");
 #pragma unroll
     for (int t = 0; t < DD; ++t) win[t] = KMOE_FRAG_AT(t);
 #pragma unroll
@@ -238,12 +241,16 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
 #pragma unroll
         for (int u = 0; u < U; ++u) acc[u][b] = mfma<MODE, HT>(as_bf16x8(w[j][u]), xa, acc[u][b]);
         if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            if (KMOE_STORE_AT(p) == t) {
+        {   // the pass stored at this fragment, if any (both maps are strictly increasing in p)
+            const int p = t < S0 ? PASSES : ((t - S0) * PASSES + (NF - S0) - 1) / (NF - S0);
+            if (p < PASSES && KMOE_STORE_AT(p) == t) {
                 const int u = (int)threadIdx.x + p * T;
                 if (PASSES * T <= kBufUnits || u < kBufUnits) next_buf[u] = xs[p];
             }
+        }
+        {   // the pass loaded at this fragment, if any
+            const int p = (t * PASSES + L1 - 1) / L1;
+            if (p < PASSES && KMOE_LOAD_AT(p) == t) xl[p] = xm.template load<false>(c, p, kload);
         }
         if (t % NS == NS - 1) {
 #pragma unroll
@@ -255,12 +262,14 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
     for (int t = 0; t < NF; ++t) {
         __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
         if (t + DD < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p)
-            if (KMOE_STORE_AT(p) == t) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        const int ps = t < S0 ? PASSES : ((t - S0) * PASSES + (NF - S0) - 1) / (NF - S0);
+        if (ps < PASSES && KMOE_STORE_AT(ps) == t) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        const int pl = (t * PASSES + L1 - 1) / L1;
+        if (pl < PASSES && KMOE_LOAD_AT(pl) == t) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         if (t % NS == NS - 1) __builtin_amdgcn_sched_group_barrier(0x020, U, 0);
     }
 #undef KMOE_FRAG_AT
+#undef KMOE_LOAD_AT
 #undef KMOE_STORE_AT
 }
 
@@ -382,12 +391,19 @@ struct Pipe {
     u32x4 wr[RS][SX][U];
     u32x4 xr[DX][PASSES];
     R8Map<R8 ? PASSES : 1, T> r8;  // R8 only
+    XMap<R8 ? 1 : PASSES, T, SX, 8 / SX> xm;  // the other formats
+    __device__ __forceinline__ void init(const TileCtx& c) {
+        if constexpr (R8) r8.init(c); else xm.init(c);
+    }
     template <int PL>
     __device__ __forceinline__ void load(const TileCtx& c, int slot, int kbase) {
-        if constexpr (R8)
+        if constexpr (R8) {
             load_x_r8<PASSES, T>(c, r8, xr[slot], kbase);
-        else
-            load_x<PASSES, T, SX, PL>(c, xr[slot], kbase);
+        } else {
+            static_assert(PL == 8 / SX, "planes per stage");
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) xr[slot][p] = xm.template load<true>(c, p, kbase);
+        }
     }
 };
 
@@ -441,7 +457,7 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int kk = k + g * SX;
-            pp.template load<PL>(c, g % DX, kk + DX * SX);
+            if constexpr (R8) pp.template load<PL>(c, g % DX, kk + DX * SX);
             __builtin_amdgcn_sched_barrier(0);
             const u32x4* L = c.lds + buf * kBufUnits + lane;
             if constexpr (R8)
@@ -450,7 +466,7 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
             else
                 stage_mfma<MODE, NB, U, SX, PL, D, HT, PASSES, T, DX>(
                     L, pp.wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc,
-                    c.lds + (buf ^ 1) * kBufUnits, pp.xr[(g + 1) % DX]);
+                    c.lds + (buf ^ 1) * kBufUnits, pp.xr[(g + 1) % DX], c, pp.xm, kk + DX * SX, pp.xr[g % DX]);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (R8) store_x<PASSES, T, R8>(c, pp.xr[(g + 1) % DX], buf ^ 1);
             __syncthreads();
@@ -639,40 +655,30 @@ __device__ __forceinline__ void store_down(const FfnArgs& a, const f32x16 (&acc)
     }
 }
 
-// All passes of a workgroup over its tile.  A workgroup serves WAVES * U consecutive output
-// units per pass and `passes` consecutive such runs; wavefront w owns, in pass p, the units
-// unit0 = ((grp * passes + p) * WAVES + w) * U .. unit0 + U - 1, as far as they exist.  It always
-// streams U real units, wunit = min(unit0, n_units - U) onwards, so that every load stays in
-// bounds, and stores only those it owns (wunit + u >= unit0).  The loads that open pass p + 1 are
-// issued before the epilogue of pass p.
+// One workgroup, one tile, WAVES * U consecutive output units: wavefront w owns the units
+// unit0 = (grp * WAVES + w) * U .. unit0 + U - 1, as far as they exist.  It always streams U real
+// units, wunit = min(unit0, n_units - U) onwards, so that every load stays in bounds, and stores
+// only those it owns (wunit + u >= unit0).  (Several such runs per workgroup, with the next
+// run's loads issued before the epilogue, were measured to gain nothing, and the loop around
+// the reduction loop made the compiler wait in every stage for reloads it had placed on the
+// outer back edge.)
 template <int MODE, int NB, int WAVES, int U, int PL, int HT = 0, int R8 = 0>
 __device__ __forceinline__ void run_tile(const FfnArgs& a, TileCtx c, gptr wsection, int n_units,
-                                         int grp, int passes, int hblk0, int sp) {
+                                         int grp, int hblk0, int sp) {
     constexpr int SX = R8 ? 4 : 8 / PL;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
     Pipe<NB, WAVES, U, SX, R8> pp;
     f32x16 acc[U][NB];
-    auto first_unit = [&](int p) { return ((grp * passes + p) * WAVES + wave) * U; };
-    auto live = [&](int p) { return p < passes && (grp * passes + p) * WAVES * U < n_units; };
-    int unit0 = first_unit(0);
-    int wunit = min(unit0, n_units - U);
+    const int unit0 = (grp * WAVES + wave) * U;
+    const int wunit = min(unit0, n_units - U);
     c.wbase = wsection + (size_t)wunit * c.ustride + lane;
-    if constexpr (R8) pp.r8.init(c);
+    pp.init(c);
     open_pass<NB, WAVES, U, SX, PL, R8>(c, pp);
-    for (int p = 0; live(p); ++p) {  // uniform over the workgroup
-        run_pass<MODE, NB, WAVES, U, SX, PL, HT, R8>(c, pp, acc);
-        const int done_wunit = wunit, done_unit0 = unit0;
-        if (live(p + 1)) {
-            unit0 = first_unit(p + 1);
-            wunit = min(unit0, n_units - U);
-            c.wbase = wsection + (size_t)wunit * c.ustride + lane;
-            open_pass<NB, WAVES, U, SX, PL, R8>(c, pp);
-        }
-        if (MODE == 0)
-            store_up<NB, U>(a, acc, c.nblk, done_wunit, done_unit0, hblk0);
-        else
-            store_down<NB, U>(a, acc, c.nblk, done_wunit, done_unit0, hblk0, sp);
-    }
+    run_pass<MODE, NB, WAVES, U, SX, PL, HT, R8>(c, pp, acc);
+    if (MODE == 0)
+        store_up<NB, U>(a, acc, c.nblk, wunit, unit0, hblk0);
+    else
+        store_down<NB, U>(a, acc, c.nblk, wunit, unit0, hblk0, sp);
 }
 
 #define NB_SWITCH(CALL)                       \
@@ -684,7 +690,7 @@ __device__ __forceinline__ void run_tile(const FfnArgs& a, TileCtx c, gptr wsect
 static_assert(kTileBlks == 8, "row-block classes above cover tiles of up to 8 blocks");
 
 template <int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_groups, int passes) {
+__global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_groups) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, 1);
     if (!w.live) return;
@@ -701,13 +707,13 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
     c.k0 = 0;
     c.k1 = c.nks;
     c.nblk = nblk;
-#define CALL(NB) run_tile<0, NB, WAVES, U, 1>(a, c, as_global(blob), a.f / 16, w.grp, passes, hblk0, 0)
+#define CALL(NB) run_tile<0, NB, WAVES, U, 1>(a, c, as_global(blob), a.f / 16, w.grp, hblk0, 0)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
 template <int WAVES, int U, int PL, int HT = 0, int R8 = 0>
-__global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups, int passes) {
+__global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, a.split_k);
     if (!w.live) return;
@@ -728,15 +734,10 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
     c.nblk = nblk;
 #define CALL(NB) \
-    run_tile<1, NB, WAVES, U, PL, HT, R8>(a, c, as_global(blob + (size_t)a.d * a.f * 4), a.d / 32, w.grp, passes, hblk0, w.sp)
+    run_tile<1, NB, WAVES, U, PL, HT, R8>(a, c, as_global(blob + (size_t)a.d * a.f * 4), a.d / 32, w.grp, hblk0, w.sp)
     NB_SWITCH(CALL)
 #undef CALL
 }
-
-// Passes per workgroup.  Measured on the decode layer, more than one pass per workgroup (which
-// hides the ring fill of the next pass behind the epilogue) gains nothing: the kernel is bound
-// chip-wide, not per workgroup.  One pass keeps the most workgroups in flight.
-static int pick_passes(int64_t) { return 1; }
 
 // ---- 4-bit group-quantised expert weights ------------------------------------------------------
 //
@@ -781,6 +782,11 @@ struct PipeQ {
     u32x4 wq[RQ];
     uint32_t sz[RQ];
     u32x4 xr[DX][PASSES];
+    XMap<PASSES, T, SX, 8 / SX> xm;
+    __device__ __forceinline__ void load(const TileCtx& c, int slot, int kbase) {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) xr[slot][p] = xm.template load<true>(c, p, kbase);
+    }
 };
 
 template <int NB, int WAVES, int SX, int PL>
@@ -788,7 +794,7 @@ __device__ __forceinline__ void open_pass_q4(const TileCtx& c, const QCtx& q, Pi
     using P = PipeQ<NB, WAVES, SX>;
 #pragma unroll
     for (int i = 0; i < P::G; ++i) {
-        if (i < P::DX) load_x<P::PASSES, P::T, SX, PL>(c, pp.xr[i], c.k0 + i * SX);
+        if (i < P::DX) pp.load(c, i, c.k0 + i * SX);
         if (i < P::RS) {
 #pragma unroll
             for (int h = 0; h < P::QS; ++h) {  // past the end: re-read the last quad (in bounds, unused)
@@ -821,7 +827,7 @@ __device__ __forceinline__ void run_pass_q4(const TileCtx& c, const QCtx& q, Pip
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int kk = k + g * SX;
-            load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
+            pp.load(c, g % DX, kk + DX * SX);
             __builtin_amdgcn_sched_barrier(0);
             const u32x4* L = c.lds + buf * kBufUnits + lane;
             u32x4 win[DD];
@@ -855,7 +861,7 @@ __device__ __forceinline__ void run_pass_q4(const TileCtx& c, const QCtx& q, Pip
             if (kk < c.k1) {  // uniform over the workgroup
                 const bool more = kk + SX < c.k1;
                 if (kk + DX * SX < c.k1)
-                    load_x<PASSES, T, SX, PL>(c, pp.xr[g % DX], kk + DX * SX);
+                    pp.load(c, g % DX, kk + DX * SX);
                 const u32x4* L = c.lds + buf * kBufUnits + lane;
 #pragma unroll
                 for (int j = 0; j < SX; ++j) {
@@ -894,6 +900,7 @@ __device__ __forceinline__ void run_tile_q4(const FfnArgs& a, TileCtx c, const u
     q.nib = as_global(nib_section) + (size_t)wunit * quads * 64 + lane;
     q.sz = (gptr32)(uintptr_t)sz_section + (size_t)wunit * quads * 32 + (lane & 31);
     PipeQ<NB, WAVES, SX> pp;
+    pp.xm.init(c);
     f32x16 acc[1][NB];
     open_pass_q4<NB, WAVES, SX, PL>(c, q, pp);
     run_pass_q4<MODE, NB, WAVES, SX, PL>(c, q, pp, acc);
@@ -959,22 +966,18 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_q4_kernel(FfnArgs a, int 
 
 template <int WAVES, int U>
 void launch_up(hipStream_t st, const FfnArgs& a) {
-    const int runs = (a.f / 16 + WAVES * U - 1) / (WAVES * U);
-    const int passes = a.passes > 0 ? a.passes : pick_passes((int64_t)a.est_tiles * runs);
-    const int n_groups = (runs + passes - 1) / passes;
+    const int n_groups = (a.f / 16 + WAVES * U - 1) / (WAVES * U);
     const int grid = (a.max_tiles * n_groups + kXcd - 1) / kXcd * kXcd;
     hipLaunchKernelGGL((ffn_up_kernel<WAVES, U>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st, a,
-                       n_groups, passes);
+                       n_groups);
 }
 
 template <int WAVES, int U, int PL, int HT = 0, int R8 = 0>
 void launch_down(hipStream_t st, const FfnArgs& a) {
-    const int runs = (a.d / 32 + WAVES * U - 1) / (WAVES * U);
-    const int passes = a.passes > 0 ? a.passes : pick_passes((int64_t)a.est_tiles * runs * a.split_k);
-    const int n_groups = (runs + passes - 1) / passes;
+    const int n_groups = (a.d / 32 + WAVES * U - 1) / (WAVES * U);
     const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
     hipLaunchKernelGGL((ffn_down_kernel<WAVES, U, PL, HT, R8>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
-                       st, a, n_groups, passes);
+                       st, a, n_groups);
 }
 
 template <typename K>

@@ -95,8 +95,7 @@ struct FfnArgs {
                                  // 4: H as bf16 value + e5m2 remainder (f a multiple of 64)
     int64_t h_plane_units;       // 16-byte units between the value plane and the remainder plane of H
     int32_t variant;             // kernel shape (waves per workgroup x units per wave); 0 = default
-    int32_t passes;              // runs of units per workgroup (0 = chosen from the tile estimate)
-    int32_t panel;               // full tiles: log2 of the tiles per panel + 1 (0 = default)
+    int32_t panel;               // full tiles: 1 + log2 of the tiles per panel of the workgroup order (0 = default)
     int32_t full_tiles;          // host estimate: most tiles are full (more than 160 rows per expert)
     int32_t weight_bits;         // 0/16: bf16 weights; 4: 4-bit codes in groups of 64 with (s, z)
     int32_t split_k;             // down projection only

@@ -808,8 +808,7 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
     a.f = s.f;
     a.o_split_stride = ctx->L.o_split_stride;
     a.variant = ctx->variant % 10;
-    a.passes = ctx->variant / 10 % 10;
-    a.panel = ctx->variant / 100;
+    a.panel = ctx->variant / 10;
     a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
     a.h_planes = ctx->h_planes;
     a.h_plane_units = ctx->L.h_plane_units;
@@ -1047,8 +1046,7 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
         a.f = s.f;
         a.o_split_stride = ctx->L.o_split_stride;
         a.variant = ctx->variant % 10;
-        a.passes = ctx->variant / 10 % 10;
-        a.panel = ctx->variant / 100;
+        a.panel = ctx->variant / 10;
         a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
         a.h_planes = ctx->h_planes;
         a.h_plane_units = ctx->L.h_plane_units;
@@ -1182,7 +1180,7 @@ moe_status moe_corr_predict(moe_ctx* ctx, int32_t layer, int32_t K, int32_t* exp
 }
 
 moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant) {
-    if (variant < -1 || variant > 949) return fail(ctx, MOE_ERR_INVALID_ARG, "variant out of range");
+    if (variant < -1 || variant > 69) return fail(ctx, MOE_ERR_INVALID_ARG, "variant out of range");
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
     if (split_k < 0 || split_k > 64) return fail(ctx, MOE_ERR_INVALID_ARG, "split_k out of range");
     if (h_planes < 0 || h_planes > 4) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1, 2, 3 or 4");

@@ -233,17 +233,21 @@ def test_mixtral_prefill_full_size_sampled_outputs(mixtral_layer):
 @pytest.mark.parametrize("w", [
     I.scaled(SMALL, name="shapes_ragged", d_model=192, d_ff=448, n_experts=4, batch_tokens=(33, 1, 200)),
     I.scaled(SMALL, name="shapes_full_tiles", n_experts=2, top_k=1, batch_tokens=(300, 300)),
+    I.scaled(SMALL, name="shapes_many_tiles", d_model=192, d_ff=448, n_experts=3, top_k=1,
+             batch_tokens=(700, 650, 300)),
 ], ids=lambda w: w.name)
 def test_every_launch_shape_gives_the_same_bits(w):
-    """The launch shapes (8 or 7 wavefronts x 1 unit, 4 x 2 units, several passes per workgroup,
-    split-K 1) only change who computes what: every accumulator still adds the same products in
-    the same order, so the outputs must be identical bit for bit, and right."""
+    """The launch shapes (8 or 7 wavefronts x 1 unit, 4 x 2 units) and, on full tiles, the order
+    in which the workgroups take the (tile, unit group) items (panels of 1 to 32 tiles, short
+    last panels and narrow last column blocks included) only change who computes what and when:
+    every accumulator still adds the same products in the same order, so the outputs must be
+    identical bit for bit, and right."""
     data, _ = I.gen_layer(w, 0)
     ctx = H.make_ctx(w)
     H.place_layer(ctx, w, 0, data)
     want = H.oracle_layer(w, data, w.batch_offsets)
     base = None
-    for variant in (1, 2, 3, 21, 22, 23, 41):
+    for variant in (1, 2, 3, 11, 21, 32, 43, 53, 61):
         ctx.set_tuning(1, 2, variant)
         got = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
         if base is None:
