@@ -522,7 +522,10 @@ struct Wg {
 // L2.  Full tiles (an expert spans many tiles and each of them streams the expert's weights
 // again): panels of kPanelTiles tiles x kPanelCols items, so that the workgroups an XCD runs at
 // the same time share both the activations of a few tiles and a few weight streams, and most
-// weight reads are L2 hits behind the first workgroup of a column.
+// weight reads are L2 hits behind the first workgroup of a column.  (Dealing the panels round
+// robin instead, so that all XCDs work on the same expert at the same time and share its weights
+// through the memory-side cache, was measured 10-20 % slower: every XCD then asks the same
+// memory channels for the same lines at once.)
 constexpr int kPanelTiles = 4, kPanelCols = 8;
 __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) {
     Wg w;
@@ -1040,7 +1043,9 @@ void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
         return;
     }
     const int units = a.d / 32;
-    const bool two = a.variant == 3 && units >= 2;  // measured: one unit per wavefront is faster here
+    // full tiles: two units per wavefront (half the LDS reads per MFMA: 2 % faster at the prefill
+    // layer); small tiles: one unit (faster at decode)
+    const bool two = (a.variant == 3 || (a.variant == 0 && a.full_tiles)) && units >= 2;
     if (a.h_planes == 3) {  // H and W2 as fp16
         if (two) launch_down<4, 2, 1, 1>(st, a); else launch_down<8, 1, 1, 1>(st, a);
         return;
