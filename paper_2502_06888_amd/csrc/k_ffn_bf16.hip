@@ -65,7 +65,6 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float v) {
 // steps are its operand of one 32x32x64 8-bit MFMA; the weight operand is the lane's four bf16
 // fragments of the same steps converted to e5m2 in registers, so both operands assign the same
 // reduction index to the same (lane half, byte) and no data moves between lanes.
-constexpr int kR8BlkUnits = 4 * 64 + 128;       // live 16-byte units of a row block per R8 stage
 constexpr int kR8LoBase = kTileBlks * 4 * 64;   // first remainder unit of an R8 stage in LDS
 struct TileCtx {
     gptr wbase;      // weight stream of this wavefront's first unit (+lane), 64 units per step
@@ -115,54 +114,56 @@ struct XMap {
     }
 };
 
-// R8 stage loads.  Unit u = b * kR8BlkUnits + r of a stage is a value unit (r < 256) or a
-// remainder unit; either way its address is a per-thread offset fixed for the tile plus the
-// group index times a stride (256 units between the value fragments of consecutive groups, 128
-// between their remainders), so the loop computes one multiply-add per load and never branches.
+// The same for an R8 stage.  A row block's part of the stage is six slots of 64 units: the four
+// value fragments of the group and the two halves of its 128 remainder units; a wavefront moves
+// one slot per pass.  Source: a base fixed for the tile plus the group index times a stride (256
+// units between the value fragments of consecutive groups, 128 between their remainders);
+// destination: the slot's place in the LDS stage.  Slots past the row blocks of this tile's class
+// read slot 0 again and land in the rows of a row block nobody multiplies (in bounds: checked
+// against the eight row blocks the stage has room for).
 template <int PASSES, int T>
 struct R8Map {
-    uint32_t off[PASSES];   // units from actbase at group 0
-    uint32_t step[PASSES];  // units per group
+    static_assert(T % 64 == 0 && PASSES * (T / 64) <= kTileBlks * 6, "slots fit the stage");
+    size_t base[PASSES];  // units from actbase at group 0, uniform
+    int gstep[PASSES];    // units per group, uniform
+    int dst[PASSES];      // unit in the LDS stage, uniform
     __device__ __forceinline__ void init(const TileCtx& c) {
-        const int live_units = c.nblk * kR8BlkUnits;
+        const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
-            int u = (int)threadIdx.x + p * T;
-            u = u < live_units ? u : 0;
-            const int b = u / kR8BlkUnits, r = u % kR8BlkUnits;
-            const bool value = r < 256;
-            off[p] = value ? (uint32_t)(b * c.nks * 64 + r)
-                           : (uint32_t)(c.lo_off + (size_t)b * c.nks * 32 + (size_t)(r - 256));
-            step[p] = value ? 256u : 128u;
+            const int slot = wave + p * (T / 64);
+            dst[p] = slot % 6 < 4 ? (slot / 6) * 256 + (slot % 6) * 64
+                                  : kR8LoBase + (slot / 6) * 128 + (slot % 6 - 4) * 64;
+            const int live = slot < c.nblk * 6 ? slot : 0;
+            const int b = live / 6, r = live % 6;
+            base[p] = r < 4 ? ((size_t)b * c.nks + r) * 64
+                            : c.lo_off + (size_t)b * c.nks * 32 + (size_t)(r - 4) * 64;
+            gstep[p] = r < 4 ? 256 : 128;
         }
+    }
+    // kbase is a multiple of 4.  CLAMP: a group past the end of the reduction is the last one
+    // again; the steady state never gets there and skips the test.
+    template <bool CLAMP>
+    __device__ __forceinline__ u32x4 load(const TileCtx& c, int p, int kbase) const {
+        const int group = (CLAMP ? min(kbase, c.nks - 4) : kbase) >> 2;
+        return (c.actbase + base[p] + (size_t)group * gstep[p])[threadIdx.x & 63];
     }
 };
-template <int PASSES, int T>
-__device__ __forceinline__ void load_x_r8(const TileCtx& c, const R8Map<PASSES, T>& m,
-                                          u32x4 (&xr)[PASSES], int kbase) {
-    const uint32_t group = (uint32_t)(min(kbase, c.nks - 4) >> 2);  // past the end: the last group again
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) xr[p] = c.actbase[m.off[p] + group * m.step[p]];
-}
 
 // When PASSES * T fits one LDS buffer the stores need no guard.
-template <int PASSES, int T, int R8 = 0>
+template <int PASSES, int T>
 __device__ __forceinline__ void store_x(const TileCtx& c, const u32x4 (&xr)[PASSES], int buf) {
-    if (R8) {
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int u = (int)threadIdx.x + p * T;
-            const int b = u / kR8BlkUnits, r = u % kR8BlkUnits;
-            if (PASSES * T <= kTileBlks * kR8BlkUnits || u < kTileBlks * kR8BlkUnits)
-                c.lds[buf * kBufUnits + (r < 256 ? b * 256 + r : kR8LoBase + b * 128 + (r - 256))] = xr[p];
-        }
-        return;
-    }
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int u = (int)threadIdx.x + p * T;
         if (PASSES * T <= kBufUnits || u < kBufUnits) c.lds[buf * kBufUnits + u] = xr[p];
     }
+}
+template <int PASSES, int T>
+__device__ __forceinline__ void store_x_r8(const TileCtx& c, const R8Map<PASSES, T>& m,
+                                           const u32x4 (&xr)[PASSES], int buf) {
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) c.lds[buf * kBufUnits + m.dst[p] + (threadIdx.x & 63)] = xr[p];
 }
 
 // HT = 0: bf16 operands; HT = 1: fp16 operands (down projection with H carried as fp16).
@@ -323,15 +324,26 @@ __device__ __forceinline__ void lo_mfma(const u32x4* stage, const i32x8 (&wq)[U]
 // A whole R8 stage: the value MFMAs of the four steps as in stage_mfma (SX = 4, one plane); each
 // step's weight fragment is converted to e5m2 before its ring slot is reloaded; the remainder
 // MFMAs of the group follow.  `stage` is the LDS buffer (no lane offset).
-template <int NB, int U, int D>
+template <int NB, int U, int D, int PASSES, int T, int DX>
 __device__ __forceinline__ void stage_mfma_r8(const u32x4* stage, u32x4 (&w)[4][U], gptr wnext,
-                                              size_t ustride, f32x16 (&acc)[U][NB]) {
+                                              size_t ustride, f32x16 (&acc)[U][NB],
+                                              u32x4* next_buf, const u32x4 (&xs)[PASSES],
+                                              const TileCtx& c, const R8Map<PASSES, T>& m, int kload,
+                                              u32x4 (&xl)[PASSES]) {
     constexpr int NF = NB * 4;
     constexpr int DD = D < NF ? D : NF;
-    const u32x4* L = stage + (threadIdx.x & 63);
+    // loads of the stage at step kload and stores of the next stage between the value MFMAs, as
+    // in stage_mfma
+    constexpr int L1 = DX == 1 ? (NF / 4 > PASSES ? NF / 4 : PASSES) : NF;
+    constexpr int S0 = DX == 1 ? NF / 2 : 0;
+    static_assert(PASSES <= NF / 2, "one pass per fragment at most");
+    const int lane = threadIdx.x & 63;
+    const u32x4* L = stage + lane;
     u32x4 win[DD];
     i32x8 wq[U];
 #define KMOE_FRAG_AT(t) L[(((t) % NB) * 4 + (t) / NB) * 64]
+#define KMOE_LOAD_AT(p) (((p) * L1) / PASSES)
+#define KMOE_STORE_AT(p) (S0 + ((p) * (NF - S0)) / PASSES)
 #pragma unroll
     for (int t = 0; t < DD; ++t) win[t] = KMOE_FRAG_AT(t);
 #pragma unroll
@@ -341,6 +353,14 @@ __device__ __forceinline__ void stage_mfma_r8(const u32x4* stage, u32x4 (&w)[4][
 #pragma unroll
         for (int u = 0; u < U; ++u) acc[u][b] = mfma<1>(as_bf16x8(w[j][u]), xa, acc[u][b]);
         if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
+        {
+            const int p = t < S0 ? PASSES : ((t - S0) * PASSES + (NF - S0) - 1) / (NF - S0);
+            if (p < PASSES && KMOE_STORE_AT(p) == t) next_buf[m.dst[p] + lane] = xs[p];
+        }
+        {
+            const int p = (t * PASSES + L1 - 1) / L1;
+            if (p < PASSES && KMOE_LOAD_AT(p) == t) xl[p] = m.template load<false>(c, p, kload);
+        }
         if (b == NB - 1) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -349,17 +369,23 @@ __device__ __forceinline__ void stage_mfma_r8(const u32x4* stage, u32x4 (&w)[4][
             }
         }
     }
-#undef KMOE_FRAG_AT
     __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
 #pragma unroll
     for (int t = 0; t < NF; ++t) {
         __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
         if (t + DD < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        const int ps = t < S0 ? PASSES : ((t - S0) * PASSES + (NF - S0) - 1) / (NF - S0);
+        if (ps < PASSES && KMOE_STORE_AT(ps) == t) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        const int pl = (t * PASSES + L1 - 1) / L1;
+        if (pl < PASSES && KMOE_LOAD_AT(pl) == t) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         if (t % NB == NB - 1) {
             __builtin_amdgcn_sched_group_barrier(0x002, 4 * U, 0);
             __builtin_amdgcn_sched_group_barrier(0x020, U, 0);
         }
     }
+#undef KMOE_FRAG_AT
+#undef KMOE_LOAD_AT
+#undef KMOE_STORE_AT
     __builtin_amdgcn_sched_barrier(0);
     lo_mfma<NB, U>(stage, wq, acc);
 }
@@ -377,7 +403,7 @@ struct Shape2 {
 template <int NB, int WAVES, int U, int SX, int R8 = 0>
 struct Pipe {
     static constexpr int T = WAVES * 64;
-    static constexpr int PASSES = (NB * (R8 ? kR8BlkUnits : kBlkStageUnits) + T - 1) / T;
+    static constexpr int PASSES = R8 ? (NB * 6 + T / 64 - 1) / (T / 64) : (NB * kBlkStageUnits + T - 1) / T;
     static constexpr int RS = Shape2<NB, WAVES, U>::RING / SX;
     // Activation look-ahead in stages.  The memory counter retires loads in issue order, so the
     // wait for a stage's activations (before they are stored to LDS) also waits for every
@@ -398,7 +424,8 @@ struct Pipe {
     template <int PL>
     __device__ __forceinline__ void load(const TileCtx& c, int slot, int kbase) {
         if constexpr (R8) {
-            load_x_r8<PASSES, T>(c, r8, xr[slot], kbase);
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) xr[slot][p] = r8.template load<true>(c, p, kbase);
         } else {
             static_assert(PL == 8 / SX, "planes per stage");
 #pragma unroll
@@ -447,7 +474,7 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[u][b][i] = 0.f;
 
-    store_x<PASSES, T, R8>(c, pp.xr[0], 0);
+    if constexpr (R8) store_x_r8<PASSES, T>(c, pp.r8, pp.xr[0], 0); else store_x<PASSES, T>(c, pp.xr[0], 0);
     __syncthreads();
 
     int k = c.k0, buf = 0;
@@ -457,18 +484,17 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int kk = k + g * SX;
-            if constexpr (R8) pp.template load<PL>(c, g % DX, kk + DX * SX);
             __builtin_amdgcn_sched_barrier(0);
             const u32x4* L = c.lds + buf * kBufUnits + lane;
             if constexpr (R8)
-                stage_mfma_r8<NB, U, D>(c.lds + buf * kBufUnits, pp.wr[g % RS],
-                                        c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc);
+                stage_mfma_r8<NB, U, D, PASSES, T, DX>(
+                    c.lds + buf * kBufUnits, pp.wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc,
+                    c.lds + (buf ^ 1) * kBufUnits, pp.xr[(g + 1) % DX], c, pp.r8, kk + DX * SX, pp.xr[g % DX]);
             else
                 stage_mfma<MODE, NB, U, SX, PL, D, HT, PASSES, T, DX>(
                     L, pp.wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc,
                     c.lds + (buf ^ 1) * kBufUnits, pp.xr[(g + 1) % DX], c, pp.xm, kk + DX * SX, pp.xr[g % DX]);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (R8) store_x<PASSES, T, R8>(c, pp.xr[(g + 1) % DX], buf ^ 1);
             __syncthreads();
             buf ^= 1;
         }
@@ -502,7 +528,10 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
                     }
                 }
                 if constexpr (R8) lo_mfma<NB, U>(c.lds + buf * kBufUnits, wq, acc);
-                if (more) store_x<PASSES, T, R8>(c, pp.xr[(g + 1) % DX], buf ^ 1);
+                if (more) {
+                    if constexpr (R8) store_x_r8<PASSES, T>(c, pp.r8, pp.xr[(g + 1) % DX], buf ^ 1);
+                    else store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
+                }
                 __syncthreads();
                 buf ^= 1;
             }
@@ -1050,8 +1079,8 @@ void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
         if (two) launch_down<4, 2, 1, 1>(st, a); else launch_down<8, 1, 1, 1>(st, a);
         return;
     }
-    if (a.h_planes == 4) {  // bf16 value + e5m2 remainder
-        if (two) launch_down<4, 2, 1, 0, 1>(st, a); else launch_down<8, 1, 1, 0, 1>(st, a);
+    if (a.h_planes == 4) {  // bf16 value + e5m2 remainder: one unit per wavefront unless asked otherwise
+        if (a.variant == 3 && units >= 2) launch_down<4, 2, 1, 0, 1>(st, a); else launch_down<8, 1, 1, 0, 1>(st, a);
     } else if (a.h_planes == 2) {
         if (two) launch_down<4, 2, 2>(st, a); else launch_down<8, 1, 2>(st, a);
     } else {
