@@ -457,6 +457,8 @@ def main():
                     help="skip the extra measurement of the opt-in fp16 intermediate format")
     ap.add_argument("--h-planes", type=int, default=0, help="0 = library default")
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
+    ap.add_argument("--variant", type=int, default=0,
+                    help="launch shape of the bf16 expert kernels (moe_set_tuning); 0 = library default")
     ap.add_argument("--prefetch", type=int, default=-1,
                     help="streamed stacks: experts prefetched per layer (-1 = top_k)")
     ap.add_argument("--prefetch-policy", choices=["prev", "corr"], default="prev",
@@ -499,8 +501,8 @@ def main():
     cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
                         w.n_batches, B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1, 4 if q4 else 0)
     ctx = B.MoeContext(cfg, compute)
-    if args.h_planes or args.split_k:       # before placement: h_planes 3 packs W2 differently
-        ctx.set_tuning(args.split_k, args.h_planes)
+    if args.h_planes or args.split_k or args.variant:   # before placement: h_planes 3 packs W2 differently
+        ctx.set_tuning(args.split_k, args.h_planes, args.variant)
     ctx.set_gate(0, data.wg.to(dev))
     for e in range(w.n_experts + w.n_shared):
         if q4:
