@@ -480,7 +480,9 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
     int k = c.k0, buf = 0;
     // steady state: every stage of the group is complete, has a successor to stage and a slot to
     // reload, so the body is branch-free (activation loads past the end re-read the last step)
-    for (; k + (G + RS) * SX <= c.k1; k += G * SX) {
+    // (the ring reloads reach RS stages ahead, the unclamped activation loads DX: the further one
+    // must stay inside the range)
+    for (; k + (G + (RS > DX ? RS : DX)) * SX <= c.k1; k += G * SX) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int kk = k + g * SX;
