@@ -16,8 +16,11 @@
 // contiguous run of 1 KiB fragments (one per 16-deep reduction step), read straight into
 // registers through a software prefetch ring.  The activations of the tile are staged through
 // LDS, double buffered, in the same fragment order, so LDS reads are one conflict-free 16-byte
-// read per lane.  The workgroup -> tile map deals consecutive tiles of one expert to the same
-// XCD so that the expert's activations stay in that XCD's L2.
+// read per lane.  All of that traffic (weight reloads, activation loads of a later stage, LDS
+// stores of the next one) is issued between the MFMAs in a pinned order, never in bursts.  The
+// workgroup -> tile map keeps what the workgroups of an XCD share in that XCD's L2: a tile's
+// activations on small tiles, and on full tiles (an expert spans many tiles that all stream its
+// weights) panels of a few tiles x a few weight streams.
 #include "kernels.h"
 
 namespace kmoe {
