@@ -255,6 +255,13 @@ def test_every_launch_shape_gives_the_same_bits(w):
             H.check_routing(got, want, w.n_experts)
             H.check_output(got["y"], want.y, w.dtype)
         assert np.array_equal(got["y"], base), f"variant {variant} differs from variant 1"
+    for bad in (70, 104, -2):                        # tens digit past the six panel shapes, or below -1
+        with pytest.raises(B.MoeError) as ei:
+            ctx.set_tuning(1, 2, bad)
+        assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    ctx.set_tuning(1, 2, -1)                         # the defaults again
+    got = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
+    assert np.array_equal(got["y"], base)
     ctx.close()
 
 
