@@ -230,6 +230,29 @@ def test_mixtral_prefill_full_size_sampled_outputs(mixtral_layer):
     assert got["counts"].sum() == 32768
 
 
+def test_prefill_size_outputs_permute_with_the_tokens_in_every_workgroup_order(mixtral_layer):
+    """The same properties on full tiles (16 tiles of 256 rows per expert, panel order of the
+    workgroups, two-unit shape): permuting the 16384 tokens moves every token to another row of
+    another tile and permutes the outputs bit for bit; another panel shape and the one-unit shape
+    change no bit either.  (Routing of a token does not depend on its neighbours, so the permuted
+    run must also select the same experts with the same weights.)"""
+    wd, data, ctx = mixtral_layer
+    w = I.WORKLOADS["mixtral8x7b_prefill"]
+    x = I.gen_x_gaussian(w)
+    base = H.gpu_layer(ctx, w, 0, x, w.batch_offsets)
+    perm = np.random.Generator(np.random.PCG64(12)).permutation(w.n_tokens)
+    shuffled = H.gpu_layer(ctx, w, 0, x[torch.from_numpy(perm)], w.batch_offsets)
+    assert np.array_equal(shuffled["idx"], base["idx"][perm])
+    assert np.array_equal(shuffled["y"].view(np.uint32), base["y"][perm].view(np.uint32))
+    try:
+        for variant in (51, 13):                     # 16 x 2 panels with one unit, 1 x 32 with two
+            ctx.set_tuning(0, 0, variant)
+            other = H.gpu_layer(ctx, w, 0, x, w.batch_offsets)
+            assert np.array_equal(other["y"].view(np.uint32), base["y"].view(np.uint32)), variant
+    finally:
+        ctx.set_tuning(0, 0, -1)
+
+
 @pytest.mark.parametrize("w", [
     I.scaled(SMALL, name="shapes_ragged", d_model=192, d_ff=448, n_experts=4, batch_tokens=(33, 1, 200)),
     I.scaled(SMALL, name="shapes_full_tiles", n_experts=2, top_k=1, batch_tokens=(300, 300)),
