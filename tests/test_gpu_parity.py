@@ -226,8 +226,16 @@ def test_mixtral_prefill_full_size_sampled_outputs(mixtral_layer):
     x = I.gen_x_gaussian(w)
     d2 = I.LayerData(x=x, wg=data.wg, w1=data.w1, w3=data.w3, w2=data.w2)
     tokens = np.random.Generator(np.random.PCG64(6)).choice(w.n_tokens, 12, replace=False)
-    got, want, err = run_case(w, tokens=np.sort(tokens).astype(np.int32), data=d2, ctx=ctx)
+    tokens = np.sort(tokens).astype(np.int32)
+    got, want, err = run_case(w, tokens=tokens, data=d2, ctx=ctx)
     assert got["counts"].sum() == 32768
+    try:                                             # the opt-in 8-bit remainder on full tiles
+        ctx.set_tuning(h_planes=4)
+        got4 = H.gpu_layer(ctx, w, 0, x, w.batch_offsets)
+        H.check_output(got4["y"], want.y, w.dtype, tokens)
+        assert np.all(np.abs(got4["y"] - got["y"]) <= 1e-2 + 2e-2 * np.abs(got["y"]))
+    finally:
+        ctx.set_tuning(h_planes=2)
 
 
 def test_prefill_size_outputs_permute_with_the_tokens_in_every_workgroup_order(mixtral_layer):
