@@ -25,8 +25,10 @@ def gen_stack(w):
     return layers
 
 
-def resident_reference(w, layers):
+def resident_reference(w, layers, h_planes=0):
     ctx = H.make_ctx(w, window_layers=0)
+    if h_planes:
+        ctx.set_tuning(0, h_planes, 0)                       # before placement (fp16 H packs W2 for it)
     ys = []
     for l, data in enumerate(layers):
         H.place_layer(ctx, w, l, data)
@@ -84,6 +86,27 @@ def test_streamed_equals_resident_bitwise(prefetch_k, delay, explicit):
     assert st["bytes_h2d"] == ctx.plan.expert_bytes * (n_active_total + unused)
     assert st["n_copies"] == n_active_total + unused
     assert st["n_active_sum"] == n_active_total
+    ctx.close()
+
+
+@pytest.mark.parametrize("h_planes", [1, 3, 4])
+def test_streamed_equals_resident_for_the_other_formats_of_the_intermediate(h_planes):
+    """The per-expert launches of the streamed forward with H as plain bf16, as fp16 (W2 placed
+    for it, in pinned memory) and as bf16 + 8-bit remainder: bit for bit the resident result."""
+    w = STACK
+    layers = gen_stack(w)
+    want = resident_reference(w, layers, h_planes)
+    ctx = H.make_ctx(w)
+    ctx.set_tuning(0, h_planes, 0)
+    for l, data in enumerate(layers):
+        H.place_layer(ctx, w, l, data, streamed=True)
+    ctx.window.fill_(0xFF)
+    torch.cuda.synchronize()
+    got = streamed_pass(ctx, w, layers, 2)
+    for l in range(w.n_layers):
+        y, counts, n_active = got[l]
+        assert np.all(np.isfinite(y)), f"layer {l}: compute ran before its copy landed"
+        assert np.array_equal(y, want[l]["y"]), f"layer {l}: streamed != resident"
     ctx.close()
 
 
