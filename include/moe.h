@@ -190,6 +190,34 @@ moe_status moe_route_wait(moe_ctx* ctx, int32_t* counts_host, int32_t* exec_orde
                           int32_t* n_active);
 
 /*
+ * moe_route_static -- for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The gate + dispatch plan of moe_route without
+ * a context and without a workspace: the scratch the dispatch kernels need beyond their inputs
+ * and outputs (per-chunk histograms, padded offsets, batches per expert, tile tables, and any
+ * of the outputs below that the caller does not ask for) lives in a fixed array of 1.5 MiB in
+ * the library's device image, one copy per GPU, held until the process ends.  The call
+ * allocates nothing (no hipMalloc, hipFree, hipHostMalloc, event or stream creation); it
+ * enqueues the router and the dispatch kernels on `stream` (hipStream_t) and returns.
+ *   dtype: moe_dtype of x_dev [n_tokens, d_model] and wg_dev [n_experts, d_model], both device.
+ *   batch_offsets_host[n_batches + 1]: as for moe_route; must end at n_tokens.
+ *   Outputs: as for moe_route, device pointers, each optional; same values bit for bit.
+ * Limits: n_tokens <= MOE_STATIC_MAX_TOKENS and n_tokens * top_k <= MOE_STATIC_MAX_ASSIGNMENTS
+ * (beyond: MOE_ERR_SHAPE, nothing is launched); d_model a multiple of 64 (bf16) or 4 (f32).
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's contents (the
+ * kernels rewrite all they read, nothing needs clearing): calls that overlap on one GPU -- from
+ * two streams or two threads -- race; calls on one stream are ordered and safe.
+ * The error text of a failed call is available from moe_last_error(NULL) on the calling thread.
+ */
+#define MOE_STATIC_MAX_TOKENS 65536
+#define MOE_STATIC_MAX_ASSIGNMENTS 65536
+moe_status moe_route_static(void* stream, int32_t dtype, const void* x_dev, const void* wg_dev,
+                            int32_t n_tokens, int32_t d_model, int32_t n_experts, int32_t top_k,
+                            int32_t renormalize, const int32_t* batch_offsets_host, int32_t n_batches,
+                            float* logits_dev, int32_t* topk_idx_dev, float* topk_w_dev,
+                            int32_t* counts_dev, int32_t* offsets_dev, int32_t* perm_dev,
+                            int32_t* inv_perm_dev, int32_t* exec_order_dev);
+
+/*
  * moe_stream_experts -- enqueue host->device copies of routed experts of `layer` on the copy
  * stream, in the order given (Section 5: prefetch the hot experts before the gate, transfer
  * the rest on demand after it, never transfer experts nobody selected).  Each expert goes to

@@ -28,7 +28,8 @@ EXPORTS = ["moe_plan", "moe_plan_batches", "moe_create", "moe_destroy", "moe_set
            "moe_set_expert", "moe_route", "moe_route_wait", "moe_stream_experts",
            "moe_layer_forward", "moe_get_stats", "moe_reset_stats", "moe_set_tuning",
            "moe_set_profiling", "moe_get_profile", "moe_last_error", "moe_corr_enable",
-           "moe_corr_reset", "moe_corr_predict", "moe_corr_table", "moe_corr_rank", "moe_measure", "moe_set_expert_q4"]
+           "moe_corr_reset", "moe_corr_predict", "moe_corr_table", "moe_corr_rank", "moe_measure", "moe_set_expert_q4",
+           "moe_route_static"]
 
 
 class MoeConfig(C.Structure):
@@ -95,6 +96,7 @@ def load_library():
     lib.moe_set_expert_q4.argtypes = [vp, i32, i32] + [vp] * 9 + [i32, vp]
     lib.moe_route.argtypes = [vp, i32, vp, P(i32), i32] + [vp] * 8
     lib.moe_route_wait.argtypes = [vp, P(i32), P(i32), P(i32)]
+    lib.moe_route_static.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, P(i32), i32] + [vp] * 8
     lib.moe_stream_experts.argtypes = [vp, i32, P(i32), i32, i32]
     lib.moe_layer_forward.argtypes = [vp, i32, vp, vp]
     lib.moe_get_stats.argtypes = [vp, P(MoeStats)]
@@ -163,6 +165,20 @@ def moe_plan_batches(t_c_A, t_c_G, t_c_hotE, t_c_E: Sequence[float], t_io_A, t_i
 def _ptr(t) -> Optional[int]:
     """Raw address of a torch tensor (or None)."""
     return None if t is None else t.data_ptr()
+
+
+def route_static(stream, dtype: int, x, wg, top_k: int, batch_offsets: Sequence[int],
+                 out: Optional["RouteOutputs"] = None, renormalize: bool = True):
+    """moe_route_static: gate + dispatch plan on the library's static device scratch (no context,
+    no workspace, nothing allocated by the call)."""
+    out = out or RouteOutputs()
+    nb = len(batch_offsets) - 1
+    bo = (C.c_int32 * (nb + 1))(*[int(v) for v in batch_offsets])
+    n_tokens = int(batch_offsets[-1])
+    _check(load_library().moe_route_static(
+        stream.cuda_stream, dtype, _ptr(x), _ptr(wg), n_tokens, int(wg.shape[1]), int(wg.shape[0]),
+        top_k, 1 if renormalize else 0, bo, nb, _ptr(out.logits), _ptr(out.topk_idx), _ptr(out.topk_w),
+        _ptr(out.counts), _ptr(out.offsets), _ptr(out.perm), _ptr(out.inv_perm), _ptr(out.exec_order)))
 
 
 @dataclass

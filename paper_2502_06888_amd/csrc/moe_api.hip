@@ -13,6 +13,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -1177,6 +1178,127 @@ moe_status moe_corr_predict(moe_ctx* ctx, int32_t layer, int32_t K, int32_t* exp
     const size_t EE = (size_t)ctx->cfg.n_experts * ctx->cfg.n_experts;
     return moe_corr_rank(ctx->corr_host + (size_t)layer * EE, ctx->h_counts.data(), ctx->cfg.n_experts, K,
                          experts_out_host, n_out, nullptr);
+}
+
+// ---- routing for callers that cannot allocate ---------------------------------------------------
+// The dispatch plan needs device scratch beyond its inputs and outputs (per-chunk histograms and
+// bases, padded offsets, batches per expert, tile tables, the selected experts when the caller
+// does not ask for them).  moe_route takes it from the context's workspace; this entry point
+// takes it from a fixed array in the library's device image, so that nothing is allocated.
+}  // extern "C"
+
+namespace {
+constexpr int64_t kStaticScratchBytes = 1536 * 1024;
+constexpr int kStaticMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+// Device address of `scratch` on each GPU (every GPU holds its own copy of the array at its own
+// address).  Host code never passes the array's name to a kernel or a copy: only these pointers.
+unsigned char* g_scratch_ptr[kStaticMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+moe_status static_scratch(unsigned char** out) {
+    int dev = -1;
+    HIP_TRY(nullptr, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticMaxDevices) return fail(nullptr, MOE_ERR_HIP, "device ordinal %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(nullptr, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(nullptr, MOE_ERR_HIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = (unsigned char*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+}  // namespace
+
+extern "C" {
+
+moe_status moe_route_static(void* stream, int32_t dtype, const void* x_dev, const void* wg_dev,
+                            int32_t n_tokens, int32_t d_model, int32_t n_experts, int32_t top_k,
+                            int32_t renormalize, const int32_t* batch_offsets_host, int32_t n_batches,
+                            float* logits_dev, int32_t* topk_idx_dev, float* topk_w_dev,
+                            int32_t* counts_dev, int32_t* offsets_dev, int32_t* perm_dev,
+                            int32_t* inv_perm_dev, int32_t* exec_order_dev) {
+    if (dtype != MOE_F32 && dtype != MOE_BF16) return fail(nullptr, MOE_ERR_INVALID_ARG, "dtype must be MOE_F32 or MOE_BF16");
+    const int mult = dtype == MOE_BF16 ? 64 : 4;
+    if (d_model <= 0 || d_model % mult) return fail(nullptr, MOE_ERR_SHAPE, "d_model must be a positive multiple of %d", mult);
+    if (n_experts < 1 || n_experts > MOE_MAX_EXPERTS) return fail(nullptr, MOE_ERR_SHAPE, "n_experts out of range");
+    if (top_k < 1 || top_k > MOE_MAX_TOPK || top_k > n_experts) return fail(nullptr, MOE_ERR_SHAPE, "top_k out of range");
+    if (!batch_offsets_host) return fail(nullptr, MOE_ERR_INVALID_ARG, "batch_offsets is null");
+    if (n_batches < 1 || n_batches > MOE_MAX_BATCHES) return fail(nullptr, MOE_ERR_SHAPE, "n_batches %d outside [1, %d]", n_batches, MOE_MAX_BATCHES);
+    if (batch_offsets_host[0] != 0) return fail(nullptr, MOE_ERR_INVALID_ARG, "batch_offsets must start at 0");
+    BatchOffsets bo;
+    bo.n = n_batches;
+    for (int b = 0; b <= n_batches; ++b) {
+        if (b > 0 && batch_offsets_host[b] < batch_offsets_host[b - 1])
+            return fail(nullptr, MOE_ERR_INVALID_ARG, "batch_offsets must be non-decreasing");
+        bo.v[b] = batch_offsets_host[b];
+    }
+    for (int b = n_batches + 1; b <= kMaxBatches; ++b) bo.v[b] = batch_offsets_host[n_batches];
+    if (batch_offsets_host[n_batches] != n_tokens)
+        return fail(nullptr, MOE_ERR_INVALID_ARG, "batch_offsets end at %d, n_tokens is %d", batch_offsets_host[n_batches], n_tokens);
+    if (n_tokens < 0 || n_tokens > MOE_STATIC_MAX_TOKENS || (int64_t)n_tokens * top_k > MOE_STATIC_MAX_ASSIGNMENTS)
+        return fail(nullptr, MOE_ERR_SHAPE, "%d tokens x top-%d exceed what moe_route_static serves (%d tokens, %d assignments)",
+                    n_tokens, top_k, MOE_STATIC_MAX_TOKENS, MOE_STATIC_MAX_ASSIGNMENTS);
+    if (n_tokens > 0 && (!x_dev || !wg_dev)) return fail(nullptr, MOE_ERR_INVALID_ARG, "x or the gate matrix is null");
+
+    // carve the scratch array; whatever the caller asks for is written in place instead
+    const int64_t E = n_experts, A = (int64_t)n_tokens * top_k;
+    const int64_t max_rowblks = (A + kRowBlk - 1) / kRowBlk + E;
+    const int64_t nchunks = (A + kPlanChunk - 1) / kPlanChunk;
+    const int max_tiles = max_tiles_for((int)max_rowblks, (int)E, 0, n_tokens);
+    unsigned char* base = nullptr;
+    moe_status rs = static_scratch(&base);
+    if (rs != MOE_OK) return rs;
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        unsigned char* at = base + off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    PlanPtrs p{};
+    p.topk_idx = topk_idx_dev ? topk_idx_dev : (int32_t*)take(A * 4);
+    p.topk_w = topk_w_dev ? topk_w_dev : (float*)take(A * 4);
+    p.counts = counts_dev ? counts_dev : (int32_t*)take(E * 4);
+    p.offsets = offsets_dev ? offsets_dev : (int32_t*)take((E + 1) * 4);
+    p.poff = (int32_t*)take((E + 1) * 4);
+    p.nbatch = (int32_t*)take(E * 4);
+    p.exec_order = exec_order_dev ? exec_order_dev : (int32_t*)take(E * 4);
+    p.meta = (int32_t*)take(16 * 4);
+    p.perm = perm_dev ? perm_dev : (int32_t*)take(A * 4);
+    p.inv_perm = inv_perm_dev ? inv_perm_dev : (int32_t*)take(A * 4);
+    p.blk_counts = (int32_t*)take(nchunks * E * 4);
+    p.blk_base = (int32_t*)take(nchunks * E * 4);
+    p.blk_mask = (unsigned long long*)take(nchunks * E * 8);
+    p.tile_expert = (int32_t*)take((int64_t)max_tiles * 4);
+    p.tile_xblk = (int32_t*)take((int64_t)max_tiles * 4);
+    p.tile_hblk = (int32_t*)take((int64_t)max_tiles * 4);
+    p.tile_nblk = (int32_t*)take((int64_t)max_tiles * 4);
+    p.exp_tile0 = (int32_t*)take(E * 4);
+    p.exp_ntiles = (int32_t*)take(E * 4);
+    p.blk_expert = (int32_t*)take(max_rowblks * 4);
+    p.mail = (int32_t*)take((2 * E + 1) * 4);
+    if (off > kStaticScratchBytes)  // cannot happen within the limits above; kept as the bound's proof
+        return fail(nullptr, MOE_ERR_SHAPE, "routing scratch of %lld bytes exceeds the static %lld", (long long)off, (long long)kStaticScratchBytes);
+    Shape s{};
+    s.N = n_tokens;
+    s.d = d_model;
+    s.f = 0;
+    s.E = n_experts;
+    s.k = top_k;
+    s.S = 0;
+    s.renorm = renormalize ? 1 : 0;
+    s.max_rowblks = (int32_t)max_rowblks;
+    hipStream_t st = (hipStream_t)stream;
+    launch_router(st, dtype, x_dev, wg_dev, s, logits_dev, p.topk_idx, p.topk_w);
+    launch_plan(st, s, bo, p, max_tiles);
+    HIP_TRY(nullptr, hipGetLastError());
+    return MOE_OK;
 }
 
 moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32_t variant) {
