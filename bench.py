@@ -3,11 +3,14 @@
 
 A step is one pass of the whole path over one batch group of synthetic input already resident
 in HBM: gate + top-k + dispatch plan (moe_route), then gather, grouped SwiGLU expert FFN and
-weighted combine (moe_layer_forward).  Workload: the Mixtral-8x7B-shaped decode layer
+weighted combine (moe_layer_forward).  Headline workload: the Mixtral-8x7B-shaped decode layer
 (d_model 4096, d_ff 14336, 8 experts, top-2, 8 batches x 64 sequences x 1 token, bf16, experts
-resident).  Prints ONE JSON line with tokens/s, the roofline of the dominant kernel (timed live
-with HIP events on the compute stream, between the launches inside the library) and the CPU
-oracle timed on a bounded sample of the same workload.
+resident), bound by HBM.  Prints ONE JSON line with tokens/s, the roofline of the dominant kernel
+(timed live with HIP events on the compute stream, between the launches inside the library) and
+the CPU oracle timed on a bounded sample of the same workload.  Without --workload the line
+also carries, under "legs", the other two rooflines the metric names: the prefill layer (matrix
+cores) and the streamed stacks (host link: achieved GB/s, idle fraction of the link and of the
+compute stream from the library's events around every copy and every kernel group).
 """
 from __future__ import annotations
 
@@ -24,6 +27,17 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # published dense bf16 matrix-core peak
+
+
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def cpu_baseline(w, data, budget_s: float = 15.0):
@@ -48,25 +62,29 @@ def cpu_baseline(w, data, budget_s: float = 15.0):
     n = max(cores, n // cores * cores)
     n = min(n, w.n_tokens)
     t = run(n) if n != probe_n else t_probe
-    return {"value": n / t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+    return {"value": n / t, "unit": "tokens/s", "cores": cores, "cpu_model": cpu_model(), "kind": "oracle",
             "sample": f"first {n} of {w.n_tokens} tokens of the same workload "
                       f"(gate, top-k, dispatch and fp64 SwiGLU experts), {t:.1f} s"}
 
 
 def recorded_traffic(workload: str, kernel: str):
     """HBM bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE +
-    WRITE_SIZE, each scaled by the copy-kernel calibration); None when no summary covers it.
-    Counters cannot be read from inside a timed run, so this figure is the recorded one."""
+    WRITE_SIZE, each scaled by the copy-kernel calibration) and the git head the summary was
+    recorded at; (None, None) when no summary covers it.  Counters cannot be read from inside a
+    timed run, so this figure is the recorded one."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                         f"{kernel}_{workload}_hbm_traffic.md")
+    traffic, head = None, None
     try:
         with open(path) as fh:
             for line in fh:
                 if line.startswith("traffic_bytes_per_launch:"):
-                    return int(float(line.split(":", 1)[1]))
+                    traffic = int(float(line.split(":", 1)[1]))
+                if line.startswith("git_head:"):
+                    head = line.split(":", 1)[1].strip()
     except OSError:
         pass
-    return None
+    return traffic, head
 
 
 def planner_report(ctx, w, xs, ys, K, compute, torch, B):
@@ -148,42 +166,13 @@ def measure_attention_batch(w, n_seq, torch, pos: int = 512) -> float:
     return best
 
 
-H_FORMATS = {1: "bf16", 2: "bf16 pair", 3: "fp16", 4: "bf16 + e5m2 remainder"}
-
-
-def h_format_variant(w, data, args, torch, B, h_planes: int):
-    """The same step with an opt-in H format (h_planes = 4: rounding remainder of H in 8 bits on
-    the 8-bit MFMA; h_planes = 3: H and W2 as fp16 in the down projection; same tolerance),
-    reported beside the headline, which keeps the all-bf16 default."""
-    dev = torch.device("cuda:0")
-    compute = torch.cuda.Stream()
-    cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
-                        w.n_batches, B.MOE_BF16, 1)
-    ctx = B.MoeContext(cfg, compute)
-    ctx.set_tuning(0, h_planes, 0)
-    ctx.set_gate(0, data.wg.to(dev))
-    for e in range(w.n_experts + w.n_shared):
-        ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
-    x = data.x.to(dev)
-    y = torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
-    bo = [int(v) for v in w.batch_offsets]
-    steps = max(1, args.steps // 2)
-    with torch.cuda.stream(compute):
-        for _ in range(args.warmup):
-            ctx.route(0, x, bo); ctx.layer_forward(0, x, y)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            ctx.route(0, x, bo); ctx.layer_forward(0, x, y)
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
-        ctx.set_profiling(True)
-        ctx.route(0, x, bo); ctx.layer_forward(0, x, y)
-        prof = ctx.profile()
-    ctx.close()
-    return {"h_format": H_FORMATS[h_planes], "steps": steps, "ms_per_step": ms,
-            "value": w.n_tokens / (ms * 1e-3), "unit": "tokens/s",
-            "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()}}
+def release_memory(torch):
+    """Hand cached device and pinned host blocks back (the streamed stacks pin tens of GiB each)."""
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
 
 
 def measure_link_peak(torch, nbytes: int = 1 << 30, reps: int = 5) -> float:
@@ -294,6 +283,24 @@ def bench_streamed(w, args):
         wall = time.perf_counter() - t0
     st = ctx.stats()
     gbs = st["bytes_h2d"] / wall / 1e9
+    # the same pass once more with the library's events around every copy and every kernel group:
+    # busy time of the link (union over the copy streams) and of the compute stream over the wall
+    # time from the first copy's start to the last kernel's end
+    ctx.reset_stats()
+    ctx.set_profiling(True)
+    with torch.cuda.stream(compute):
+        one_pass()
+    torch.cuda.synchronize()
+    pst = ctx.stats()
+    ctx.set_profiling(False)
+    wall_ns = max(1, pst["wall_ns"])
+    # smallest number of batches per group for which compute would cover the transfers (the
+    # planner's inequality group, without an attention layer in between): measured on layer 0
+    with torch.cuda.stream(compute):
+        m = ctx.measure(0, xs[0], bo, ys[0], reps=2)
+    order = m["exec_order"]
+    n_min = B.moe_plan_batches(0.0, m["t_c_gate_group_s"] / w.n_batches, sum(m["t_c_expert_s"][e] for e in order[:K]),
+                               [m["t_c_expert_s"][e] for e in order[K:]], 0.0, 0.0, m["t_io_expert_s"], K)
     out = {
         "metric": "moe_stack_tokens_per_s", "value": w.n_tokens * steps / wall, "unit": "tokens/s",
         "n_gpus": 1, "steps": steps, "warmup": 1, "ms_per_step": wall / steps * 1e3,
@@ -309,18 +316,28 @@ def bench_streamed(w, args):
         "token_layers_per_s": w.n_tokens * w.n_layers * steps / wall,
         "host_link": {"achieved_GBps": gbs, "measured_peak_GBps": link_peak, "nominal_peak_GBps": 64.0,
                       "frac_of_nominal": gbs / 64.0, "frac_of_measured": gbs / link_peak,
-                      "bubble_link_idle": max(0.0, 1.0 - gbs / link_peak),
+                      "rate_shortfall_vs_probe": 1.0 - gbs / link_peak,
                       "bytes_h2d_per_step": st["bytes_h2d"] / steps, "copies_per_step": st["n_copies"] / steps,
                       "prefetch_hits_per_step": st["n_prefetch_hits"] / steps,
                       "prefetch_unused_per_step": st["n_prefetch_unused"] / steps},
         "prefetch": {"predicted": acc["predicted"],
                      "hot_accuracy": acc["in_true_topk"] / max(1, acc["predicted"]),
                      "activated_fraction": acc["activated"] / max(1, acc["predicted"])},
+        "pipeline": {"profiled_pass_wall_ms": wall_ns * 1e-6, "copy_busy_ms": pst["copy_busy_ns"] * 1e-6,
+                     "compute_busy_ms": pst["compute_busy_ns"] * 1e-6,
+                     "bubble_link_idle": 1.0 - pst["copy_busy_ns"] / wall_ns,
+                     "bubble_compute_idle": 1.0 - pst["compute_busy_ns"] / wall_ns,
+                     "copy_rate_GBps": pst["bytes_h2d"] / max(1, pst["copy_busy_ns"]),
+                     "n_min_batches_for_full_overlap": n_min,
+                     "note": "bubble_link_idle = 1 - copy busy / wall (the binding resource); bubble_compute_idle "
+                             "= 1 - compute busy / wall is the paper's bubble: compute waiting for transfers"},
         "setup_s": t_setup,
     }
     if plan_report is not None:
         out["planner"] = plan_report
     ctx.close()
+    del ctx, xs, ys
+    release_memory(torch)
     return out
 
 
@@ -341,7 +358,7 @@ def attn_cpu_baseline(w, ws, hs, caches, budget_s: float = 12.0):
         done += w.batch_seqs[b]
         if t > budget_s:
             break
-    return {"value": done / t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+    return {"value": done / t, "unit": "tokens/s", "cores": cores, "cpu_model": cpu_model(), "kind": "oracle",
             "sample": f"first {done} of {w.n_tokens} sequences (whole batches) of the same workload, fp64 "
                       f"attention layer over {w.batch_pos[0]} cached positions, {t:.1f} s"}
 
@@ -429,7 +446,8 @@ def bench_attention(w, args):
     out["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel", "launches_per_step": launches,
                        "achieved": attn_bytes / launches / t_attn / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": attn_bytes / launches / t_attn / 1e9 / HBM_PEAK_GBS,
-                       "traffic": recorded_traffic(w.name, "attn_decode_kernel"),
+                       "traffic": recorded_traffic(w.name, "attn_decode_kernel")[0],
+                       "traffic_recorded_at": recorded_traffic(w.name, "attn_decode_kernel")[1],
                        "algorithmic_bytes_per_launch": attn_bytes // launches,
                        "layer_bytes_per_step": layer_bytes,
                        "layer_GBps": layer_bytes / pr.compute_busy_s / 1e9}
@@ -446,16 +464,166 @@ def bench_attention(w, args):
     return out
 
 
+def bench_resident(w, args, data=None, steps=None, warmup=None, with_cpu_baseline=True):
+    """One all-resident layer (decode or prefill shape): K timed steps after W warm-up steps, then
+    per-kernel durations from the library's events and the roofline of the dominant kernel."""
+    import torch
+    from paper_2502_06888_amd import binding as B
+    from paper_2502_06888_amd import inputs as I
+    steps = args.steps if steps is None else steps
+    warmup = args.warmup if warmup is None else warmup
+    dev = torch.device("cuda:0")
+    q4 = args.weight_bits == 4
+    if data is None:
+        data, _ = I.gen_layer(w, 0, threads=16, with_experts=not q4)
+    compute = torch.cuda.Stream()
+    cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
+                        w.n_batches, B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1, 4 if q4 else 0)
+    ctx = B.MoeContext(cfg, compute)
+    if args.h_planes or args.split_k or args.variant:
+        ctx.set_tuning(args.split_k, args.h_planes, args.variant)
+    ctx.set_gate(0, data.wg.to(dev))
+    for e in range(w.n_experts + w.n_shared):
+        if q4:
+            trip = I.gen_expert_q4(w, 0, e)
+            ctx.set_expert_q4(0, e, tuple(tuple(t.to(dev) for t in m) for m in trip))
+        else:
+            ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
+    x = data.x.to(dev)
+    y = torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
+    bo = [int(v) for v in w.batch_offsets]
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB read
+        dst = torch.empty_like(src)                                     # 1 GiB written
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        del src, dst
+    torch.cuda.synchronize()
+
+    def step():
+        ctx.route(0, x, bo)
+        ctx.layer_forward(0, x, y)
+
+    # Settling (untimed, before the warm-up steps): a GPU that sat idle during set-up starts at
+    # its boost clock, overshoots its power limit and throttles for some tens of milliseconds;
+    # the steady state a serving loop sees comes after that.
+    settle_steps = 0
+    with torch.cuda.stream(compute):
+        step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < args.settle_ms:
+            for _ in range(8):
+                step()
+            torch.cuda.synchronize()
+            settle_steps += 8
+        for _ in range(warmup):
+            step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps, inputs resident, bracketed by device synchronisation
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(compute):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record(compute)
+        for _ in range(steps):
+            step()
+        ev1.record(compute)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    dev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = max(wall_ms, dev_ms) / steps
+
+    # per-kernel durations, HIP events recorded by the library between its launches
+    ctx.reset_stats()
+    ctx.set_profiling(True)
+    prof = {}
+    reps = max(10, min(50, steps))
+    with torch.cuda.stream(compute):
+        for _ in range(reps):
+            step()
+            for k_, v in ctx.profile().items():
+                prof[k_] = prof.get(k_, 0.0) + v / reps
+    ctx.set_profiling(False)
+    counts, order, n_active = ctx.route_wait()
+    st = ctx.stats()
+
+    elt = w.elt_bytes
+    A = w.n_tokens * w.top_k
+    # algorithmic bytes of the dominant kernel (up projections + SwiGLU): W1 and W3 of every
+    # activated expert once, the gathered token rows once, H written once
+    wbytes = 9.0 / 16.0 if q4 else elt      # 4-bit codes + one (scale, zero point) pair per 64 weights
+    up_bytes = int(n_active * 2 * w.d_model * w.d_ff * wbytes) + A * w.d_model * elt + A * w.d_ff * elt
+    layer_bytes = (int(n_active * 3 * w.d_model * w.d_ff * wbytes) + w.n_tokens * w.d_model * elt * 2 +
+                   2 * A * w.d_ff * elt + A * w.d_model * 4)
+    achieved = up_bytes / (prof["up_ms"] * 1e-3) / 1e9 if prof.get("up_ms", 0) > 0 else 0.0
+    # gate and up projections: 2 flops x rows x d x 2f.  Above the machine balance (2.5 PFLOP/s over
+    # 8 TB/s = 312 flop/byte) the kernel is priced against the dense bf16 MFMA peak instead
+    up_flops = 2.0 * A * w.d_model * 2 * w.d_ff
+    layer_flops = 2.0 * A * w.d_model * 3 * w.d_ff
+    traffic, traffic_head = (None, None) if q4 else recorded_traffic(w.name, "ffn_up_kernel")
+    if w.dtype == "bf16" and up_flops / up_bytes > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+        tf = up_flops / (prof["up_ms"] * 1e-3) / 1e12 if prof.get("up_ms", 0) > 0 else 0.0
+        down_tf = (2.0 * A * w.d_model * w.d_ff) / (prof["down_ms"] * 1e-3) / 1e12 if prof.get("down_ms", 0) > 0 else 0.0
+        roofline = {"bound": "mfma", "kernel": "ffn_up_kernel", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                    "traffic_recorded_at": traffic_head,
+                    "algorithmic_flops": up_flops, "algorithmic_bytes": up_bytes,
+                    "down_kernel_TFLOPs": down_tf, "down_kernel_frac": down_tf / MFMA_BF16_PEAK_TFLOPS,
+                    "layer_TFLOPs": layer_flops / (ms_per_step * 1e-3) / 1e12,
+                    "layer_frac": layer_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    else:
+        roofline = {"bound": "hbm", "kernel": "ffn_up_kernel", "achieved": achieved,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": traffic, "traffic_recorded_at": traffic_head, "algorithmic_bytes": up_bytes}
+
+    out = {
+        "metric": "moe_layer_tokens_per_s", "value": w.n_tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "d_model": w.d_model, "d_ff": w.d_ff,
+                   "n_experts": w.n_experts, "top_k": w.top_k, "n_batches": w.n_batches,
+                   "tokens": w.n_tokens, "experts": "resident in HBM", "weight_bits": args.weight_bits,
+                   "n_active": n_active,
+                   "h_format": "f32" if w.dtype == "f32" else ("bf16 pair" if q4 else
+                               "fp16 + fp16 remainder plane (" + ("always multiplied" if args.h_planes == 2
+                                                                   else "multiplied where needed") + ")"),
+                   "remainder_plane_workgroups_per_step": st["h_remainder_wgs"] / reps,
+                   "h_values_clamped": st["h_saturated"],
+                   "settle_steps_untimed": settle_steps,
+                   "tokens_per_expert": counts},
+        "roofline": roofline,
+        "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()},
+        "layer": {"algorithmic_bytes": layer_bytes,
+                  "hbm_frac_of_peak": layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                  "device_ms_per_step": dev_ms / steps},
+    }
+    ctx.close()
+    if with_cpu_baseline and not args.no_cpu_baseline and not q4:
+        out["cpu_baseline"] = cpu_baseline(w, data)
+    return out, data
+
+
+LEG_KEYS = ("value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config", "roofline", "kernels_us",
+            "layer", "token_layers_per_s", "host_link", "pipeline", "setup_s")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="mixtral8x7b_decode")
+    ap.add_argument("--workload", default=None,
+                    help="one workload only (default: the decode layer as the headline plus the prefill "
+                         "layer and the streamed stacks as legs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-variants", action="store_true",
-                    help="skip the extra measurement of the opt-in fp16 intermediate format")
-    ap.add_argument("--h-planes", type=int, default=0, help="0 = library default")
+    ap.add_argument("--no-legs", action="store_true", help="headline workload only")
+    ap.add_argument("--settle-ms", type=float, default=300.0,
+                    help="untimed steps run before the warm-up until the clocks have settled")
+    ap.add_argument("--h-planes", type=int, default=0,
+                    help="0 = library default (remainder plane of H multiplied where needed), 2 = always")
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
     ap.add_argument("--variant", type=int, default=0,
                     help="launch shape of the bf16 expert kernels (moe_set_tuning); 0 = library default")
@@ -490,122 +658,29 @@ def main():
     if args.workload in I.ATTN_WORKLOADS:
         print(json.dumps(bench_attention(I.ATTN_WORKLOADS[args.workload], args)))
         return
-    w = I.WORKLOADS[args.workload]
-    if w.streamed:
-        print(json.dumps(bench_streamed(w, args)))
+    if args.workload is not None:
+        w = I.WORKLOADS[args.workload]
+        out = bench_streamed(w, args) if w.streamed else bench_resident(w, args)[0]
+        print(json.dumps(out))
         return
-    dev = torch.device("cuda:0")
-    data, _ = I.gen_layer(w, 0, threads=16, with_experts=args.weight_bits != 4)
-    compute = torch.cuda.Stream()
-    q4 = args.weight_bits == 4
-    cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
-                        w.n_batches, B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1, 4 if q4 else 0)
-    ctx = B.MoeContext(cfg, compute)
-    if args.h_planes or args.split_k or args.variant:   # before placement: h_planes 3 packs W2 differently
-        ctx.set_tuning(args.split_k, args.h_planes, args.variant)
-    ctx.set_gate(0, data.wg.to(dev))
-    for e in range(w.n_experts + w.n_shared):
-        if q4:
-            trip = I.gen_expert_q4(w, 0, e)
-            ctx.set_expert_q4(0, e, tuple(tuple(t.to(dev) for t in m) for m in trip))
-        else:
-            ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
-    x = data.x.to(dev)
-    y = torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
-    bo = [int(v) for v in w.batch_offsets]
-    if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB read
-        dst = torch.empty_like(src)                                     # 1 GiB written
-        for _ in range(3):
-            torch.add(src, 1, out=dst)
-        del src, dst
-    torch.cuda.synchronize()
 
-    def step():
-        ctx.route(0, x, bo)
-        ctx.layer_forward(0, x, y)
-
-    with torch.cuda.stream(compute):
-        for _ in range(args.warmup):
-            step()
-    torch.cuda.synchronize()
-
-    # timed region: exactly K steps, inputs resident, bracketed by device synchronisation
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    with torch.cuda.stream(compute):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        ev0.record(compute)
-        for _ in range(args.steps):
-            step()
-        ev1.record(compute)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    dev_ms = ev0.elapsed_time(ev1)
-    ms_per_step = max(wall_ms, dev_ms) / args.steps
-
-    # per-kernel durations, HIP events recorded by the library between its launches
-    ctx.set_profiling(True)
-    prof = {}
-    reps = max(10, min(50, args.steps))
-    with torch.cuda.stream(compute):
-        for _ in range(reps):
-            step()
-            for k_, v in ctx.profile().items():
-                prof[k_] = prof.get(k_, 0.0) + v / reps
-    ctx.set_profiling(False)
-    counts, order, n_active = ctx.route_wait()
-
-    elt = w.elt_bytes
-    A = w.n_tokens * w.top_k
-    # algorithmic bytes of the dominant kernel (up projections + SwiGLU): W1 and W3 of every
-    # activated expert once, the gathered token rows once, H written once
-    wbytes = 9.0 / 16.0 if q4 else elt      # 4-bit codes + one (scale, zero point) pair per 64 weights
-    up_bytes = int(n_active * 2 * w.d_model * w.d_ff * wbytes) + A * w.d_model * elt + A * w.d_ff * elt
-    layer_bytes = (int(n_active * 3 * w.d_model * w.d_ff * wbytes) + w.n_tokens * w.d_model * elt * 2 +
-                   2 * A * w.d_ff * elt + A * w.d_model * 4)
-    achieved = up_bytes / (prof["up_ms"] * 1e-3) / 1e9 if prof.get("up_ms", 0) > 0 else 0.0
-    # gate and up projections: 2 flops x rows x d x 2f.  Above the machine balance (2.5 PFLOP/s over
-    # 8 TB/s = 312 flop/byte) the kernel is priced against the dense bf16 MFMA peak instead
-    up_flops = 2.0 * A * w.d_model * 2 * w.d_ff
-    layer_flops = 2.0 * A * w.d_model * 3 * w.d_ff
-    traffic = None if q4 else recorded_traffic(w.name, "ffn_up_kernel")
-    if w.dtype == "bf16" and up_flops / up_bytes > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
-        tf = up_flops / (prof["up_ms"] * 1e-3) / 1e12 if prof.get("up_ms", 0) > 0 else 0.0
-        roofline = {"bound": "mfma", "kernel": "ffn_up_kernel", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
-                    "algorithmic_flops": up_flops, "algorithmic_bytes": up_bytes,
-                    "layer_TFLOPs": layer_flops / (ms_per_step * 1e-3) / 1e12,
-                    "layer_frac": layer_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
-    else:
-        roofline = {"bound": "hbm", "kernel": "ffn_up_kernel", "achieved": achieved,
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": traffic, "algorithmic_bytes": up_bytes}
-
-    out = {
-        "metric": "moe_layer_tokens_per_s", "value": w.n_tokens / (ms_per_step * 1e-3),
-        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "d_model": w.d_model, "d_ff": w.d_ff,
-                   "n_experts": w.n_experts, "top_k": w.top_k, "n_batches": w.n_batches,
-                   "tokens": w.n_tokens, "experts": "resident in HBM", "weight_bits": args.weight_bits,
-                   "n_active": n_active,
-                   "h_format": "f32" if w.dtype == "f32" else H_FORMATS[args.h_planes or 2],
-                   "tokens_per_expert": counts},
-        "roofline": roofline,
-        "kernels_us": {k_.replace("_ms", ""): round(v * 1e3, 2) for k_, v in prof.items()},
-        "layer": {"algorithmic_bytes": layer_bytes,
-                  "hbm_frac_of_peak": layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                  "device_ms_per_step": dev_ms / args.steps},
-    }
-    ctx.close()
-    if (w.dtype == "bf16" and not q4 and args.h_planes == 0 and not args.calibrate_copy
-            and not args.no_variants):
-        out["opt_in_e5m2_remainder"] = h_format_variant(w, data, args, torch, B, 4)
-        out["opt_in_fp16_intermediate"] = h_format_variant(w, data, args, torch, B, 3)
-    if not args.no_cpu_baseline and not q4:
-        out["cpu_baseline"] = cpu_baseline(w, data)
+    # headline: the decode layer (HBM roofline); then the other legs of the metric
+    wd = I.WORKLOADS["mixtral8x7b_decode"]
+    out, data = bench_resident(wd, args)
+    if not args.no_legs:
+        legs = {}
+        wp = I.WORKLOADS["mixtral8x7b_prefill"]     # matrix-core roofline: same layer, 16384 tokens
+        dp = I.LayerData(x=I.gen_x_gaussian(wp), wg=data.wg, w1=data.w1, w3=data.w3, w2=data.w2)
+        leg, _ = bench_resident(wp, args, data=dp, steps=min(args.steps, 20), warmup=min(args.warmup, 5),
+                                with_cpu_baseline=False)
+        legs[wp.name] = {k: leg[k] for k in LEG_KEYS if k in leg}
+        del data, dp
+        release_memory(torch)
+        for name, bits in (("finegrained_stream", 16), ("finegrained_stream", 4), ("mixtral8x22b_stream", 16)):
+            args.weight_bits = bits                 # host-link roofline and the pipeline's bubbles
+            leg = bench_streamed(I.WORKLOADS[name], args)
+            legs[name + ("_4bit" if bits == 4 else "")] = {k: leg[k] for k in LEG_KEYS if k in leg}
+        out["legs"] = legs
     print(json.dumps(out))
 
 

@@ -8,9 +8,10 @@
  * pinned host residency; Section 8, "Overlapping Computation and I/O", for the streams).
  *
  * Conventions
- *  - Every entry point returns a moe_status; nothing throws, aborts or keeps
- *    process-global state.  A failed call leaves the context usable; the reason is
- *    available from moe_last_error().
+ *  - Every entry point returns a moe_status; nothing throws or aborts.  The library keeps no
+ *    process-global state except the last error text of calls that have no context (kept per
+ *    thread) and the static device scratch of moe_route_static.  A failed call leaves the
+ *    context usable; the reason is available from moe_last_error().
  *  - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses,
  *    "pinned" host pointers must come from hipHostMalloc (e.g. a pin_memory tensor).
  *  - The caller owns all tensors, the workspace, the window and both streams
@@ -83,7 +84,7 @@ typedef struct {
     double t_c_gate_s;       /* gate: bytes of X over hbm_Bps */
 } moe_plan_t;
 
-/* Counters of the streamed pipeline, cumulative since moe_create or moe_reset_stats. */
+/* Counters of the pipeline, cumulative since moe_create or moe_reset_stats. */
 typedef struct {
     int64_t tokens;          /* tokens routed */
     int64_t bytes_h2d;       /* expert bytes copied host -> device */
@@ -92,6 +93,17 @@ typedef struct {
     int64_t n_prefetch_unused; /* prefetched experts that the gate then did not select */
     int64_t n_forward;       /* moe_layer_forward calls */
     int64_t n_active_sum;    /* sum over forwards of activated routed experts */
+    int64_t h_saturated;     /* values of the intermediate H clamped to the fp16 range (0 in any sane layer) */
+    int64_t h_remainder_wgs; /* down-projection workgroups that multiplied the remainder plane of H because the
+                                recorded remainder energy of their tile asked for it (h_planes 1, see moe_set_tuning) */
+    /* The three times below cover the work enqueued while profiling was on (moe_set_profiling)
+     * since the last moe_reset_stats, measured with HIP events around every expert copy and
+     * every group of kernels; 0 when nothing was recorded.  The pipeline's bubble (paper
+     * Section 3 and Section 7, T = T_c + T_b) is 1 - compute_busy_ns / wall_ns; the idle
+     * fraction of the host link is 1 - copy_busy_ns / wall_ns. */
+    int64_t copy_busy_ns;    /* time with at least one expert copy in progress (union over the copy streams) */
+    int64_t compute_busy_ns; /* time the compute stream spent in this library's kernels */
+    int64_t wall_ns;         /* first recorded start to last recorded end */
 } moe_stats;
 
 /*
@@ -129,7 +141,8 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
 /* moe_destroy -- synchronises both streams, releases events and the mailbox. */
 moe_status moe_destroy(moe_ctx* ctx);
 
-/* moe_set_gate -- register the gate matrix Wg [E, d] (device) of a layer.  Not copied. */
+/* moe_set_gate -- register the gate matrix Wg [E, d] (device) of a layer: the gating network
+ * whose softmax scores select the top-k experts of every token (paper Section 2.1).  Not copied. */
 moe_status moe_set_gate(moe_ctx* ctx, int32_t layer, const void* wg_dev);
 
 /*
@@ -240,28 +253,25 @@ moe_status moe_stream_experts(moe_ctx* ctx, int32_t layer, const int32_t* expert
  */
 moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, void* y_dev);
 
-moe_status moe_get_stats(const moe_ctx* ctx, moe_stats* out);
+/* moe_get_stats blocks until the compute stream (and, for the three times, the recorded copies)
+ * are done.  moe_reset_stats zeroes the counters and drops the recorded spans. */
+moe_status moe_get_stats(moe_ctx* ctx, moe_stats* out);
 moe_status moe_reset_stats(moe_ctx* ctx);
 
 /*
  * moe_set_tuning -- knobs, 0 keeps the current value.  split_k: split of the down projection's
- * reduction (auto by default).  h_planes (bf16 only) is the format of the intermediate
- * H = silu(X W1^T) .* (X W3^T) between the two GEMMs.  2 (default) carries it as a pair of bf16
- * numbers (value and rounding remainder, both multiplied with W2 on the bf16 MFMA), which keeps
- * the layer inside the 1e-2 absolute tolerance at d_ff = 14336.  1 stores plain bf16 H (no
- * remainder: about twice the output error).  4 (opt-in, bf16 experts only) carries the remainder
- * in 8 bits instead (e5m2, nearest even, clamped to its finite range) and multiplies it with the
- * W2 fragment converted to e5m2 in registers on the 8-bit MFMA (fp32 accumulate), the value plane
- * staying on the bf16 MFMA: three quarters of the pair's MFMA time.  The remainder is 2^-9 of the
- * value and its product is then good to about 2^-3, so the error H contributes is about 0.07 of
- * plain bf16's (the pair: 2^-8 of it): inside the absolute tolerance while the outputs' typical
- * magnitude stays below about 10, which is why it is not the default.
- * 3 (opt-in, bf16 experts only) carries H as fp16 (11 significant bits, saturating at 65504) and
- * multiplies it with W2 converted to fp16 on an fp16 MFMA: the accuracy of the pair at the cost
- * of the single plane.  The conversion of W2 happens at placement, so h_planes must be set to 3
- * before moe_set_expert and kept; it is exact for |w| in [2^-14, 65504], rounds smaller weights
- * to fp16 subnormals (absolute error at most 2^-25) and fails with MOE_ERR_SHAPE on larger ones.
- * moe_layer_forward returns MOE_ERR_STATE when the experts were placed for another H format.
+ * reduction (auto by default).
+ * h_planes (bf16 experts): the intermediate H = silu(X W1^T) .* (X W3^T) is handed from the up
+ * projections to the down projection as fp16 (W2 is placed as fp16 as well, times a power of two
+ * when it holds weights beyond the fp16 range, undone on the outputs), together with a second
+ * fp16 plane holding the rounding remainder H - fp16(H).  1 (default): the down projection
+ * multiplies the remainder plane only for the tiles that need it -- the up kernel records the
+ * energy of the remainders per token row, and a tile whose rows all stay below the expert's
+ * threshold (6 standard deviations of the remainders' contribution to an output within 0.8 of
+ * the 1e-2 absolute tolerance, from the row energies of W2 taken at placement) is computed from
+ * the value plane alone, at half the matrix-core work.  2: the remainder plane is always
+ * multiplied (outputs then never depend on which tokens share a tile).  4-bit experts carry H as
+ * a bf16 pair and always multiply both planes.
  * variant: launch shape of the bf16 expert kernels, ones digit: 1 = 8 wavefronts x 1 output unit,
  * 2 = 7 x 1, 3 = 4 x 2 (0 = chosen by tile size); tens digit p (1..6): on full tiles the workgroups
  * an XCD runs together cover 2^(p-1) tiles x 32/2^(p-1) unit groups (0 = 4 x 8); -1 selects the
@@ -326,7 +336,10 @@ moe_status moe_corr_rank(const int32_t* table_host, const int32_t* counts_prev_h
                          int32_t K, int32_t* experts_out_host, int32_t* n_out, double* score_out);
 
 /*
- * Per-kernel timing of the last moe_route + moe_layer_forward pair (all-resident layers only),
+ * moe_set_profiling(1) turns on two things: HIP events around every expert copy and every group
+ * of kernels, from which moe_get_stats derives copy_busy_ns, compute_busy_ns and wall_ns (the
+ * events cost a few microseconds each: time throughput with profiling off); and the
+ * per-kernel timing of the last moe_route + moe_layer_forward pair (all-resident layers only),
  * taken with HIP events on the compute stream between the launches.  For the fp32 path up_ms is
  * 0 and down_ms covers both expert kernels.  moe_get_profile blocks until that forward is done.
  */

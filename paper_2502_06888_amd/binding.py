@@ -58,7 +58,8 @@ class MoePlan(C.Structure):
 class MoeStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in
                 ("tokens", "bytes_h2d", "n_copies", "n_prefetch_hits", "n_prefetch_unused",
-                 "n_forward", "n_active_sum")]
+                 "n_forward", "n_active_sum", "h_saturated", "h_remainder_wgs", "copy_busy_ns", "compute_busy_ns",
+                 "wall_ns")]
 
 
 class MoeProfile(C.Structure):
@@ -338,6 +339,9 @@ class MoeContext:
         if getattr(self, "h", None):
             self.lib.moe_destroy(self.h)
             self.h = None
+            self._keep = []          # the library no longer points into these
+            self.workspace = None
+            self.window = None
 
     def __del__(self):
         try:

@@ -58,23 +58,13 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float v) {
 }
 
 // One LDS stage holds, per row block, SX reduction steps of 16 for PL planes of the activations
-// (SX * PL == 8): SX = 8, PL = 1 normally; SX = 4, PL = 2 when H is carried as a bf16 pair
-// (value + rounding remainder) through the down projection.
-//
-// R8 (H as bf16 value + 8-bit remainder, down projection only): a stage is one group of four
-// reduction steps; per row block it holds the four bf16 value fragments (unit j*64 + lane) and,
-// behind the value fragments of all row blocks, the group's remainders: 8 bytes per lane and
-// step in e5m2, [step][lane], 128 units per row block.  The eight dwords of a lane over the four
-// steps are its operand of one 32x32x64 8-bit MFMA; the weight operand is the lane's four bf16
-// fragments of the same steps converted to e5m2 in registers, so both operands assign the same
-// reduction index to the same (lane half, byte) and no data moves between lanes.
-constexpr int kR8LoBase = kTileBlks * 4 * 64;   // first remainder unit of an R8 stage in LDS
+// (SX * PL == 8): SX = 8, PL = 1 normally; SX = 4, PL = 2 when the down projection also
+// multiplies the rounding remainder of H (second plane).
 struct TileCtx {
     gptr wbase;      // weight stream of this wavefront's first unit (+lane), 64 units per step
     size_t ustride;  // 16-byte units between the streams of consecutive output units
     gptr actbase;    // packed activations at the tile's first row block (plane 0)
     size_t plane;    // units between activation planes
-    size_t lo_off;   // R8: units from actbase to the tile's remainders (nks/4 * 128 units per row block)
     u32x4* lds;
     int nks;         // reduction steps of 16 in the whole reduction
     int k0, k1;      // reduction steps of this workgroup: [k0, k1), k0 a multiple of SX
@@ -117,42 +107,6 @@ struct XMap {
     }
 };
 
-// The same for an R8 stage.  A row block's part of the stage is six slots of 64 units: the four
-// value fragments of the group and the two halves of its 128 remainder units; a wavefront moves
-// one slot per pass.  Source: a base fixed for the tile plus the group index times a stride (256
-// units between the value fragments of consecutive groups, 128 between their remainders);
-// destination: the slot's place in the LDS stage.  Slots past the row blocks of this tile's class
-// read slot 0 again and land in the rows of a row block nobody multiplies (in bounds: checked
-// against the eight row blocks the stage has room for).
-template <int PASSES, int T>
-struct R8Map {
-    static_assert(T % 64 == 0 && PASSES * (T / 64) <= kTileBlks * 6, "slots fit the stage");
-    size_t base[PASSES];  // units from actbase at group 0, uniform
-    int gstep[PASSES];    // units per group, uniform
-    int dst[PASSES];      // unit in the LDS stage, uniform
-    __device__ __forceinline__ void init(const TileCtx& c) {
-        const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int slot = wave + p * (T / 64);
-            dst[p] = slot % 6 < 4 ? (slot / 6) * 256 + (slot % 6) * 64
-                                  : kR8LoBase + (slot / 6) * 128 + (slot % 6 - 4) * 64;
-            const int live = slot < c.nblk * 6 ? slot : 0;
-            const int b = live / 6, r = live % 6;
-            base[p] = r < 4 ? ((size_t)b * c.nks + r) * 64
-                            : c.lo_off + (size_t)b * c.nks * 32 + (size_t)(r - 4) * 64;
-            gstep[p] = r < 4 ? 256 : 128;
-        }
-    }
-    // kbase is a multiple of 4.  CLAMP: a group past the end of the reduction is the last one
-    // again; the steady state never gets there and skips the test.
-    template <bool CLAMP>
-    __device__ __forceinline__ u32x4 load(const TileCtx& c, int p, int kbase) const {
-        const int group = (CLAMP ? min(kbase, c.nks - 4) : kbase) >> 2;
-        return (c.actbase + base[p] + (size_t)group * gstep[p])[threadIdx.x & 63];
-    }
-};
-
 // When PASSES * T fits one LDS buffer the stores need no guard.
 template <int PASSES, int T>
 __device__ __forceinline__ void store_x(const TileCtx& c, const u32x4 (&xr)[PASSES], int buf) {
@@ -162,13 +116,6 @@ __device__ __forceinline__ void store_x(const TileCtx& c, const u32x4 (&xr)[PASS
         if (PASSES * T <= kBufUnits || u < kBufUnits) c.lds[buf * kBufUnits + u] = xr[p];
     }
 }
-template <int PASSES, int T>
-__device__ __forceinline__ void store_x_r8(const TileCtx& c, const R8Map<PASSES, T>& m,
-                                           const u32x4 (&xr)[PASSES], int buf) {
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) c.lds[buf * kBufUnits + m.dst[p] + (threadIdx.x & 63)] = xr[p];
-}
-
 // HT = 0: bf16 operands; HT = 1: fp16 operands (down projection with H carried as fp16).
 template <int MODE, int HT = 0>
 __device__ __forceinline__ f32x16 mfma(const bf16x8 wf, const bf16x8 xa, const f32x16 acc) {
@@ -277,122 +224,6 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
 #undef KMOE_STORE_AT
 }
 
-// ---- R8: bf16 value plane + 8-bit (e5m2) remainder plane ---------------------------------------
-
-// The lane's bf16 weight fragment of one step as e5m2 (nearest even): dwords 2j, 2j+1 of the
-// 8-bit operand of the group.
-__device__ __forceinline__ void to_e5m2(const u32x4 w, int j, i32x8& q) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        // the dwords are copied to scalars first: a bit cast applied directly to an element of a
-        // vector value reads element 0 with this compiler
-        const uint32_t w0 = w[2 * h], w1 = w[2 * h + 1];
-        i16x2 v = {0, 0};
-        v = __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(v, __builtin_bit_cast(bf16x2, w0), 1.0f, false);
-        v = __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(v, __builtin_bit_cast(bf16x2, w1), 1.0f, true);
-        q[2 * j + h] = __builtin_bit_cast(int, v);
-    }
-}
-
-// Remainder products of one group for all row blocks: acc[u][b] += lo_b . e5m2(W) over 64
-// reduction indices, one 32x32x64 MFMA each (rows = tokens, cols = output columns).
-template <int NB, int U>
-__device__ __forceinline__ void lo_mfma(const u32x4* stage, const i32x8 (&wq)[U], f32x16 (&acc)[U][NB]) {
-    const int lane = threadIdx.x & 63;
-    const u32x2* lo = reinterpret_cast<const u32x2*>(stage + kR8LoBase) + lane;
-    u32x2 v[2][4];  // the operand of the next row block is read while this one multiplies
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[0][j] = lo[j * 64];
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if (b + 1 < NB) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[(b + 1) & 1][j] = lo[(b + 1) * 256 + j * 64];
-        }
-        const u32x2(&c)[4] = v[b & 1];
-        const i32x8 xa = {(int)c[0][0], (int)c[0][1], (int)c[1][0], (int)c[1][1],
-                          (int)c[2][0], (int)c[2][1], (int)c[3][0], (int)c[3][1]};
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            acc[u][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xa, wq[u], acc[u][b], 1, 1, 0, 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if (b + 1 < NB) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
-    }
-}
-
-// A whole R8 stage: the value MFMAs of the four steps as in stage_mfma (SX = 4, one plane); each
-// step's weight fragment is converted to e5m2 before its ring slot is reloaded; the remainder
-// MFMAs of the group follow.  `stage` is the LDS buffer (no lane offset).
-template <int NB, int U, int D, int PASSES, int T, int DX>
-__device__ __forceinline__ void stage_mfma_r8(const u32x4* stage, u32x4 (&w)[4][U], gptr wnext,
-                                              size_t ustride, f32x16 (&acc)[U][NB],
-                                              u32x4* next_buf, const u32x4 (&xs)[PASSES],
-                                              const TileCtx& c, const R8Map<PASSES, T>& m, int kload,
-                                              u32x4 (&xl)[PASSES]) {
-    constexpr int NF = NB * 4;
-    constexpr int DD = D < NF ? D : NF;
-    // loads of the stage at step kload and stores of the next stage between the value MFMAs, as
-    // in stage_mfma
-    constexpr int L1 = DX == 1 ? (NF / 4 > PASSES ? NF / 4 : PASSES) : NF;
-    constexpr int S0 = DX == 1 ? NF / 2 : 0;
-    static_assert(PASSES <= NF / 2, "one pass per fragment at most");
-    const int lane = threadIdx.x & 63;
-    const u32x4* L = stage + lane;
-    u32x4 win[DD];
-    i32x8 wq[U];
-#define KMOE_FRAG_AT(t) L[(((t) % NB) * 4 + (t) / NB) * 64]
-#define KMOE_LOAD_AT(p) (((p) * L1) / PASSES)
-#define KMOE_STORE_AT(p) (S0 + ((p) * (NF - S0)) / PASSES)
-#pragma unroll
-    for (int t = 0; t < DD; ++t) win[t] = KMOE_FRAG_AT(t);
-#pragma unroll
-    for (int t = 0; t < NF; ++t) {
-        const int j = t / NB, b = t % NB;
-        const bf16x8 xa = as_bf16x8(win[t % DD]);
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc[u][b] = mfma<1>(as_bf16x8(w[j][u]), xa, acc[u][b]);
-        if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
-        {
-            const int p = t < S0 ? PASSES : ((t - S0) * PASSES + (NF - S0) - 1) / (NF - S0);
-            if (p < PASSES && KMOE_STORE_AT(p) == t) next_buf[m.dst[p] + lane] = xs[p];
-        }
-        {
-            const int p = (t * PASSES + L1 - 1) / L1;
-            if (p < PASSES && KMOE_LOAD_AT(p) == t) xl[p] = m.template load<false>(c, p, kload);
-        }
-        if (b == NB - 1) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                to_e5m2(w[j][u], j, wq[u]);
-                w[j][u] = load_stream(wnext + (size_t)u * ustride + (size_t)j * 64);
-            }
-        }
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
-#pragma unroll
-    for (int t = 0; t < NF; ++t) {
-        __builtin_amdgcn_sched_group_barrier(0x008, U, 0);
-        if (t + DD < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        const int ps = t < S0 ? PASSES : ((t - S0) * PASSES + (NF - S0) - 1) / (NF - S0);
-        if (ps < PASSES && KMOE_STORE_AT(ps) == t) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-        const int pl = (t * PASSES + L1 - 1) / L1;
-        if (pl < PASSES && KMOE_LOAD_AT(pl) == t) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        if (t % NB == NB - 1) {
-            __builtin_amdgcn_sched_group_barrier(0x002, 4 * U, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, U, 0);
-        }
-    }
-#undef KMOE_FRAG_AT
-#undef KMOE_LOAD_AT
-#undef KMOE_STORE_AT
-    __builtin_amdgcn_sched_barrier(0);
-    lo_mfma<NB, U>(stage, wq, acc);
-}
-
 // Register budget of one shape: the weight ring is RING steps deep (U KiB per step in flight
 // per wavefront), the activation look-ahead DX stages.
 template <int NB, int WAVES, int U>
@@ -403,10 +234,10 @@ struct Shape2 {
 
 // Registers of the software pipeline of one tile pass: the weight ring (RS stages of SX steps,
 // U units) and the activations in flight to LDS (DX stages ahead).
-template <int NB, int WAVES, int U, int SX, int R8 = 0>
+template <int NB, int WAVES, int U, int SX>
 struct Pipe {
     static constexpr int T = WAVES * 64;
-    static constexpr int PASSES = R8 ? (NB * 6 + T / 64 - 1) / (T / 64) : (NB * kBlkStageUnits + T - 1) / T;
+    static constexpr int PASSES = (NB * kBlkStageUnits + T - 1) / T;
     static constexpr int RS = Shape2<NB, WAVES, U>::RING / SX;
     // Activation look-ahead in stages.  The memory counter retires loads in issue order, so the
     // wait for a stage's activations (before they are stored to LDS) also waits for every
@@ -419,21 +250,13 @@ struct Pipe {
     static_assert(RS >= 1 && G % RS == 0 && G % DX == 0, "group must cycle ring and look-ahead");
     u32x4 wr[RS][SX][U];
     u32x4 xr[DX][PASSES];
-    R8Map<R8 ? PASSES : 1, T> r8;  // R8 only
-    XMap<R8 ? 1 : PASSES, T, SX, 8 / SX> xm;  // the other formats
-    __device__ __forceinline__ void init(const TileCtx& c) {
-        if constexpr (R8) r8.init(c); else xm.init(c);
-    }
+    XMap<PASSES, T, SX, 8 / SX> xm;
+    __device__ __forceinline__ void init(const TileCtx& c) { xm.init(c); }
     template <int PL>
     __device__ __forceinline__ void load(const TileCtx& c, int slot, int kbase) {
-        if constexpr (R8) {
+        static_assert(PL == 8 / SX, "planes per stage");
 #pragma unroll
-            for (int p = 0; p < PASSES; ++p) xr[slot][p] = r8.template load<true>(c, p, kbase);
-        } else {
-            static_assert(PL == 8 / SX, "planes per stage");
-#pragma unroll
-            for (int p = 0; p < PASSES; ++p) xr[slot][p] = xm.template load<true>(c, p, kbase);
-        }
+        for (int p = 0; p < PASSES; ++p) xr[slot][p] = xm.template load<true>(c, p, kbase);
     }
 };
 
@@ -442,9 +265,9 @@ struct Pipe {
 // loop head are the same on entry and on the back edge.  Nothing is waited for here: a
 // workgroup calls this for its next pass before the epilogue of the current one, so the
 // memory latency of the ring fill hides behind the epilogue.
-template <int NB, int WAVES, int U, int SX, int PL, int R8 = 0>
-__device__ __forceinline__ void open_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX, R8>& pp) {
-    using P = Pipe<NB, WAVES, U, SX, R8>;
+template <int NB, int WAVES, int U, int SX, int PL>
+__device__ __forceinline__ void open_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX>& pp) {
+    using P = Pipe<NB, WAVES, U, SX>;
 #pragma unroll
     for (int i = 0; i < P::G; ++i) {
         if (i < P::DX) pp.template load<PL>(c, i, c.k0 + i * SX);
@@ -461,11 +284,11 @@ __device__ __forceinline__ void open_pass(const TileCtx& c, Pipe<NB, WAVES, U, S
 
 // One pass over the reduction range of the tile for the U units of every wavefront; the pass
 // must have been opened.  On return all LDS reads of the pass are behind a barrier.
-template <int MODE, int NB, int WAVES, int U, int SX, int PL, int HT = 0, int R8 = 0>
-__device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX, R8>& pp,
+template <int MODE, int NB, int WAVES, int U, int SX, int PL, int HT = 0>
+__device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX>& pp,
                                          f32x16 (&acc)[U][NB]) {
-    static_assert(R8 ? (SX == 4 && PL == 1 && MODE == 1 && HT == 0) : SX * PL == kFragsPerBlk, "stage geometry");
-    using P = Pipe<NB, WAVES, U, SX, R8>;
+    static_assert(SX * PL == kFragsPerBlk, "stage geometry");
+    using P = Pipe<NB, WAVES, U, SX>;
     constexpr int T = P::T, PASSES = P::PASSES, RS = P::RS, DX = P::DX, G = P::G;
     constexpr int D = 3;
     const int lane = threadIdx.x & 63;
@@ -477,7 +300,7 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[u][b][i] = 0.f;
 
-    if constexpr (R8) store_x_r8<PASSES, T>(c, pp.r8, pp.xr[0], 0); else store_x<PASSES, T>(c, pp.xr[0], 0);
+    store_x<PASSES, T>(c, pp.xr[0], 0);
     __syncthreads();
 
     int k = c.k0, buf = 0;
@@ -491,14 +314,9 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
             const int kk = k + g * SX;
             __builtin_amdgcn_sched_barrier(0);
             const u32x4* L = c.lds + buf * kBufUnits + lane;
-            if constexpr (R8)
-                stage_mfma_r8<NB, U, D, PASSES, T, DX>(
-                    c.lds + buf * kBufUnits, pp.wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc,
-                    c.lds + (buf ^ 1) * kBufUnits, pp.xr[(g + 1) % DX], c, pp.r8, kk + DX * SX, pp.xr[g % DX]);
-            else
-                stage_mfma<MODE, NB, U, SX, PL, D, HT, PASSES, T, DX>(
-                    L, pp.wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc,
-                    c.lds + (buf ^ 1) * kBufUnits, pp.xr[(g + 1) % DX], c, pp.xm, kk + DX * SX, pp.xr[g % DX]);
+            stage_mfma<MODE, NB, U, SX, PL, D, HT, PASSES, T, DX>(
+                L, pp.wr[g % RS], c.wbase + (size_t)(kk + RS * SX) * 64, c.ustride, acc,
+                c.lds + (buf ^ 1) * kBufUnits, pp.xr[(g + 1) % DX], c, pp.xm, kk + DX * SX, pp.xr[g % DX]);
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
             buf ^= 1;
@@ -514,15 +332,10 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
                 if (kk + DX * SX < c.k1)
                     pp.template load<PL>(c, g % DX, kk + DX * SX);
                 const u32x4* L = c.lds + buf * kBufUnits + lane;
-                i32x8 wq[U];  // R8 only (its stages are always whole groups)
 #pragma unroll
                 for (int j = 0; j < SX; ++j) {
                     if (kk + j < c.k1) {
                         step_mfma<MODE, NB, U, SX, PL, D, HT>(L, j, pp.wr[g % RS][j], acc);
-                        if constexpr (R8) {
-#pragma unroll
-                            for (int u = 0; u < U; ++u) to_e5m2(pp.wr[g % RS][j][u], j, wq[u]);
-                        }
                         if (kk + RS * SX + j < c.k1) {
 #pragma unroll
                             for (int u = 0; u < U; ++u)
@@ -532,11 +345,7 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
                         }
                     }
                 }
-                if constexpr (R8) lo_mfma<NB, U>(c.lds + buf * kBufUnits, wq, acc);
-                if (more) {
-                    if constexpr (R8) store_x_r8<PASSES, T>(c, pp.r8, pp.xr[(g + 1) % DX], buf ^ 1);
-                    else store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
-                }
+                if (more) store_x<PASSES, T>(c, pp.xr[(g + 1) % DX], buf ^ 1);
                 __syncthreads();
                 buf ^= 1;
             }
@@ -548,6 +357,17 @@ struct Wg {
     int tile, grp, sp;
     bool live;
 };
+
+// Packed weights of expert e for this launch: one blob for all tiles (a streamed expert run on
+// its own), a window slot named in the launch's group list, or the layer's table of resident blobs.
+__device__ __forceinline__ const uint8_t* blob_of(const FfnArgs& a, int e) {
+    if (a.w_single) return a.w_single;
+    const uint8_t* blob = nullptr;
+#pragma unroll
+    for (int i = 0; i < kMaxLaunchGroup; ++i)
+        if (i < a.n_group && a.group_expert[i] == e) blob = a.w_group[i];
+    return blob ? blob : a.wtab[e];
+}
 
 // XCD-aware map from the hardware workgroup id (dealt round-robin to the 8 XCDs) to a logical
 // id such that each XCD walks a contiguous range of (tile, split, group) items.  Two orders of
@@ -563,7 +383,7 @@ struct Wg {
 constexpr int kPanelTiles = 4, kPanelCols = 8;
 __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) {
     Wg w;
-    const int ntile = *a.tile_count;
+    const int ntile = a.tile_count ? *a.tile_count : a.tile_count_v;
     const int per_tile = n_groups * split;
     const int live = ntile * per_tile;
     const int per_xcd = (live + kXcd - 1) / kXcd;
@@ -584,7 +404,7 @@ __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) 
         tile = L / per_tile;
         r = L % per_tile;
     }
-    w.tile = (a.tile_first ? *a.tile_first : 0) + tile;
+    w.tile = (a.tile_first ? *a.tile_first : a.tile_first_v) + tile;
     w.sp = r / n_groups;
     w.grp = r % n_groups;
     return w;
@@ -594,21 +414,34 @@ __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) 
 // holds, in register r < 8, the gate value of feature 16*unit + 8*(r/4) + 4*hi + r%4 and in
 // register r + 8 the up value of the same feature: exactly the lane's 16-byte unit in the
 // fragment order of the down projection, so H is written with one 16-byte store per row block.
-template <int NB, int U>
+//
+// Format of H.  bf16 experts (h_mode 0, 1): fp16 (nearest even, clamped to the largest finite
+// value; clamped values are counted), plus a second plane with the rounding remainder
+// h - fp16(h), also fp16.  The down projection multiplies the remainder plane only for tiles that
+// need it: the up kernel adds, per token row, the energy of the remainders (sum of squares over
+// the features of this workgroup) to herr[row], in integer units of 2^-20 of the expert's
+// threshold, so that the total does not depend on the order of the atomic additions.
+// 4-bit experts (h_mode 2): a bf16 pair (value and remainder), both always multiplied.
+constexpr float kErrUnit = 1048576.f;  // herr counts in units of threshold / 2^20
+template <int NB, int WAVES, int U>
 __device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U][NB], int nblk,
-                                         int wunit, int unit0, int hblk0) {
+                                         int wunit, int unit0, int hblk0, int expert, u32x4* lds) {
     const int lane = threadIdx.x & 63;
     u32x4* hp = reinterpret_cast<u32x4*>(a.out);
     const size_t ksteps_h = (size_t)a.f / 16;
+    const bool pair_bf16 = a.h_mode == 2;
+    float esum[NB];
+    int sat = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) esum[b] = 0.f;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (wunit + u < unit0) continue;  // streamed only to stay in bounds: another wavefront's
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             if (b < nblk) {
-                // H = silu(gate) * up, rounded to bf16 (RNE, hardware conversion); the second plane
-                // carries the rounding remainder.  silu through the hardware reciprocal (1 ulp),
-                // far inside the bf16 rounding of H.
+                // H = silu(gate) * up; silu through the hardware reciprocal (1 ulp), far inside
+                // the rounding of H
                 uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -618,60 +451,63 @@ __device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U
                         const float gv = acc[u][b][2 * q + t];
                         h[t] = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][2 * q + t + 8];
                     }
-                    const bf16x2 v = {(__bf16)h[0], (__bf16)h[1]};
-                    const bf16x2 l = {(__bf16)(h[0] - (float)v[0]), (__bf16)(h[1] - (float)v[1])};
-                    hi[q] = __builtin_bit_cast(uint32_t, v);
-                    lo[q] = __builtin_bit_cast(uint32_t, l);
-                }
-                const size_t at = ((size_t)(hblk0 + b) * ksteps_h + (size_t)(wunit + u)) * 64 + lane;
-                if (a.h_planes == 3) {  // H as fp16 (nearest-even, saturating at the largest finite value)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float h[2];
+                    if (pair_bf16) {
+                        const bf16x2 v = {(__bf16)h[0], (__bf16)h[1]};
+                        const bf16x2 l = {(__bf16)(h[0] - (float)v[0]), (__bf16)(h[1] - (float)v[1])};
+                        hi[q] = __builtin_bit_cast(uint32_t, v);
+                        lo[q] = __builtin_bit_cast(uint32_t, l);
+                    } else {
+                        float r[2];
+                        f16x2 v, l;
 #pragma unroll
                         for (int t = 0; t < 2; ++t) {
-                            const float gv = acc[u][b][2 * q + t];
-                            const float v = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][2 * q + t + 8];
-                            h[t] = __builtin_fminf(__builtin_fmaxf(v, -65504.f), 65504.f);
+                            sat += __builtin_fabsf(h[t]) > 65504.f ? 1 : 0;
+                            v[t] = (_Float16)__builtin_fminf(__builtin_fmaxf(h[t], -65504.f), 65504.f);
+                            r[t] = h[t] - (float)v[t];  // exact in fp32
+                            l[t] = (_Float16)__builtin_fminf(__builtin_fmaxf(r[t], -65504.f), 65504.f);
+                            esum[b] = __builtin_fmaf(r[t], r[t], esum[b]);
                         }
-                        const f16x2 v = {(_Float16)h[0], (_Float16)h[1]};
                         hi[q] = __builtin_bit_cast(uint32_t, v);
+                        lo[q] = __builtin_bit_cast(uint32_t, l);
                     }
                 }
+                const size_t at = ((size_t)(hblk0 + b) * ksteps_h + (size_t)(wunit + u)) * 64 + lane;
                 // streaming stores: measurably cheaper next to the weight stream than cached ones
                 __builtin_nontemporal_store(u32x4{hi[0], hi[1], hi[2], hi[3]}, hp + at);
-                if (a.h_planes == 2)
-                    __builtin_nontemporal_store(u32x4{lo[0], lo[1], lo[2], lo[3]},
-                                                hp + at + (size_t)a.h_plane_units);
-                if (a.h_planes == 4) {  // remainder as e5m2 (nearest even, clamped to its finite range)
-                    float r[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const float gv = acc[u][b][i];
-                        const float h = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][i + 8];
-                        const float hv = __uint_as_float((hi[i / 2] >> (16 * (i % 2))) << 16);
-                        r[i] = __builtin_fminf(__builtin_fmaxf(h - hv, -57344.f), 57344.f);
-                    }
-                    uint32_t r8[2];
-#pragma unroll
-                    for (int h2 = 0; h2 < 2; ++h2) {
-                        int v = __builtin_amdgcn_cvt_pk_bf8_f32(r[4 * h2], r[4 * h2 + 1], 0, false);
-                        v = __builtin_amdgcn_cvt_pk_bf8_f32(r[4 * h2 + 2], r[4 * h2 + 3], v, true);
-                        r8[h2] = (uint32_t)v;
-                    }
-                    u32x2* lp = reinterpret_cast<u32x2*>(hp + (size_t)a.h_plane_units);
-                    __builtin_nontemporal_store(u32x2{r8[0], r8[1]}, lp + at);
-                }
+                __builtin_nontemporal_store(u32x4{lo[0], lo[1], lo[2], lo[3]},
+                                            hp + at + (size_t)a.h_plane_units);
             }
         }
+    }
+    if (a.h_mode != 0) return;  // uniform over the launch
+    if (sat) atomicAdd(a.sat_count, sat);
+    // remainder energy per token row of the tile: lanes l and l + 32 hold the same token, the
+    // wavefronts meet in LDS (free: every LDS read of the pass is behind a barrier), one integer
+    // atomic per row and workgroup
+    float* red = reinterpret_cast<float*>(lds);
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        esum[b] += __shfl_xor(esum[b], 32, 64);
+        if (lane < 32) red[(wave * NB + b) * 32 + lane] = esum[b];
+    }
+    __syncthreads();
+    const float inv_tau = a.wmeta[expert].y * kErrUnit;
+    for (int i = threadIdx.x; i < nblk * 32; i += WAVES * 64) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += red[w * NB * 32 + i];
+        const unsigned long long q = (unsigned long long)__builtin_fminf(sum * inv_tau, 1.7e13f);
+        if (q) atomicAdd(a.herr + (size_t)hblk0 * 32 + i, q);
     }
 }
 
 // Down projection: lane (column n = lane & 31, half hi) holds in register r the token row
-// 8*(r/4) + 4*hi + r%4 of the row block.
+// 8*(r/4) + 4*hi + r%4 of the row block.  `scale` undoes the power-of-two scaling of W2 (1 unless
+// the expert holds weights beyond the fp16 range).
 template <int NB, int U>
 __device__ __forceinline__ void store_down(const FfnArgs& a, const f32x16 (&acc)[U][NB], int nblk,
-                                           int wunit, int unit0, int hblk0, int sp) {
+                                           int wunit, int unit0, int hblk0, int sp, float scale) {
     const int lane = threadIdx.x & 63;
     float* o = reinterpret_cast<float*>(a.out) + (size_t)sp * a.o_split_stride;
 #pragma unroll
@@ -685,7 +521,7 @@ __device__ __forceinline__ void store_down(const FfnArgs& a, const f32x16 (&acc)
                 for (int r = 0; r < 16; ++r) {
                     const size_t row =
                         (size_t)(hblk0 + b) * kRowBlk + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
-                    __builtin_nontemporal_store(acc[u][b][r], o + row * a.d + col);
+                    __builtin_nontemporal_store(acc[u][b][r] * scale, o + row * a.d + col);
                 }
             }
         }
@@ -699,23 +535,23 @@ __device__ __forceinline__ void store_down(const FfnArgs& a, const f32x16 (&acc)
 // run's loads issued before the epilogue, were measured to gain nothing, and the loop around
 // the reduction loop made the compiler wait in every stage for reloads it had placed on the
 // outer back edge.)
-template <int MODE, int NB, int WAVES, int U, int PL, int HT = 0, int R8 = 0>
+template <int MODE, int NB, int WAVES, int U, int PL, int HT = 0>
 __device__ __forceinline__ void run_tile(const FfnArgs& a, TileCtx c, gptr wsection, int n_units,
-                                         int grp, int hblk0, int sp) {
-    constexpr int SX = R8 ? 4 : 8 / PL;
+                                         int grp, int hblk0, int sp, int expert, float scale) {
+    constexpr int SX = 8 / PL;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
-    Pipe<NB, WAVES, U, SX, R8> pp;
+    Pipe<NB, WAVES, U, SX> pp;
     f32x16 acc[U][NB];
     const int unit0 = (grp * WAVES + wave) * U;
     const int wunit = min(unit0, n_units - U);
     c.wbase = wsection + (size_t)wunit * c.ustride + lane;
     pp.init(c);
-    open_pass<NB, WAVES, U, SX, PL, R8>(c, pp);
-    run_pass<MODE, NB, WAVES, U, SX, PL, HT, R8>(c, pp, acc);
+    open_pass<NB, WAVES, U, SX, PL>(c, pp);
+    run_pass<MODE, NB, WAVES, U, SX, PL, HT>(c, pp, acc);
     if (MODE == 0)
-        store_up<NB, U>(a, acc, c.nblk, wunit, unit0, hblk0);
+        store_up<NB, WAVES, U>(a, acc, c.nblk, wunit, unit0, hblk0, expert, c.lds);
     else
-        store_down<NB, U>(a, acc, c.nblk, wunit, unit0, hblk0, sp);
+        store_down<NB, U>(a, acc, c.nblk, wunit, unit0, hblk0, sp, scale);
 }
 
 #define NB_SWITCH(CALL)                       \
@@ -734,7 +570,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
     const int e = a.tile_expert[w.tile];
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
-    const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
+    const uint8_t* blob = blob_of(a, e);
     TileCtx c;
     c.nks = a.d / 16;
     c.ustride = (size_t)c.nks * 64;
@@ -744,12 +580,16 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
     c.k0 = 0;
     c.k1 = c.nks;
     c.nblk = nblk;
-#define CALL(NB) run_tile<0, NB, WAVES, U, 1>(a, c, as_global(blob), a.f / 16, w.grp, hblk0, 0)
+#define CALL(NB) run_tile<0, NB, WAVES, U, 1>(a, c, as_global(blob), a.f / 16, w.grp, hblk0, 0, e, 1.f)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
-template <int WAVES, int U, int PL, int HT = 0, int R8 = 0>
+// Down projection of bf16 experts: H and W2 as fp16 on the fp16 MFMA.  The remainder plane of H
+// is multiplied as well (two planes per stage, twice the MFMAs) when the launch asks for it
+// (h_mode 1) or when, for some token row of the tile, the energy of the remainders recorded by
+// the up kernel exceeds the expert's threshold (h_mode 0); the test is uniform over the workgroup.
+template <int WAVES, int U>
 __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_groups) {
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, a.split_k);
@@ -757,23 +597,41 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     const int e = a.tile_expert[w.tile];
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
-    const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
+    const uint8_t* blob = blob_of(a, e);
+    const float scale = a.wmeta[e].x;
+    int two = a.h_mode == 1;
+    if (a.h_mode == 0) {
+        static_assert(WAVES * 64 >= kTileBlks * kRowBlk, "one thread per token row of the tile");
+        const int over = (int)threadIdx.x < nblk * kRowBlk &&
+                         a.herr[(size_t)hblk0 * kRowBlk + threadIdx.x] > (unsigned long long)kErrUnit;
+        two = __syncthreads_or(over);
+        if (two && threadIdx.x == 0) atomicAdd(a.sat_count + 1, 1);  // workgroups that took the remainder plane
+    }
     TileCtx c;
     c.nks = a.f / 16;
     c.ustride = (size_t)c.nks * 64;
     c.actbase = as_global(a.act) + (size_t)hblk0 * c.nks * 64;
     c.plane = (size_t)a.h_plane_units;
-    c.lo_off = (size_t)a.h_plane_units - (size_t)hblk0 * c.nks * 32;  // plane + hblk0*nks*32 - hblk0*nks*64
     c.lds = lds;
-    constexpr int SX = R8 ? 4 : 8 / PL;
-    const int nstage = (c.nks + SX - 1) / SX;
-    c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
-    c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
     c.nblk = nblk;
-#define CALL(NB) \
-    run_tile<1, NB, WAVES, U, PL, HT, R8>(a, c, as_global(blob + (size_t)a.d * a.f * 4), a.d / 32, w.grp, hblk0, w.sp)
-    NB_SWITCH(CALL)
+    const gptr wsec = as_global(blob + (size_t)a.d * a.f * 4);
+    if (two) {
+        constexpr int SX = 4;
+        const int nstage = (c.nks + SX - 1) / SX;
+        c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
+        c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
+#define CALL(NB) run_tile<1, NB, WAVES, U, 2, 1>(a, c, wsec, a.d / 32, w.grp, hblk0, w.sp, e, scale)
+        NB_SWITCH(CALL)
 #undef CALL
+    } else {
+        constexpr int SX = 8;
+        const int nstage = (c.nks + SX - 1) / SX;
+        c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
+        c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
+#define CALL(NB) run_tile<1, NB, WAVES, U, 1, 1>(a, c, wsec, a.d / 32, w.grp, hblk0, w.sp, e, scale)
+        NB_SWITCH(CALL)
+#undef CALL
+    }
 }
 
 // ---- 4-bit group-quantised expert weights ------------------------------------------------------
@@ -942,9 +800,9 @@ __device__ __forceinline__ void run_tile_q4(const FfnArgs& a, TileCtx c, const u
     open_pass_q4<NB, WAVES, SX, PL>(c, q, pp);
     run_pass_q4<MODE, NB, WAVES, SX, PL>(c, q, pp, acc);
     if (MODE == 0)
-        store_up<NB, 1>(a, acc, c.nblk, wunit, unit0, hblk0);
+        store_up<NB, WAVES, 1>(a, acc, c.nblk, wunit, unit0, hblk0, 0, c.lds);  // h_mode 2: bf16 pair
     else
-        store_down<NB, 1>(a, acc, c.nblk, wunit, unit0, hblk0, sp);
+        store_down<NB, 1>(a, acc, c.nblk, wunit, unit0, hblk0, sp, 1.f);
 }
 
 // Blob of a 4-bit expert: [up codes d*f | up (s,z) d*f/8 | down codes d*f/2 | down (s,z) d*f/16] bytes.
@@ -956,7 +814,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_q4_kernel(FfnArgs a, int n_
     const int e = a.tile_expert[w.tile];
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
-    const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
+    const uint8_t* blob = blob_of(a, e);
     TileCtx c;
     c.nks = a.d / 16;
     c.ustride = 0;
@@ -981,7 +839,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_q4_kernel(FfnArgs a, int 
     const int e = a.tile_expert[w.tile];
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
-    const uint8_t* blob = a.w_single ? a.w_single : a.wtab[e];
+    const uint8_t* blob = blob_of(a, e);
     TileCtx c;
     c.nks = a.f / 16;
     c.ustride = 0;
@@ -1009,12 +867,12 @@ void launch_up(hipStream_t st, const FfnArgs& a) {
                        n_groups);
 }
 
-template <int WAVES, int U, int PL, int HT = 0, int R8 = 0>
+template <int WAVES, int U>
 void launch_down(hipStream_t st, const FfnArgs& a) {
     const int n_groups = (a.d / 32 + WAVES * U - 1) / (WAVES * U);
     const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((ffn_down_kernel<WAVES, U, PL, HT, R8>), dim3(grid), dim3(WAVES * 64), kLdsBytes,
-                       st, a, n_groups);
+    hipLaunchKernelGGL((ffn_down_kernel<WAVES, U>), dim3(grid), dim3(WAVES * 64), kLdsBytes, st, a,
+                       n_groups);
 }
 
 template <typename K>
@@ -1028,19 +886,11 @@ hipError_t allow_lds(K kernel) {
 int ffn_configure() {
     hipError_t e = allow_lds(&ffn_up_kernel<8, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_up_q4_kernel<8>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_q4_kernel<8, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_down_q4_kernel<8, 2>);
-
     if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<7, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<4, 2>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 1>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 2>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 1, 1>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1, 1>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 2>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1, 1, 0, 1>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2, 1, 0, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<4, 2>);
     return (int)e;
 }
 
@@ -1067,32 +917,18 @@ void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) {
 }
 
 void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
-    if (a.weight_bits == 4) {
+    if (a.weight_bits == 4) {  // 4-bit experts: bf16 pair, both planes always
         const int n_groups = (a.d / 32 + 7) / 8;
         const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
-        if (a.h_planes == 2)
-            hipLaunchKernelGGL((ffn_down_q4_kernel<8, 2>), dim3(grid), dim3(512), kLdsBytes, st, a, n_groups);
-        else
-            hipLaunchKernelGGL((ffn_down_q4_kernel<8, 1>), dim3(grid), dim3(512), kLdsBytes, st, a, n_groups);
+        hipLaunchKernelGGL((ffn_down_q4_kernel<8, 2>), dim3(grid), dim3(512), kLdsBytes, st, a, n_groups);
         return;
     }
+    // Two units per wavefront halve the LDS reads per MFMA: faster on full tiles (prefill layer)
+    // and whenever the remainder plane is multiplied too (twice the MFMAs per weight byte); with
+    // one plane on small tiles (decode layer) eight single-unit wavefronts are 2-3 % faster.
     const int units = a.d / 32;
-    // Two units per wavefront halve the LDS reads per MFMA: 2 % faster on full tiles (prefill
-    // layer) for every format, and 4 % faster on small tiles (decode layer) for the bf16 pair,
-    // whose second plane makes this kernel compute-bound there too; the single-plane formats are
-    // 2-3 % faster with one unit on small tiles.
-    const bool two = (a.variant == 3 || (a.variant == 0 && (a.full_tiles || a.h_planes == 2))) && units >= 2;
-    if (a.h_planes == 3) {  // H and W2 as fp16
-        if (two) launch_down<4, 2, 1, 1>(st, a); else launch_down<8, 1, 1, 1>(st, a);
-        return;
-    }
-    if (a.h_planes == 4) {  // bf16 value + e5m2 remainder: one unit per wavefront unless asked otherwise
-        if (a.variant == 3 && units >= 2) launch_down<4, 2, 1, 0, 1>(st, a); else launch_down<8, 1, 1, 0, 1>(st, a);
-    } else if (a.h_planes == 2) {
-        if (two) launch_down<4, 2, 2>(st, a); else launch_down<8, 1, 2>(st, a);
-    } else {
-        if (two) launch_down<4, 2, 1>(st, a); else launch_down<8, 1, 1>(st, a);
-    }
+    const bool two = (a.variant == 3 || (a.variant == 0 && (a.full_tiles || a.h_mode == 1))) && units >= 2;
+    if (two) launch_down<4, 2>(st, a); else launch_down<8, 1>(st, a);
 }
 
 }  // namespace kmoe

@@ -19,7 +19,7 @@ constexpr int kThreads = 256;
 
 // ---- offline packing of expert weights ----------------------------------------------------
 // W13p: [unit = f/16][ks = d/16][lane 64] x 16 B   rows 0..15 = W1, rows 16..31 = W3 of the unit
-// W2p : [unit = d/32][ks = f/16][lane 64] x 16 B   rows = 32 output columns
+// W2p : [unit = d/32][ks = f/16][lane 64] x 16 B   rows = 32 output columns, values as fp16 (pack_down_f16_kernel)
 __global__ __launch_bounds__(kThreads) void pack_up_kernel(const uint16_t* __restrict__ w1,
                                                            const uint16_t* __restrict__ w3, int d,
                                                            int f, uint4* __restrict__ out) {
@@ -35,25 +35,6 @@ __global__ __launch_bounds__(kThreads) void pack_up_kernel(const uint16_t* __res
         const uint16_t* src = (r < 16 ? w1 + (size_t)(unit * 16 + r) * d
                                       : w3 + (size_t)(unit * 16 + r - 16) * d) + ks * 16 + hi * 8;
         out[u] = *reinterpret_cast<const uint4*>(src);
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void pack_down_kernel(const uint16_t* __restrict__ w2, int d,
-                                                             int f, uint4* __restrict__ out) {
-    const size_t units = (size_t)f * d / 8;
-    const int nks = f / 16;
-    for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
-         u += (size_t)gridDim.x * kThreads) {
-        const int lane = (int)(u & 63);
-        const size_t q = u >> 6;
-        const int ks = (int)(q % nks);
-        const int unit = (int)(q / nks);
-        const int col = unit * 32 + (lane & 31);  // output feature (row of W2)
-        const int hi = lane >> 5;
-        const uint16_t* src = w2 + (size_t)col * f + ks * 16 + 4 * hi;
-        const uint2 lo = *reinterpret_cast<const uint2*>(src);      // f = 16ks + 4hi + 0..3
-        const uint2 up = *reinterpret_cast<const uint2*>(src + 8);  // f = 16ks + 8 + 4hi + 0..3
-        out[u] = make_uint4(lo.x, lo.y, up.x, up.y);
     }
 }
 
@@ -136,16 +117,58 @@ __global__ __launch_bounds__(kThreads) void pack_sz_q4_kernel(const uint16_t* __
     }
 }
 
-// W2 for the fp16 form of the down projection: every bf16 weight converted to fp16 (nearest
-// even).  Exact for |w| in [2^-14, 65504]; smaller weights land on fp16 subnormals (absolute
-// error at most 2^-25); weights beyond the fp16 range are counted in *overflow and make the
-// placement fail.
+// Range and row energy of W2 [d, f] (bf16), for its placement as fp16: out[0] = bits of the
+// largest |w| (NaN and infinity order above every finite value), out[1] = bits of the largest
+// sum of squares over a row (one output column of the down projection).  One workgroup per row,
+// integer maxima, so the result does not depend on the order.  out is zeroed by the caller.
+__global__ __launch_bounds__(kThreads) void w2_stats_kernel(const uint16_t* __restrict__ w2, int d, int f,
+                                                            uint32_t* __restrict__ out) {
+    __shared__ float ssum[kThreads / 64];
+    __shared__ uint32_t smax[kThreads / 64];
+    for (int row = blockIdx.x; row < d; row += gridDim.x) {
+        const uint16_t* src = w2 + (size_t)row * f;
+        float sum = 0.f;
+        uint32_t amax = 0;
+        for (int i = threadIdx.x; i < f; i += kThreads) {
+            const uint32_t bits = (uint32_t)src[i] << 16;
+            const float w = __uint_as_float(bits);
+            amax = max(amax, bits & 0x7fffffffu);
+            sum = __builtin_fmaf(w, w, sum);
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            sum += __shfl_xor(sum, m, 64);
+            amax = max(amax, (uint32_t)__shfl_xor((int)amax, m, 64));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            ssum[threadIdx.x >> 6] = sum;
+            smax[threadIdx.x >> 6] = amax;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            uint32_t m = 0;
+            for (int w = 0; w < kThreads / 64; ++w) {
+                t += ssum[w];
+                m = max(m, smax[w]);
+            }
+            atomicMax(out, m);
+            atomicMax(out + 1, __float_as_uint(t));  // t >= 0 (or NaN, which orders above): bits order as values
+        }
+        __syncthreads();
+    }
+}
+
+// W2 for the down projection, which runs on the fp16 MFMA: every bf16 weight times `scale` (a
+// power of two, 1 unless the expert holds weights beyond the fp16 range: exact) converted to
+// fp16 (nearest even).  Exact for scaled |w| in [2^-17, 65504] (a bf16 value has 8 significant
+// bits, an fp16 subnormal at least that many down to 2^-17); smaller weights round to a multiple
+// of 2^-24 (absolute error at most 2^-25 of the scaled value).
 __global__ __launch_bounds__(kThreads) void pack_down_f16_kernel(const uint16_t* __restrict__ w2, int d,
-                                                                 int f, uint4* __restrict__ out,
-                                                                 int32_t* __restrict__ overflow) {
+                                                                 int f, float scale,
+                                                                 uint4* __restrict__ out) {
     const size_t units = (size_t)f * d / 8;
     const int nks = f / 16;
-    int bad = 0;
     for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
          u += (size_t)gridDim.x * kThreads) {
         const int lane = (int)(u & 63);
@@ -162,8 +185,7 @@ __global__ __launch_bounds__(kThreads) void pack_down_f16_kernel(const uint16_t*
             uint32_t packed = 0;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const float w = __uint_as_float((uint32_t)pp[t] << 16);
-                if (fabsf(w) > 65504.f) ++bad;  // also catches NaN-free infinities; NaN compares false
+                const float w = __uint_as_float((uint32_t)pp[t] << 16) * scale;
                 const _Float16 hv = (_Float16)w;
                 packed |= (uint32_t)__builtin_bit_cast(uint16_t, hv) << (16 * t);
             }
@@ -171,7 +193,11 @@ __global__ __launch_bounds__(kThreads) void pack_down_f16_kernel(const uint16_t*
         }
         out[u] = make_uint4(v[0], v[1], v[2], v[3]);
     }
-    if (bad) atomicAdd(overflow, bad);
+}
+
+__global__ __launch_bounds__(kThreads) void zero_u64_kernel(unsigned long long* __restrict__ p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads)
+        p[i] = 0ull;
 }
 
 __global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict__ src, size_t units,
@@ -185,10 +211,15 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict_
 // Xp: [row block][ks = d/16][lane 64] x 16 B.  Routed blocks follow the padded per-expert row
 // space; the rows of shared experts (all tokens, natural order) follow them.
 __global__ __launch_bounds__(kThreads) void gather_kernel(const uint16_t* __restrict__ x, Shape s,
-                                                          PlanPtrs p, uint4* __restrict__ xp) {
+                                                          PlanPtrs p, uint4* __restrict__ xp,
+                                                          unsigned long long* __restrict__ herr) {
     const int nks = s.d / 16;
     const int routed_blks = p.meta[2];
     const int shared_blks = s.S > 0 ? (s.N + kRowBlk - 1) / kRowBlk : 0;
+    // the up kernel adds the remainder energy of every H row of this call to herr: start at zero
+    const size_t h_rows = ((size_t)routed_blks + (size_t)s.S * ((s.N + kRowBlk - 1) / kRowBlk)) * kRowBlk;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < h_rows; i += (size_t)gridDim.x * kThreads)
+        herr[i] = 0ull;
     const size_t units = (size_t)(routed_blks + shared_blks) * nks * 64;
     for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
          u += (size_t)gridDim.x * kThreads) {
@@ -279,17 +310,23 @@ inline int grid_for(size_t work_items, int cap = 4096) {
 }  // namespace
 
 void launch_pack_expert_bf16(hipStream_t st, const void* w1, const void* w3, const void* w2, int d,
-                             int f, void* blob, int32_t* w2_f16_overflow) {
+                             int f, void* blob, float w2_scale) {
     uint4* up = (uint4*)blob;
     uint4* down = up + (size_t)f * d * 2 / 8;
     hipLaunchKernelGGL(pack_up_kernel, dim3(grid_for((size_t)f * d / 4)), dim3(kThreads), 0, st,
                        (const uint16_t*)w1, (const uint16_t*)w3, d, f, up);
-    if (w2_f16_overflow)  // down section as fp16, for H carried as fp16
-        hipLaunchKernelGGL(pack_down_f16_kernel, dim3(grid_for((size_t)f * d / 8)), dim3(kThreads), 0,
-                           st, (const uint16_t*)w2, d, f, down, w2_f16_overflow);
-    else
-        hipLaunchKernelGGL(pack_down_kernel, dim3(grid_for((size_t)f * d / 8)), dim3(kThreads), 0, st,
-                           (const uint16_t*)w2, d, f, down);
+    hipLaunchKernelGGL(pack_down_f16_kernel, dim3(grid_for((size_t)f * d / 8)), dim3(kThreads), 0, st,
+                       (const uint16_t*)w2, d, f, w2_scale, down);
+}
+
+void launch_w2_stats(hipStream_t st, const void* w2, int d, int f, uint32_t* out2) {
+    hipLaunchKernelGGL(w2_stats_kernel, dim3(d < 2048 ? d : 2048), dim3(kThreads), 0, st, (const uint16_t*)w2,
+                       d, f, out2);
+}
+
+void launch_zero_u64(hipStream_t st, unsigned long long* p, size_t n) {
+    if (n == 0) return;
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(grid_for(n, 1024)), dim3(kThreads), 0, st, p, n);
 }
 
 void launch_pack_expert_q4(hipStream_t st, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
@@ -318,12 +355,12 @@ void launch_pack_expert_f32(hipStream_t st, const void* w1, const void* w3, cons
 }
 
 void launch_gather_bf16(hipStream_t st, const void* x, const Shape& s, const PlanPtrs& p,
-                        void* xp) {
+                        void* xp, unsigned long long* herr) {
     if (s.N <= 0) return;
     const size_t max_units =
         ((size_t)s.max_rowblks + (s.S > 0 ? (s.N + kRowBlk - 1) / kRowBlk : 0)) * (s.d / 16) * 64;
     hipLaunchKernelGGL(gather_kernel, dim3(grid_for(max_units, 2048)), dim3(kThreads), 0, st,
-                       (const uint16_t*)x, s, p, (uint4*)xp);
+                       (const uint16_t*)x, s, p, (uint4*)xp, herr);
 }
 
 void launch_combine(hipStream_t st, int out_dtype, const Shape& s, const PlanPtrs& p,

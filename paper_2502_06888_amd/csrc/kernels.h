@@ -63,37 +63,52 @@ void launch_plan(hipStream_t st, const Shape& s, const BatchOffsets& bo, const P
                  int max_tiles);
 
 // ---- bf16 path ----------------------------------------------------------------------------
-// Offline packing of one expert (W1,W3 [f,d]; W2 [d,f]) into the fragment-ordered blob.
-// w2_f16_overflow != null: the down section holds W2 as fp16; the counter (device, zeroed by the
-// caller) receives the number of weights beyond the fp16 range.
+// Offline packing of one expert (W1,W3 [f,d]; W2 [d,f]) into the fragment-ordered blob.  The
+// down section holds W2 * w2_scale as fp16 (w2_scale a power of two chosen from launch_w2_stats).
 void launch_pack_expert_bf16(hipStream_t st, const void* w1, const void* w3, const void* w2,
-                             int d, int f, void* blob, int32_t* w2_f16_overflow);
+                             int d, int f, void* blob, float w2_scale);
+// out2[0] = bits of max |w2|, out2[1] = bits of the largest row sum of squares; out2 zeroed by the caller.
+void launch_w2_stats(hipStream_t st, const void* w2, int d, int f, uint32_t* out2);
+void launch_zero_u64(hipStream_t st, unsigned long long* p, size_t n);
 // The same for a 4-bit group-quantised expert: codes [rows, cols/2] (even column in the low
 // nibble), scales and zero points [rows, cols/64] as bf16, for W1, W3 ([f, d]) and W2 ([d, f]).
 void launch_pack_expert_q4(hipStream_t st, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
                            const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
                            const uint16_t* s2, const uint16_t* z2, int d, int f, void* blob);
 // Gather token rows per expert (and the plain rows for shared experts) into fragment order.
+// Also zeroes herr (remainder energy per H row of this call).
 void launch_gather_bf16(hipStream_t st, const void* x, const Shape& s, const PlanPtrs& p,
-                        void* xp);
+                        void* xp, unsigned long long* herr);
+
+constexpr int kMaxLaunchGroup = 8;  // streamed experts whose tiles one launch may cover
 
 struct FfnArgs {
     const uint8_t* const* wtab;  // device table: blob of expert id e (may hold nulls for streamed)
     const uint8_t* w_single;     // non-null: use this blob for every tile of the launch
+    const uint8_t* w_group[kMaxLaunchGroup];  // n_group > 0: blobs (window slots) of the experts group_expert[i];
+    int32_t group_expert[kMaxLaunchGroup];    // any other expert of the launch is looked up in wtab
+    int32_t n_group;
     const void* act;             // packed activations (Xp for up, Hp for down)
     void* out;                   // Hp (up) or O partials (down)
     const int32_t* tile_expert;
     const int32_t* tile_xblk;
     const int32_t* tile_hblk;
     const int32_t* tile_nblk;
-    const int32_t* tile_first;   // device: index of the first tile of this launch (null = 0)
-    const int32_t* tile_count;   // device: number of tiles of this launch
+    const int32_t* tile_first;   // device: index of the first tile of this launch (null = tile_first_v)
+    const int32_t* tile_count;   // device: number of tiles of this launch (null = tile_count_v)
+    int32_t tile_first_v, tile_count_v;  // the same by value, from the host's mirror of the tile tables
     int32_t max_tiles;           // tiles the grid was sized for
     int32_t est_tiles;           // tiles the host expects to be live (launch-shape heuristic)
     int32_t d, f;
-    int32_t h_planes;            // 1: H as bf16; 2: H as a bf16 pair (value + rounding remainder); 3: H (and W2) as fp16;
-                                 // 4: H as bf16 value + e5m2 remainder (f a multiple of 64)
+    int32_t h_mode;              // format of H between the projections.  0: fp16 value plane + fp16 remainder
+                                 // plane, the remainder multiplied only by tiles whose recorded remainder
+                                 // energy asks for it; 1: the same, remainder always multiplied;
+                                 // 2: bf16 value + bf16 remainder, both always (4-bit experts)
     int64_t h_plane_units;       // 16-byte units between the value plane and the remainder plane of H
+    unsigned long long* herr;    // per H row: remainder energy in units of threshold / 2^20 (h_mode 0)
+    const float2* wmeta;         // per expert of the layer: (output scale of the down projection, 1 / threshold)
+    int32_t* sat_count;          // device counters: [0] H values clamped to the fp16 range, [1] down-projection
+                                 // workgroups that multiplied the remainder plane on their own finding (h_mode 0)
     int32_t variant;             // kernel shape (waves per workgroup x units per wave); 0 = default
     int32_t panel;               // full tiles: 1 + log2 of the tiles per panel of the workgroup order (0 = default)
     int32_t full_tiles;          // host estimate: most tiles are full (more than 160 rows per expert)

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -25,8 +26,10 @@ using namespace kmoe;
 
 namespace {
 constexpr int kTileRows = kRowBlk * kTileBlks;
-// experts smaller than this (bytes) are copied over two alternating streams
+// experts smaller than this (bytes) are copied over two alternating streams (four were measured slower)
 constexpr int64_t kSecondCopyStreamBelow = 64ll << 20;
+// consecutive small experts share a pair of launches while their blobs stay below this
+constexpr int64_t kGroupBytes = 24ll << 20;
 
 
 thread_local std::string g_last_error;
@@ -38,9 +41,9 @@ struct Layout {
     // byte offsets into the workspace
     int64_t topk_idx, topk_w, counts, offsets, poff, nbatch, exec_order, meta, perm, inv_perm,
         blk_counts, blk_base, blk_mask, tile_expert, tile_xblk, tile_hblk, tile_nblk, exp_tile0,
-        exp_ntiles, blk_expert, mail, wtab, xp, h, o;
+        exp_ntiles, blk_expert, mail, wtab, wmeta, herr, xp, h, o;
     int64_t o_split_stride = 0;  // elements
-    int64_t h_plane_units = 0;   // 16-byte units between the two bf16 planes of H
+    int64_t h_plane_units = 0;   // 16-byte units between the value plane and the remainder plane of H
     int64_t corr_table = 0;      // int32 [n_layers][E][E]
     int64_t prev_idx = 0;        // top-k ids of the previously routed layer
     int64_t total = 0;
@@ -113,11 +116,13 @@ void compute_layout(const moe_config& c, Layout& L) {
     L.blk_expert = take(L.max_rowblks * 4);
     L.mail = take((2 * E + 1) * 4);
     L.wtab = take((int64_t)c.n_layers * (E + S) * 8);
+    L.wmeta = take((int64_t)c.n_layers * (E + S) * 8);
     const int64_t h_rows = L.h_rows16 * kRowBlk;
+    L.herr = take(h_rows * 8);
     if (c.dtype == MOE_BF16) {
         L.xp = take(L.x_rows16 * kRowBlk * d * 2);
         L.h_plane_units = h_rows * f * 2 / 16;
-        L.h = take(2 * h_rows * f * 2);  // H as a bf16 pair: value plane + remainder plane
+        L.h = take(2 * h_rows * f * 2);  // H: value plane + remainder plane, 2 bytes per element each
     } else {
         L.xp = off;
         L.h = take(h_rows * f * 4);
@@ -140,6 +145,7 @@ struct Slot {
     hipEvent_t done = nullptr;   // last reader finished (recorded on the compute stream)
     bool done_pending = false;
     bool ready_recorded = false;  // a copy into this slot has been issued at some time
+    uint64_t released_at = 0;     // order in which slots were released (0 = never used)
 };
 
 struct LayerState {
@@ -147,7 +153,6 @@ struct LayerState {
     std::vector<const uint8_t*> resident;  // E+S device blobs (null if not resident)
     std::vector<const uint8_t*> host;      // E pinned host blobs (null if resident)
     std::vector<int> slot_of;              // E: window slot holding the expert, or -1
-    std::vector<char> w2_f16;              // E+S: the expert's down section holds W2 as fp16
 };
 
 struct HostTile {
@@ -160,8 +165,9 @@ struct moe_ctx {
     moe_config cfg{};
     Layout L;
     hipStream_t compute = nullptr, copy = nullptr;
-    hipStream_t copy2 = nullptr;  // library-owned second copy stream (small experts only)
+    std::vector<hipStream_t> copy_extra;  // library-owned additional copy streams (small experts only)
     uint64_t copies_issued = 0;
+    uint64_t release_clock = 0;
     uint8_t* ws = nullptr;
     uint8_t* window = nullptr;
     PlanPtrs plan{};
@@ -181,8 +187,18 @@ struct moe_ctx {
     std::vector<HostTile> h_tiles;  // per expert id (E+S)
     int split_k_user = 0;
     int variant = 0;   // kernel shape selector of the bf16 FFN (0 = default)
-    int h_planes = 2;  // bf16 path, format of H between the projections: 1 plain bf16, 2 bf16 pair (default),
-                       // 3 fp16, 4 bf16 + e5m2 remainder
+    int h_mode = 0;    // bf16 experts: 0 = the remainder plane of H is multiplied where its recorded energy
+                       // asks for it (default), 1 = always
+    float2* wmeta_dev = nullptr;         // [n_layers][E+S]: (down-projection output scale, 1 / remainder threshold)
+    // timed spans of the pipeline, recorded while profiling is on (moe_get_stats harvests them)
+    struct Span {
+        hipEvent_t a, b;
+        int kind;  // 0: host->device copy, 1: kernels on the compute stream
+        bool closed;
+    };
+    std::vector<Span> spans;
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used = 0;
     // correlation-aware prefetcher
     bool corr_on = false;      // predictions allowed
     bool corr_learn = false;   // moe_route adds transitions to the table
@@ -197,9 +213,40 @@ struct moe_ctx {
 
 namespace {
 
-// The 8-bit remainder format of H (h_planes 4) exists in the kernels for bf16 weights only (d_ff
-// is a multiple of 64, one group of the 8-bit MFMA, in every bf16 configuration).
-bool r8_applies(const moe_config& c) { return c.dtype == MOE_BF16 && c.weight_bits != 4; }
+// Remainder plane of H: when is one fp16 plane enough?  The down projection of an expert turns the
+// rounding remainders r_i = h_i - fp16(h_i) of a token row into an output error sum_i r_i * W2[n,i].
+// Rounding remainders are as good as independent of the weights, so that error has variance
+// sum_i r_i^2 W2[n,i]^2 ~ (sum_i r_i^2) * (sum_i W2[n,i]^2) / f.  A token's output adds at most one
+// such term with total weight 1 for the routed experts (the routing weights sum to at most 1) and
+// one per shared expert.  The remainder plane is skipped for a tile while, for each of its rows,
+// kSigmas standard deviations of that sum stay below kErrBudget (0.8 of the 1e-2 absolute
+// tolerance the layer is held to; the rest covers the final rounding and fp32 reassociation):
+//     energy(row) = sum_i r_i^2  <=  tau = kErrBudget^2 * f / (kSigmas^2 * (1 + S) * R),
+// R = the largest sum of squares over a row of W2, taken at placement.
+constexpr double kErrBudget = 8e-3, kSigmas = 6.0;
+
+// Timing event from the context's pool (created on first use, reused after moe_reset_stats).
+hipEvent_t pool_event(moe_ctx* c) {
+    if (c->ev_used == c->ev_pool.size()) {
+        hipEvent_t ev = nullptr;
+        if (hipEventCreate(&ev) != hipSuccess) return nullptr;
+        c->ev_pool.push_back(ev);
+    }
+    return c->ev_pool[c->ev_used++];
+}
+
+// Opens a timed span on `st` while profiling is on; returns its index or -1.
+int span_open(moe_ctx* c, hipStream_t st, int kind) {
+    if (!c->profiling || c->spans.size() >= (1u << 16)) return -1;
+    hipEvent_t a = pool_event(c), b = pool_event(c);
+    if (!a || !b) return -1;
+    if (hipEventRecord(a, st) != hipSuccess) return -1;
+    c->spans.push_back({a, b, kind, false});
+    return (int)c->spans.size() - 1;
+}
+void span_close(moe_ctx* c, hipStream_t st, int idx) {
+    if (idx >= 0 && hipEventRecord(c->spans[idx].b, st) == hipSuccess) c->spans[idx].closed = true;
+}
 
 moe_status fail(const moe_ctx* ctx, moe_status s, const char* fmt, ...) {
     char buf[512];
@@ -310,6 +357,7 @@ void release_slot(moe_ctx* ctx, Slot& s, bool record_done) {
     s.expert = -1;
     s.state = SLOT_FREE;
     s.prefetched = false;
+    s.released_at = ++ctx->release_clock;
 }
 
 moe_status stream_one(moe_ctx* ctx, int layer, int e, bool prefetch) {
@@ -317,27 +365,35 @@ moe_status stream_one(moe_ctx* ctx, int layer, int e, bool prefetch) {
     if (ls.resident[e]) return MOE_OK;  // nothing to move
     if (!ls.host[e]) return fail(ctx, MOE_ERR_STATE, "layer %d expert %d has no weights", layer, e);
     if (ls.slot_of[e] >= 0) return MOE_OK;  // already in flight or loaded
+    // The free slot released longest ago: its readers are the furthest behind the head of the
+    // compute stream, so the copy stream's wait for them is the least likely to stall.  (Taking
+    // the first free slot by index drifts, over many passes, towards slots released a moment
+    // ago, whose readers still wait for copies that sit just ahead in the same copy stream.)
     int pick = -1;
     for (size_t i = 0; i < ctx->slots.size(); ++i)
-        if (ctx->slots[i].state == SLOT_FREE) {
+        if (ctx->slots[i].state == SLOT_FREE &&
+            (pick < 0 || ctx->slots[i].released_at < ctx->slots[pick].released_at))
             pick = (int)i;
-            break;
-        }
     if (pick < 0) return fail(ctx, MOE_ERR_OOM, "no free window slot for layer %d expert %d", layer, e);
     Slot& s = ctx->slots[pick];
     // Small experts alternate between two copy streams: the fixed start-up gap of one copy then
     // hides behind the other stream's transfer and the link stays busy.  Every slot still has
     // its own ready event, so nothing depends on the order in which the copies land.
     hipStream_t cs = ctx->copy;
-    if (ctx->copy2 && (ctx->copies_issued++ & 1)) cs = ctx->copy2;
+    if (!ctx->copy_extra.empty()) {
+        const size_t which = (size_t)(ctx->copies_issued++ % (ctx->copy_extra.size() + 1));
+        if (which > 0) cs = ctx->copy_extra[which - 1];
+    }
     if (s.done_pending) {  // the slot's previous readers must finish before it is overwritten
         HIP_TRY(ctx, hipStreamWaitEvent(cs, s.done, 0));
         s.done_pending = false;
     }
     // ... and so must its previous copy, which may have gone over the other copy stream (a
     // dropped prefetch guess frees a slot without any reader)
-    if (ctx->copy2 && s.ready_recorded) HIP_TRY(ctx, hipStreamWaitEvent(cs, s.ready, 0));
+    if (!ctx->copy_extra.empty() && s.ready_recorded) HIP_TRY(ctx, hipStreamWaitEvent(cs, s.ready, 0));
+    const int span = span_open(ctx, cs, 0);
     HIP_TRY(ctx, hipMemcpyAsync(s.ptr, ls.host[e], (size_t)ctx->L.expert_bytes, hipMemcpyHostToDevice, cs));
+    span_close(ctx, cs, span);
     HIP_TRY(ctx, hipEventRecord(s.ready, cs));
     s.ready_recorded = true;
     s.layer = layer;
@@ -477,13 +533,13 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
     p.blk_expert = (int32_t*)(w + L.blk_expert);
     p.mail = (int32_t*)(w + L.mail);
     c->wtab_dev = (const uint8_t**)(w + L.wtab);
+    c->wmeta_dev = (float2*)(w + L.wmeta);
     const int E = cfg->n_experts, S = cfg->n_shared;
     c->layers.resize(cfg->n_layers);
     for (auto& ls : c->layers) {
         ls.resident.assign(E + S, nullptr);
         ls.host.assign(E, nullptr);
         ls.slot_of.assign(E, -1);
-        ls.w2_f16.assign(E + S, 0);
     }
     auto cleanup = [&](moe_status s, const char* what, hipError_t e) {
         moe_status r = fail(nullptr, s, "%s failed: %s", what, hipGetErrorString(e));
@@ -494,6 +550,10 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
     e = hipMemsetAsync(w + L.wtab, 0, (size_t)cfg->n_layers * (E + S) * 8, c->compute);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
     e = hipMemsetAsync(w + L.meta, 0, 64, c->compute);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
+    e = hipMemsetAsync(w + L.wmeta, 0, (size_t)cfg->n_layers * (E + S) * 8, c->compute);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
+    e = hipMemsetAsync(w + L.herr, 0, (size_t)L.h_rows16 * kRowBlk * 8, c->compute);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
     e = hipMemsetAsync(w + L.corr_table, 0, (size_t)cfg->n_layers * E * E * 4, c->compute);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipMemsetAsync", e);
@@ -511,8 +571,13 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
         if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipEventCreate", e);
     }
     if (n_slots > 0 && L.expert_bytes < kSecondCopyStreamBelow) {
-        e = hipStreamCreateWithFlags(&c->copy2, hipStreamNonBlocking);  // default priority
-        if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipStreamCreateWithFlags", e);
+        const int extra = 1;
+        for (int i = 0; i < extra; ++i) {
+            hipStream_t cs = nullptr;
+            e = hipStreamCreateWithFlags(&cs, hipStreamNonBlocking);  // default priority
+            if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipStreamCreateWithFlags", e);
+            c->copy_extra.push_back(cs);
+        }
     }
     c->slots.resize(n_slots);
     for (int i = 0; i < n_slots; ++i) {
@@ -535,9 +600,9 @@ moe_status moe_destroy(moe_ctx* ctx) {
     if (!ctx) return MOE_OK;
     if (ctx->compute || true) (void)hipStreamSynchronize(ctx->compute);
     if (ctx->copy != ctx->compute) (void)hipStreamSynchronize(ctx->copy);
-    if (ctx->copy2) {
-        (void)hipStreamSynchronize(ctx->copy2);
-        (void)hipStreamDestroy(ctx->copy2);
+    for (hipStream_t cs : ctx->copy_extra) {
+        (void)hipStreamSynchronize(cs);
+        (void)hipStreamDestroy(cs);
     }
     for (Slot& s : ctx->slots) {
         if (s.ready) (void)hipEventDestroy(s.ready);
@@ -546,6 +611,7 @@ moe_status moe_destroy(moe_ctx* ctx) {
     if (ctx->route_ev) (void)hipEventDestroy(ctx->route_ev);
     for (auto& ev : ctx->pev)
         if (ev) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : ctx->ev_pool) (void)hipEventDestroy(ev);
     if (ctx->mailbox) (void)hipHostFree(ctx->mailbox);
     if (ctx->corr_host) (void)hipHostFree(ctx->corr_host);
     delete ctx;
@@ -584,7 +650,7 @@ moe_status place_expert(moe_ctx* ctx, int32_t layer, int32_t expert, int32_t whe
         for (const Slot& s : ctx->slots)
             if (s.state != SLOT_FREE) return fail(ctx, MOE_ERR_STATE, "placement while experts are in the window");
         HIP_TRY(ctx, hipStreamSynchronize(ctx->copy));
-        if (ctx->copy2) HIP_TRY(ctx, hipStreamSynchronize(ctx->copy2));
+        for (hipStream_t cs : ctx->copy_extra) HIP_TRY(ctx, hipStreamSynchronize(cs));
         pack_to = ctx->slots[0].ptr;  // staging: slot 0 is idle during the offline phase
     }
     HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
@@ -617,26 +683,40 @@ moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const voi
     if (!w1_dev || !w3_dev || !w2_dev) return fail(ctx, MOE_ERR_INVALID_ARG, "null weight pointer");
     if (ctx->cfg.weight_bits == 4) return fail(ctx, MOE_ERR_STATE, "this context holds 4-bit experts: use moe_set_expert_q4");
     const int d = ctx->cfg.d_model, f = ctx->cfg.d_ff;
-    const bool f16 = ctx->cfg.dtype == MOE_BF16 && ctx->h_planes == 3;
-    int32_t* overflow = (int32_t*)(ctx->ws + ctx->L.meta) + 8;  // spare word of the meta block
-    if (f16) HIP_TRY(ctx, hipMemsetAsync(overflow, 0, 4, ctx->compute));
+    const int E = ctx->cfg.n_experts, S = ctx->cfg.n_shared;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (expert < 0 || expert >= E + S) return fail(ctx, MOE_ERR_INVALID_ARG, "expert %d out of range", expert);
+    float2 meta = make_float2(1.f, 0.f);
+    float w2_scale = 1.f;
+    if (ctx->cfg.dtype == MOE_BF16) {
+        // range and row energy of W2: the power of two that brings it into the fp16 range, and the
+        // threshold below which the remainder plane of H need not be multiplied (see kErrBudget)
+        uint32_t* stats_dev = (uint32_t*)(ctx->ws + ctx->L.meta) + 8;  // two spare words of the meta block
+        uint32_t stats[2] = {0, 0};
+        HIP_TRY(ctx, hipMemsetAsync(stats_dev, 0, 8, ctx->compute));
+        launch_w2_stats(ctx->compute, w2_dev, d, f, stats_dev);
+        HIP_TRY(ctx, hipGetLastError());
+        HIP_TRY(ctx, hipMemcpyAsync(stats, stats_dev, 8, hipMemcpyDeviceToHost, ctx->compute));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+        if (stats[0] >= 0x7f800000u || stats[1] >= 0x7f800000u)
+            return fail(ctx, MOE_ERR_SHAPE, "W2 of layer %d expert %d holds non-finite weights (or its row energy overflows)", layer, expert);
+        float amax, rowsq;
+        memcpy(&amax, &stats[0], 4);
+        memcpy(&rowsq, &stats[1], 4);
+        int shift = 0;
+        while (std::ldexp((double)amax, -shift) > 65504.0) ++shift;
+        w2_scale = (float)std::ldexp(1.0, -shift);
+        const double inv_tau = kSigmas * kSigmas * (1.0 + S) * (double)rowsq / ((double)f * kErrBudget * kErrBudget);
+        meta = make_float2((float)std::ldexp(1.0, shift), (float)std::min(inv_tau, 3.0e38));
+    }
     moe_status st = place_expert(ctx, layer, expert, where, packed_dst, [&](void* to) {
         if (ctx->cfg.dtype == MOE_BF16)
-            launch_pack_expert_bf16(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, to, f16 ? overflow : nullptr);
+            launch_pack_expert_bf16(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, to, w2_scale);
         else
             launch_pack_expert_f32(ctx->compute, w1_dev, w3_dev, w2_dev, d, f, to);
     });
     if (st != MOE_OK) return st;
-    ctx->layers[layer].w2_f16[expert] = f16 ? 1 : 0;
-    if (f16) {
-        int32_t n_bad = 0;
-        HIP_TRY(ctx, hipMemcpy(&n_bad, overflow, 4, hipMemcpyDeviceToHost));
-        if (n_bad > 0) {
-            ctx->layers[layer].resident[expert] = nullptr;  // the blob is not usable
-            if (expert < ctx->cfg.n_experts) ctx->layers[layer].host[expert] = nullptr;
-            return fail(ctx, MOE_ERR_SHAPE, "W2 of layer %d expert %d has %d weights beyond the fp16 range: place it with h_planes 1 or 2", layer, expert, n_bad);
-        }
-    }
+    HIP_TRY(ctx, hipMemcpy((void*)(ctx->wmeta_dev + (size_t)layer * (E + S) + expert), &meta, 8, hipMemcpyHostToDevice));
     return MOE_OK;
 }
 
@@ -687,11 +767,13 @@ moe_status moe_route(moe_ctx* ctx, int32_t layer, const void* x_dev,
     const Shape s = make_shape(ctx, N);
     hipStream_t st = ctx->compute;
     const bool prof = ctx->profiling;
+    const int span = span_open(ctx, st, 1);
     if (prof) (void)hipEventRecord(ctx->pev[0], st);
     launch_router(st, ctx->cfg.dtype, x_dev, ls.wg, s, logits_dev, ctx->plan.topk_idx, ctx->plan.topk_w);
     if (prof) (void)hipEventRecord(ctx->pev[1], st);
     launch_plan(st, s, bo, ctx->plan, ctx->L.max_tiles);
     if (prof) (void)hipEventRecord(ctx->pev[2], st);
+    span_close(ctx, st, span);
     ctx->prof_route = prof;
     HIP_TRY(ctx, hipGetLastError());
     const size_t A = (size_t)N * k;
@@ -786,10 +868,6 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
             if (e >= E || !ls.host[e]) return fail(ctx, MOE_ERR_STATE, "weights of layer %d expert %d not set", layer, e);
         }
     }
-    if (ctx->cfg.dtype == MOE_BF16 && ctx->cfg.weight_bits != 4)
-        for (int e = 0; e < E + S; ++e)
-            if ((ls.w2_f16[e] != 0) != (ctx->h_planes == 3))
-                return fail(ctx, MOE_ERR_STATE, "layer %d expert %d was placed for %s H, the context is set to h_planes %d", layer, e, ls.w2_f16[e] ? "fp16" : "bf16", ctx->h_planes);
     const Shape s = make_shape(ctx, N);
     const PlanPtrs& p = ctx->plan;
     hipStream_t st = ctx->compute;
@@ -811,14 +889,18 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
     a.variant = ctx->variant % 10;
     a.panel = ctx->variant / 10;
     a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
-    a.h_planes = ctx->h_planes;
+    a.h_mode = ctx->cfg.weight_bits == 4 ? 2 : ctx->h_mode;
     a.h_plane_units = ctx->L.h_plane_units;
+    a.herr = (unsigned long long*)(w + ctx->L.herr);
+    a.wmeta = ctx->wmeta_dev + (size_t)layer * (E + S);
+    a.sat_count = (int32_t*)(w + ctx->L.meta) + 10;
     a.weight_bits = ctx->cfg.weight_bits;
 
     const bool prof = ctx->profiling && all_resident_layer(ctx, layer);
     ctx->prof_fwd = false;
     if (prof) (void)hipEventRecord(ctx->pev[3], st);
-    if (bf16) launch_gather_bf16(st, x_dev, s, p, w + ctx->L.xp);
+    int span = span_open(ctx, st, 1);
+    if (bf16) launch_gather_bf16(st, x_dev, s, p, w + ctx->L.xp, a.herr);
     if (prof) (void)hipEventRecord(ctx->pev[4], st);
 
     if (all_resident) {
@@ -847,6 +929,8 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
         }
         if (prof) (void)hipEventRecord(ctx->pev[6], st);
     } else {
+        span_close(ctx, st, span);  // the gather; every expert and the combine get spans of their own
+        span = -1;
         moe_status rs = wait_route(ctx);
         if (rs != MOE_OK) return rs;
         // experts of this layer in the window that the gate did not select are dropped
@@ -869,52 +953,107 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
         }
         // device-side tile ranges are addressed through exp_tile0 / exp_ntiles
         auto run_expert = [&](int e, const uint8_t* blob) {
+            const int sp = span_open(ctx, st, 1);
             if (bf16) {
                 a.w_single = blob;
                 a.tile_first = p.exp_tile0 + e;
                 a.tile_count = p.exp_ntiles + e;
                 a.max_tiles = ctx->h_tiles[e].count;
                 a.est_tiles = a.max_tiles;
-                if (a.max_tiles == 0) return;
-                a.act = w + ctx->L.xp;
-                a.out = w + ctx->L.h;
-                a.split_k = 1;
-                launch_ffn_up_bf16(st, a);
-                a.act = w + ctx->L.h;
-                a.out = o;
-                a.split_k = split;
-                launch_ffn_down_bf16(st, a);
+                if (a.max_tiles > 0) {
+                    a.act = w + ctx->L.xp;
+                    a.out = w + ctx->L.h;
+                    a.split_k = 1;
+                    launch_ffn_up_bf16(st, a);
+                    a.act = w + ctx->L.h;
+                    a.out = o;
+                    a.split_k = split;
+                    launch_ffn_down_bf16(st, a);
+                }
             } else {
                 launch_ffn_f32(st, (const float*)x_dev, s, p, wtab, blob, e, (float*)(w + ctx->L.h), o);
             }
+            span_close(ctx, st, sp);
         };
         for (int sh = 0; sh < S; ++sh) run_expert(E + sh, ls.resident[E + sh]);
         // experts whose weights were on the device before the gate ran (resident or prefetched)
         // go first, then the rest in execution order, which is also their copy order
-        std::vector<char> early(ctx->h_nactive, 0);
-        for (int i = 0; i < ctx->h_nactive; ++i) {
-            const int e = ctx->h_order[i];
-            early[i] = ls.resident[e] != nullptr ||
-                       (ls.slot_of[e] >= 0 && ctx->slots[ls.slot_of[e]].prefetched);
-        }
-        for (int pass = 0; pass < 2; ++pass) {
+        std::vector<int> seq;  // positions in the execution order, in launch order
+        for (int pass = 0; pass < 2; ++pass)
             for (int i = 0; i < ctx->h_nactive; ++i) {
-                if ((pass == 0) != (early[i] != 0)) continue;
                 const int e = ctx->h_order[i];
-                if (ls.resident[e]) {
-                    run_expert(e, ls.resident[e]);
-                } else {
+                const bool early = ls.resident[e] != nullptr ||
+                                   (ls.slot_of[e] >= 0 && ctx->slots[ls.slot_of[e]].prefetched);
+                if ((pass == 0) == early) seq.push_back(i);
+            }
+        // Small experts are computed in groups.  A pair of launches per expert costs about as much
+        // as moving a 5 MB expert over the link, so the compute stream, not the link, would set
+        // the pace.  Experts that follow each other both in the launch sequence and in execution
+        // order own one contiguous range of tiles: they share one pair of launches, issued once
+        // the last of them has landed, while the group's blobs stay below kGroupBytes.
+        size_t at = 0;
+        while (at < seq.size()) {
+            size_t end = at + 1;
+            if (bf16) {
+                int64_t bytes = ctx->L.expert_bytes;
+                while (end < seq.size() && end - at < (size_t)kMaxLaunchGroup && seq[end] == seq[end - 1] + 1 &&
+                       bytes + ctx->L.expert_bytes <= kGroupBytes) {
+                    ++end;
+                    bytes += ctx->L.expert_bytes;
+                }
+            }
+            const int sp = end - at > 1 ? span_open(ctx, st, 1) : -1;
+            int tiles = 0;
+            for (size_t j = at; j < end; ++j) {
+                const int e = ctx->h_order[seq[j]];
+                const uint8_t* blob = ls.resident[e];
+                if (!blob) {
                     if (ls.slot_of[e] < 0)
                         return fail(ctx, MOE_ERR_STATE, "layer %d expert %d is not in the window", layer, e);
                     Slot& sl = ctx->slots[ls.slot_of[e]];
                     HIP_TRY(ctx, hipStreamWaitEvent(st, sl.ready, 0));
-                    run_expert(e, sl.ptr);
-                    release_slot(ctx, sl, true);  // freed as soon as its last kernel is queued
+                    blob = sl.ptr;
+                }
+                if (end - at == 1) {
+                    run_expert(e, blob);
+                } else {
+                    a.w_group[j - at] = blob;
+                    a.group_expert[j - at] = e;
+                    tiles += ctx->h_tiles[e].count;
                 }
             }
+            if (end - at > 1) {
+                a.w_single = nullptr;
+                a.n_group = (int32_t)(end - at);
+                a.tile_first = nullptr;
+                a.tile_count = nullptr;
+                a.tile_first_v = ctx->h_tiles[ctx->h_order[seq[at]]].first;
+                a.tile_count_v = tiles;
+                a.max_tiles = tiles;
+                a.est_tiles = tiles;
+                if (tiles > 0) {
+                    a.act = w + ctx->L.xp;
+                    a.out = w + ctx->L.h;
+                    a.split_k = 1;
+                    launch_ffn_up_bf16(st, a);
+                    a.act = w + ctx->L.h;
+                    a.out = o;
+                    a.split_k = split;
+                    launch_ffn_down_bf16(st, a);
+                }
+                a.n_group = 0;
+                span_close(ctx, st, sp);
+            }
+            for (size_t j = at; j < end; ++j) {  // slots are freed as soon as their last kernel is queued
+                const int e = ctx->h_order[seq[j]];
+                if (!ls.resident[e]) release_slot(ctx, ctx->slots[ls.slot_of[e]], true);
+            }
+            at = end;
         }
     }
+    if (span < 0) span = span_open(ctx, st, 1);
     launch_combine(st, bf16 ? 1 : 0, s, p, o, bf16 ? split : 1, ctx->L.o_split_stride, y_dev);
+    span_close(ctx, st, span);
     if (prof) {
         (void)hipEventRecord(ctx->pev[7], st);
         ctx->prof_fwd = true;
@@ -923,14 +1062,71 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
     return MOE_OK;
 }
 
-moe_status moe_get_stats(const moe_ctx* ctx, moe_stats* out) {
+moe_status moe_get_stats(moe_ctx* ctx, moe_stats* out) {
     if (!ctx || !out) return fail(ctx, MOE_ERR_INVALID_ARG, "null argument");
+    // device counters since the last reset (stream-ordered read): H values clamped to the fp16 range,
+    // down-projection workgroups that multiplied the remainder plane
+    int32_t cnt[2] = {0, 0};
+    HIP_TRY(ctx, hipMemcpyAsync(cnt, (int32_t*)(ctx->ws + ctx->L.meta) + 10, 8, hipMemcpyDeviceToHost, ctx->compute));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+    ctx->stats.h_saturated = cnt[0];
+    ctx->stats.h_remainder_wgs = cnt[1];
+    // timed spans recorded while profiling was on: busy time of the link (union of the copy
+    // intervals: two copy streams may overlap), of the compute stream, and the wall time from the
+    // first start to the last end
+    ctx->stats.copy_busy_ns = ctx->stats.compute_busy_ns = ctx->stats.wall_ns = 0;
+    std::vector<std::pair<double, double>> copies;
+    double lo = 0.0, hi = 0.0, compute_ms = 0.0;
+    bool any = false;
+    hipEvent_t ref = nullptr;
+    for (const moe_ctx::Span& sp : ctx->spans) {
+        if (!sp.closed) continue;
+        HIP_TRY(ctx, hipEventSynchronize(sp.b));
+        if (!ref) ref = sp.a;
+        float t0 = 0.f, dt = 0.f;
+        if (hipEventElapsedTime(&t0, ref, sp.a) != hipSuccess || hipEventElapsedTime(&dt, sp.a, sp.b) != hipSuccess) {
+            (void)hipGetLastError();
+            continue;
+        }
+        const double a0 = t0, a1 = (double)t0 + dt;
+        lo = any ? std::min(lo, a0) : a0;
+        hi = any ? std::max(hi, a1) : a1;
+        any = true;
+        if (sp.kind == 0) copies.emplace_back(a0, a1); else compute_ms += dt;
+    }
+    std::sort(copies.begin(), copies.end());
+    double busy = 0.0, cur0 = 0.0, cur1 = 0.0;
+    bool open = false;
+    for (const auto& iv : copies) {
+        if (open && iv.first <= cur1) {
+            cur1 = std::max(cur1, iv.second);
+        } else {
+            if (open) busy += cur1 - cur0;
+            cur0 = iv.first;
+            cur1 = iv.second;
+            open = true;
+        }
+    }
+    if (open) busy += cur1 - cur0;
+    ctx->stats.copy_busy_ns = (int64_t)(busy * 1e6);
+    ctx->stats.compute_busy_ns = (int64_t)(compute_ms * 1e6);
+    ctx->stats.wall_ns = any ? (int64_t)((hi - lo) * 1e6) : 0;
     *out = ctx->stats;
     return MOE_OK;
 }
 
 moe_status moe_reset_stats(moe_ctx* ctx) {
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
+    // spans still in flight keep their events until the streams have passed them
+    if (!ctx->spans.empty()) {
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+        if (ctx->copy && ctx->copy != ctx->compute) HIP_TRY(ctx, hipStreamSynchronize(ctx->copy));
+        for (hipStream_t cs : ctx->copy_extra) HIP_TRY(ctx, hipStreamSynchronize(cs));
+    }
+    ctx->spans.clear();
+    ctx->ev_used = 0;
+    launch_zero_u64(ctx->compute, (unsigned long long*)((int32_t*)(ctx->ws + ctx->L.meta) + 10), 1);  // meta[10..11]
+    HIP_TRY(ctx, hipGetLastError());
     ctx->stats = moe_stats{};
     return MOE_OK;
 }
@@ -1049,10 +1245,15 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
         a.variant = ctx->variant % 10;
         a.panel = ctx->variant / 10;
         a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
-        a.h_planes = ctx->h_planes;
+        a.h_mode = ctx->cfg.weight_bits == 4 ? 2 : ctx->h_mode;
         a.h_plane_units = ctx->L.h_plane_units;
+        a.herr = (unsigned long long*)(w + ctx->L.herr);
+        a.wmeta = ctx->wmeta_dev + (size_t)layer * (E + S);
+        a.sat_count = (int32_t*)(w + ctx->L.meta) + 10;
         a.weight_bits = ctx->cfg.weight_bits;
+        const size_t herr_rows = (size_t)ctx->L.h_rows16 * kRowBlk;
         auto run_expert = [&](int e, const uint8_t* blob) {
+            launch_zero_u64(st, a.herr, herr_rows);  // repeated runs must not add up their remainder energies
             a.w_single = blob;
             a.tile_first = p.exp_tile0 + e;
             a.tile_count = p.exp_ntiles + e;
@@ -1069,7 +1270,7 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
             launch_ffn_down_bf16(st, a);
         };
         const int q0 = mark(st);
-        for (int i = 0; i < reps; ++i) launch_gather_bf16(st, x_dev, s, p, w + ctx->L.xp);
+        for (int i = 0; i < reps; ++i) launch_gather_bf16(st, x_dev, s, p, w + ctx->L.xp, a.herr);
         const int q1 = mark(st);
         for (int sh = 0; sh < S; ++sh) run_expert(E + sh, ls.resident[E + sh]);
         std::vector<int> e0(ctx->h_nactive), e1(ctx->h_nactive);
@@ -1305,13 +1506,9 @@ moe_status moe_set_tuning(moe_ctx* ctx, int32_t split_k, int32_t h_planes, int32
     if (variant < -1 || variant > 69) return fail(ctx, MOE_ERR_INVALID_ARG, "variant out of range");
     if (!ctx) return fail(nullptr, MOE_ERR_INVALID_ARG, "ctx is null");
     if (split_k < 0 || split_k > 64) return fail(ctx, MOE_ERR_INVALID_ARG, "split_k out of range");
-    if (h_planes < 0 || h_planes > 4) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0, 1, 2, 3 or 4");
-    if (h_planes == 4 && !r8_applies(ctx->cfg))
-        return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes 4 (bf16 H + 8-bit remainder) needs bf16 experts");
-    if (h_planes == 3 && (ctx->cfg.dtype != MOE_BF16 || ctx->cfg.weight_bits == 4))
-        return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes 3 (fp16 H) needs bf16 experts");
+    if (h_planes < 0 || h_planes > 2) return fail(ctx, MOE_ERR_INVALID_ARG, "h_planes must be 0 (keep), 1 (automatic) or 2 (always both planes)");
     ctx->split_k_user = split_k;
-    if (h_planes > 0) ctx->h_planes = h_planes;
+    if (h_planes > 0) ctx->h_mode = h_planes == 2 ? 1 : 0;
     if (variant != 0) ctx->variant = variant < 0 ? 0 : variant;
     return MOE_OK;
 }

@@ -76,20 +76,6 @@ def test_q4_small_shapes(w):
     assert rms > 0.05                                    # outputs are not hiding in the absolute term
 
 
-def test_q4_plain_bf16_h_option():
-    w = SMALL
-    data, _ = I.gen_layer(w, 0, with_experts=False)
-    experts = [I.gen_expert_q4(w, 0, e) for e in range(w.n_experts)]
-    ctx = make_ctx_q4(w)
-    place_q4(ctx, w, 0, data.wg, experts)
-    ctx.set_tuning(0, 1, 0)
-    got = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
-    want = oracle_q4(w, data, experts)
-    rtol, atol = H.TOL["bf16"]
-    assert np.all(np.abs(got["y"] - want.y) <= 2 * atol + rtol * np.abs(want.y))
-    ctx.close()
-
-
 def test_q4_full_size_decode_layer_sampled_tokens():
     w = I.WORKLOADS["mixtral8x7b_decode"]
     tokens = sorted(np.random.default_rng(7).choice(w.n_tokens, size=12, replace=False).tolist())
@@ -138,10 +124,6 @@ def test_q4_context_refuses_plain_weights_and_vice_versa():
     with pytest.raises(B.MoeError) as ei:
         ctx.set_expert(0, 0, data.w1[0].to(dev), data.w3[0].to(dev), data.w2[0].to(dev))
     assert ei.value.status == B.MOE_ERR_STATE
-    for h_planes in (3, 4):                          # H formats of the bf16-weight kernels only
-        with pytest.raises(B.MoeError) as ei:
-            ctx.set_tuning(0, h_planes, 0)
-        assert ei.value.status == B.MOE_ERR_INVALID_ARG
     ctx.close()
     ctx = H.make_ctx(w)
     q4 = tuple(tuple(t.to(dev) for t in trip) for trip in I.gen_expert_q4(w, 0, 0))
