@@ -388,3 +388,36 @@ void ko_quant_q4(const double *w, const uint16_t *s_bf16, const uint16_t *z_bf16
         }
 }
 
+/* ------------------------------------------------------------------------------------------
+ * Constraint-sensitive planner, stage "constraint solving" (paper Section 7, inequality group).
+ *
+ * n batches per batch group are enough when the compute of n batches covers the transfers that
+ * must have landed at four points of the pipeline (the arrows I-IV of the pipeline figure):
+ *   I    n * t_c_A                                   >= t_io_G
+ *   II   n * (t_c_A + t_c_G)                         >= t_io_G + K * t_io_E
+ *   III  n * (t_c_A + t_c_G) + t_c_hotE              >= t_io_G + (K + 1) * t_io_E
+ *   IV   n * (t_c_A + t_c_G) + t_c_hotE + sum_Q t_c_E >= t_io_G + (K + len(Q)) * t_io_E + t_io_A
+ * (K = prefetched hot experts, Q = queue of activated experts that are not hot).  The answer is
+ * the smallest positive integer n that satisfies the group.  Readings: the legend's t_c_topk-E is
+ * the formulas' t_c_hot-E; with an empty queue nothing cold is computed or moved, so III and IV
+ * do not apply (the paper's best case).
+ *
+ * Written as the search the text describes: n = 1, 2, 3, ... until all inequalities hold, each
+ * evaluated as printed.  Returns -1 when no n up to n_max does (e.g. no compute to hide I/O behind).
+ */
+int64_t ko_plan_batches(double t_c_A, double t_c_G, double t_c_hotE, const double *t_c_E, int len_q,
+                        double t_io_A, double t_io_G, double t_io_E, int K, int64_t n_max) {
+    double sum_q = 0.0;
+    for (int i = 0; i < len_q; ++i) sum_q += t_c_E[i];
+    for (int64_t n = 1; n <= n_max; ++n) {
+        const double dn = (double)n;
+        if (!(dn * t_c_A >= t_io_G)) continue;
+        if (!(dn * (t_c_A + t_c_G) >= t_io_G + K * t_io_E)) continue;
+        if (len_q > 0) {
+            if (!(dn * (t_c_A + t_c_G) + t_c_hotE >= t_io_G + (K + 1) * t_io_E)) continue;
+            if (!(dn * (t_c_A + t_c_G) + t_c_hotE + sum_q >= t_io_G + (K + len_q) * t_io_E + t_io_A)) continue;
+        }
+        return n;
+    }
+    return -1;
+}

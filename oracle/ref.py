@@ -262,3 +262,14 @@ def corr_predict(table: np.ndarray, counts_prev, K: int):
                           _p(score, C.c_double), _p(experts, C.c_int32), C.byref(n))
     return experts[:n.value].copy(), score
 
+
+def plan_batches(t_c_A, t_c_G, t_c_hotE, t_c_E, t_io_A, t_io_G, t_io_E, K: int,
+                 n_max: int = 10_000_000) -> int:
+    """Smallest n of the planner's inequality group by trying n = 1, 2, ...; -1 if none <= n_max."""
+    q = np.ascontiguousarray(np.asarray(list(t_c_E), dtype=np.float64))
+    fn = lib().ko_plan_batches
+    fn.restype = C.c_int64
+    fn.argtypes = [C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double), C.c_int, C.c_double,
+                   C.c_double, C.c_double, C.c_int, C.c_int64]
+    buf = q if q.size else np.zeros(1)
+    return int(fn(t_c_A, t_c_G, t_c_hotE, _p(buf, C.c_double), int(q.size), t_io_A, t_io_G, t_io_E, K, n_max))

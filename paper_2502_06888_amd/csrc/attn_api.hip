@@ -192,7 +192,7 @@ moe_status moe_attn_create(const moe_attn_config* cfg, void* workspace_dev, int6
     hipEvent_t* plain[] = {&c->entry, &c->finish, &c->loaded[0], &c->loaded[1], &c->done[0], &c->done[1], &c->stored[0], &c->stored[1]};
     for (hipEvent_t* e : plain) {
         if (hipEventCreate(e) != hipSuccess) {  // timing enabled: entry / finish bracket the wall time
-            delete c;
+            moe_attn_destroy(c);  // releases the events created so far
             return fail(nullptr, MOE_ERR_HIP, "hipEventCreate failed");
         }
     }

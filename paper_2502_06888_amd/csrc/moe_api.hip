@@ -451,28 +451,41 @@ moe_status moe_plan_batches(double t_c_A, double t_c_G, double t_c_hotE, const d
         if (!(t_c_E[i] >= 0.0)) return fail(nullptr, MOE_ERR_INVALID_ARG, "times must be >= 0");
         sum_q += t_c_E[i];
     }
-    // n * lhs_rate + lhs_const >= rhs, one row per arrow of the pipeline figure (I..IV)
+    // n * rate + hot + queue >= rhs, one row per arrow of the pipeline figure (I..IV)
     struct Row {
-        double rate, lhs_const, rhs;
+        double rate, hot, queue, rhs;
     };
     std::vector<Row> rows;
-    rows.push_back({t_c_A, 0.0, t_io_G});
-    rows.push_back({t_c_A + t_c_G, 0.0, t_io_G + K * t_io_E});
+    rows.push_back({t_c_A, 0.0, 0.0, t_io_G});
+    rows.push_back({t_c_A + t_c_G, 0.0, 0.0, t_io_G + K * t_io_E});
     if (len_q > 0) {  // with no cold expert queued the last two conditions do not apply
-        rows.push_back({t_c_A + t_c_G, t_c_hotE, t_io_G + (K + 1) * t_io_E});
-        rows.push_back({t_c_A + t_c_G, t_c_hotE + sum_q, t_io_G + (K + len_q) * t_io_E + t_io_A});
+        rows.push_back({t_c_A + t_c_G, t_c_hotE, 0.0, t_io_G + (K + 1) * t_io_E});
+        rows.push_back({t_c_A + t_c_G, t_c_hotE, sum_q, t_io_G + (K + len_q) * t_io_E + t_io_A});
     }
     long long n = 1;
-    for (const Row& r : rows) {
-        const double need = r.rhs - r.lhs_const;
+    for (const Row& r : rows) {  // first guess: the ceiling of each row's quotient
+        const double need = r.rhs - r.hot - r.queue;
         if (need <= 0.0) continue;
         if (!(r.rate > 0.0))
             return fail(nullptr, MOE_ERR_INVALID_ARG, "no compute time to overlap the I/O with");
         const double x = need / r.rate;
+        if (x >= 2.0e9) {
+            n = INT32_MAX;
+            continue;
+        }
         long long c = (long long)x;
         if ((double)c < x) ++c;
         n = std::max(n, c);
     }
+    // The quotients can be off by an ulp: settle on the smallest n that satisfies every
+    // inequality evaluated as printed.
+    auto holds = [&](long long m) {
+        for (const Row& r : rows)
+            if (!((double)m * r.rate + r.hot + r.queue >= r.rhs)) return false;
+        return true;
+    };
+    while (n > 1 && holds(n - 1)) --n;
+    while (n < INT32_MAX && !holds(n)) ++n;
     if (n > INT32_MAX) n = INT32_MAX;
     *n_out = (int32_t)n;
     return MOE_OK;
@@ -1169,11 +1182,20 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
             return fail(ctx, MOE_ERR_STATE, "weights of layer %d expert %d not set", layer, e);
     hipStream_t st = ctx->compute;
     std::vector<hipEvent_t> evs;
+    bool hip_failed = false;  // any HIP call of the measurement failed: the figures are void
+    auto check = [&](hipError_t e) {
+        if (e != hipSuccess) hip_failed = true;
+    };
+    // A timing event recorded on `on`; on failure the index of the first event is returned (so
+    // that later look-ups stay in bounds) and the measurement is reported as failed at the end.
     auto mark = [&](hipStream_t on) -> int {
         hipEvent_t ev = nullptr;
-        if (hipEventCreate(&ev) != hipSuccess) return -1;
-        (void)hipEventRecord(ev, on);
+        if (hipEventCreate(&ev) != hipSuccess) {
+            hip_failed = true;
+            return 0;
+        }
         evs.push_back(ev);
+        check(hipEventRecord(ev, on));
         return (int)evs.size() - 1;
     };
     auto done = [&](moe_status r) {
@@ -1182,7 +1204,11 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
     };
     auto secs = [&](int a, int b) {
         float ms = 0.f;
-        (void)hipEventElapsedTime(&ms, evs[a], evs[b]);
+        if (evs.empty() || a < 0 || b < 0 || (size_t)a >= evs.size() || (size_t)b >= evs.size()) {
+            hip_failed = true;
+            return 0.0;
+        }
+        check(hipEventElapsedTime(&ms, evs[a], evs[b]));
         return (double)ms * 1e-3;
     };
     const bool learn = ctx->corr_learn;  // repeated routing of one group must not feed the table
@@ -1214,17 +1240,17 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
         if (slot < 0) return done(fail(ctx, MOE_ERR_OOM, "no free window slot to measure a transfer"));
         Slot& sl = ctx->slots[slot];
         if (sl.done_pending) {
-            (void)hipStreamWaitEvent(ctx->copy, sl.done, 0);
+            check(hipStreamWaitEvent(ctx->copy, sl.done, 0));
             sl.done_pending = false;
         }
-        if (sl.ready_recorded) (void)hipStreamWaitEvent(ctx->copy, sl.ready, 0);
+        if (sl.ready_recorded) check(hipStreamWaitEvent(ctx->copy, sl.ready, 0));
         io0 = mark(ctx->copy);
         for (int i = 0; i < reps; ++i)
-            (void)hipMemcpyAsync(sl.ptr, ls.host[host_e], (size_t)ctx->L.expert_bytes, hipMemcpyHostToDevice, ctx->copy);
+            check(hipMemcpyAsync(sl.ptr, ls.host[host_e], (size_t)ctx->L.expert_bytes, hipMemcpyHostToDevice, ctx->copy));
         io1 = mark(ctx->copy);
-        (void)hipEventRecord(sl.ready, ctx->copy);
+        check(hipEventRecord(sl.ready, ctx->copy));
         sl.ready_recorded = true;
-        (void)hipStreamWaitEvent(st, sl.ready, 0);
+        check(hipStreamWaitEvent(st, sl.ready, 0));
         standin = sl.ptr;
     }
     if (N > 0) {
@@ -1295,7 +1321,8 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
     }
     out->t_c_gate_group_s = secs(g0, g1) / reps;
     if (io0 >= 0) out->t_io_expert_s = secs(io0, io1) / reps;
-    if (hipGetLastError() != hipSuccess) return done(fail(ctx, MOE_ERR_HIP, "a measurement launch failed"));
+    if (hipGetLastError() != hipSuccess || hip_failed)
+        return done(fail(ctx, MOE_ERR_HIP, "a HIP call of the measurement failed: the reported times are void"));
     return done(MOE_OK);
 }
 

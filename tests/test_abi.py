@@ -140,6 +140,33 @@ def test_plan_batches_closed_forms():
     assert ns == sorted(ns, reverse=True)
 
 
+def test_plan_batches_equals_the_oracle_search_on_a_seeded_sweep():
+    """The library solves the inequality group with one division per row and a fix-up; the oracle
+    tries n = 1, 2, 3, ... with the inequalities as printed.  Same n on drawn times, including
+    the measured magnitudes of the streamed stacks (microseconds of compute against milliseconds
+    of transfer) and cases built to sit exactly on a boundary."""
+    import numpy as np
+    from oracle import ref
+    g = np.random.Generator(np.random.PCG64(2024))
+    for trial in range(400):
+        scale = float(10.0 ** g.uniform(-6, 0))
+        tA, tG = float(g.uniform(0.0, 3.0)) * scale, float(g.uniform(0.0, 0.5)) * scale
+        if tA + tG == 0.0:
+            tA = scale
+        thot = float(g.uniform(0.0, 4.0)) * scale
+        q = [float(v) * scale for v in g.uniform(0.0, 2.0, size=int(g.integers(0, 9)))]
+        io = [float(v) * scale * float(10.0 ** g.uniform(0, 3)) for v in g.uniform(0, 5, size=3)]
+        K = int(g.integers(0, 7))
+        if tA == 0.0:
+            io[1] = 0.0                              # nothing but attention compute hides the gate transfer
+        want = ref.plan_batches(tA, tG, thot, q, io[0], io[1], io[2], K)
+        assert B.moe_plan_batches(tA, tG, thot, q, io[0], io[1], io[2], K) == want, trial
+    for n in (1, 2, 7, 64, 1000):                    # exact boundaries in dyadic arithmetic
+        assert B.moe_plan_batches(0.5, 0.25, 0.0, [], 0.0, 0.0, 0.75 * n, 1) == ref.plan_batches(0.5, 0.25, 0.0, [], 0.0, 0.0, 0.75 * n, 1) == n
+        assert B.moe_plan_batches(0.5, 0.25, 1.0, [2.0], 0.25, 0.0, (0.75 * n + 3.0 - 0.25) / 2, 1) == \
+            ref.plan_batches(0.5, 0.25, 1.0, [2.0], 0.25, 0.0, (0.75 * n + 3.0 - 0.25) / 2, 1)
+
+
 def test_plan_batches_errors():
     with pytest.raises(B.MoeError):
         B.moe_plan_batches(0.0, 0.0, 0.0, [], 0.0, 1.0, 0.0, 0)              # nothing to overlap with

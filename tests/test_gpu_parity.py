@@ -140,10 +140,11 @@ def mixtral_layer():
     ctx.close()
 
 
-def test_mixtral_decode_full_size_sampled_outputs(mixtral_layer):
+def test_mixtral_decode_full_size_every_output(mixtral_layer):
+    """The benchmark's headline layer in the benchmark's launch configuration: every one of the
+    512 x 4096 outputs against the oracle (a few seconds of CPU time), routing in full."""
     w, data, ctx = mixtral_layer
-    tokens = np.random.Generator(np.random.PCG64(5)).choice(w.n_tokens, 24, replace=False)
-    got, want, err = run_case(w, tokens=np.sort(tokens).astype(np.int32), data=data, ctx=ctx)
+    got, want, err = run_case(w, data=data, ctx=ctx)
     assert got["counts"].sum() == 1024 and (got["counts"] > 0).all()
 
 
@@ -237,15 +238,48 @@ def test_full_size_outputs_do_not_depend_on_token_order_or_batch_cut(mixtral_lay
     assert np.array_equal(recut["counts"], base["counts"]) and np.array_equal(recut["perm"], base["perm"])
 
 
-def test_mixtral_prefill_full_size_sampled_outputs(mixtral_layer):
+def stratified_tokens(got, n_experts, top_k, tile_rows=256, blk_rows=32):
+    """Tokens whose assignments cover every (expert, tile) of the dispatch plan at least once,
+    plus, for the first and the last tile of every expert, every row of the tile's first and
+    last row block (the ragged tail of the expert included)."""
+    idx, inv_perm, offsets = got["idx"].reshape(-1), got["inv_perm"], got["offsets"]
+    pos = inv_perm - offsets[idx]                       # row of the assignment inside its expert
+    tile = pos // tile_rows
+    picked = set()
+    for e in range(n_experts):
+        mine = np.nonzero(idx == e)[0]
+        if mine.size == 0:
+            continue
+        last_tile = int(tile[mine].max())
+        for t in range(last_tile + 1):                  # one row of every tile, at a varying height
+            rows = mine[tile[mine] == t]
+            picked.add(int(rows[(7 * t + 3 * e) % rows.size]) // top_k)
+        for t in {0, last_tile}:
+            rows = mine[tile[mine] == t]
+            r = pos[rows] - t * tile_rows
+            last_blk = int(r.max()) // blk_rows
+            for a in rows[(r < blk_rows) | (r // blk_rows == last_blk)]:
+                picked.add(int(a) // top_k)
+    return np.array(sorted(picked), dtype=np.int32)
+
+
+def test_mixtral_prefill_full_size_stratified_outputs(mixtral_layer):
+    """The prefill layer (16 tiles of 256 rows per expert) in the benchmark's launch configuration.
+    The compared tokens are drawn from the dispatch plan so that every (expert, tile) contributes a
+    row, and the first and last row block of every expert's first and last tile contribute all of
+    theirs: several hundred tokens, each checked on all 4096 outputs."""
     wd, data, ctx = mixtral_layer
     w = I.WORKLOADS["mixtral8x7b_prefill"]
     x = I.gen_x_gaussian(w)
     d2 = I.LayerData(x=x, wg=data.wg, w1=data.w1, w3=data.w3, w2=data.w2)
-    tokens = np.random.Generator(np.random.PCG64(6)).choice(w.n_tokens, 12, replace=False)
-    tokens = np.sort(tokens).astype(np.int32)
-    got, want, err = run_case(w, tokens=tokens, data=d2, ctx=ctx)
+    got = H.gpu_layer(ctx, w, 0, x, w.batch_offsets)
     assert got["counts"].sum() == 32768
+    tokens = stratified_tokens(got, w.n_experts, w.top_k)
+    n_tiles = int(sum((c + 255) // 256 for c in got["counts"]))
+    assert tokens.size >= n_tiles >= 128
+    want = H.oracle_layer(w, d2, w.batch_offsets, tokens=tokens)
+    H.check_routing(got, want, w.n_experts)
+    H.check_output(got["y"], want.y, w.dtype, tokens)
     try:                                             # always both planes, on full tiles
         ctx.set_tuning(h_planes=2)
         got2 = H.gpu_layer(ctx, w, 0, x, w.batch_offsets)

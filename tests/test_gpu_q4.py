@@ -78,7 +78,7 @@ def test_q4_small_shapes(w):
 
 def test_q4_full_size_decode_layer_sampled_tokens():
     w = I.WORKLOADS["mixtral8x7b_decode"]
-    tokens = sorted(np.random.default_rng(7).choice(w.n_tokens, size=12, replace=False).tolist())
+    tokens = sorted(np.random.default_rng(7).choice(w.n_tokens, size=96, replace=False).tolist())
     err, rms = run_case(w, tokens=tokens, wdtype=np.float32)   # bf16-valued weights are exact in fp32
 
 

@@ -12,6 +12,7 @@ from oracle import ref
 
 import test_oracle_corr_pins as PC
 import test_oracle_pins as P
+import test_oracle_plan_pins as PP
 import test_oracle_q4_pins as PQ
 
 SRC = os.path.join(os.path.dirname(ref.__file__), "moe_oracle.c")
@@ -32,7 +33,10 @@ PINS = [P.test_logits_exact_on_small_integers, P.test_logits_within_fp32_bound_o
         PQ.test_zero_point_code_is_exact_zero_and_integers_stay_integers,
         PQ.test_round_trip_error_is_at_most_half_a_step, PQ.test_double_weights_feed_the_expert_like_float32_ones,
         PQ.test_rounding_to_bf16_matches_the_library_conversion_and_hand_ties,
-        PQ.test_dequant_to_original_precision_is_the_rounded_exact_value]
+        PQ.test_dequant_to_original_precision_is_the_rounded_exact_value,
+        PP.test_hand_solved_cases, PP.test_result_is_the_smallest_n_that_satisfies_the_group_exactly,
+        PP.test_each_inequality_can_be_the_binding_one, PP.test_best_and_worst_case_of_the_paper,
+        PP.test_invariances_and_monotonicity]
 
 MUTATIONS = {
     "ties go to the higher index": ("if (best < 0 || row[e] > row[best]) best = e;", "if (best < 0 || row[e] >= row[best]) best = e;"),
@@ -62,6 +66,12 @@ MUTATIONS = {
     "scale of the neighbouring group": ("const double s = bf16_to_double(s_bf16[(size_t)r * ng + c / group]);\n            const double z = bf16_to_double(z_bf16[(size_t)r * ng + c / group]);\n            const double v", "const double s = bf16_to_double(s_bf16[(size_t)r * ng + (c / group + 1) % ng]);\n            const double z = bf16_to_double(z_bf16[(size_t)r * ng + c / group]);\n            const double v"),
     "quantisation truncates": ("double v = rint(w[(size_t)r * cols + c] / s + z);", "double v = floor(w[(size_t)r * cols + c] / s + z);"),
     "dequantised weight not rounded to bf16": ("out[(size_t)r * cols + c] = to_bf16 ? round_to_bf16(v) : v;", "out[(size_t)r * cols + c] = v;"),
+    "planner: gate compute helps the gate transfer": ("if (!(dn * t_c_A >= t_io_G)) continue;", "if (!(dn * (t_c_A + t_c_G) >= t_io_G)) continue;"),
+    "planner: one hot expert too few in the third inequality": ("+ t_c_hotE >= t_io_G + (K + 1) * t_io_E)) continue;", "+ t_c_hotE >= t_io_G + K * t_io_E)) continue;"),
+    "planner: attention transfer forgotten": ("(K + len_q) * t_io_E + t_io_A)) continue;", "(K + len_q) * t_io_E)) continue;"),
+    "planner: queue compute forgotten": ("+ t_c_hotE + sum_q >= t_io_G", "+ t_c_hotE >= t_io_G"),
+    "planner: strict inequalities": ("if (!(dn * (t_c_A + t_c_G) >= t_io_G + K * t_io_E)) continue;", "if (!(dn * (t_c_A + t_c_G) > t_io_G + K * t_io_E)) continue;"),
+    "planner: empty queue still waits for the cold path": ("if (len_q > 0) {\n            if (!(dn * (t_c_A + t_c_G) + t_c_hotE", "if (len_q >= 0) {\n            if (!(dn * (t_c_A + t_c_G) + t_c_hotE"),
     "last selected expert skipped": ("for (int j = 0; j < k + S; ++j) {\n                int e = j < k ?", "for (int j = (k > 1); j < k + S; ++j) {\n                int e = j < k ?"),
 }
 
