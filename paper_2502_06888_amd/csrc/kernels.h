@@ -45,7 +45,7 @@ struct PlanPtrs {
     int32_t* exp_tile0;   // [E+S] first tile of an expert
     int32_t* exp_ntiles;  // [E+S]
     int32_t* blk_expert;  // [max_rowblks] routed expert owning a row block
-    int32_t* mail;        // [2E+1] counts, exec_order, n_active (copied to the host mailbox)
+    int32_t* mail;        // [2E+1] counts, exec_order, n_active: the host's mailbox (pinned, written by the plan)
 };
 
 struct Shape {

@@ -544,7 +544,6 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
     p.exp_tile0 = (int32_t*)(w + L.exp_tile0);
     p.exp_ntiles = (int32_t*)(w + L.exp_ntiles);
     p.blk_expert = (int32_t*)(w + L.blk_expert);
-    p.mail = (int32_t*)(w + L.mail);
     c->wtab_dev = (const uint8_t**)(w + L.wtab);
     c->wmeta_dev = (float2*)(w + L.wmeta);
     const int E = cfg->n_experts, S = cfg->n_shared;
@@ -574,6 +573,13 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipStreamSynchronize", e);
     e = hipHostMalloc((void**)&c->mailbox, (size_t)(2 * E + 1) * 4, hipHostMallocDefault);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipHostMalloc", e);
+    // The plan kernel writes counts and execution order straight into this pinned block (device
+    // stores to mapped host memory, visible to the host once the route event has completed): no
+    // copy node sits between the plan and the expert kernels.
+    void* mail_dev = nullptr;
+    e = hipHostGetDevicePointer(&mail_dev, c->mailbox, 0);
+    if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipHostGetDevicePointer", e);
+    p.mail = (int32_t*)mail_dev;
     e = hipHostMalloc((void**)&c->corr_host, (size_t)cfg->n_layers * E * E * 4, hipHostMallocDefault);
     if (e != hipSuccess) return cleanup(MOE_ERR_HIP, "hipHostMalloc", e);
     memset(c->corr_host, 0, (size_t)cfg->n_layers * E * E * 4);
@@ -814,7 +820,6 @@ moe_status moe_route(moe_ctx* ctx, int32_t layer, const void* x_dev,
         ctx->prev_idx_layer = layer;
         ctx->prev_idx_tokens = N;
     }
-    HIP_TRY(ctx, hipMemcpyAsync(ctx->mailbox, ctx->plan.mail, (size_t)(2 * E + 1) * 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipEventRecord(ctx->route_ev, st));
     ctx->routed_layer = layer;
     ctx->routed_tokens = N;
@@ -1490,6 +1495,7 @@ moe_status moe_route_static(void* stream, int32_t dtype, const void* x_dev, cons
         return at;
     };
     PlanPtrs p{};
+    p.meta = (int32_t*)take(16 * 4);
     p.topk_idx = topk_idx_dev ? topk_idx_dev : (int32_t*)take(A * 4);
     p.topk_w = topk_w_dev ? topk_w_dev : (float*)take(A * 4);
     p.counts = counts_dev ? counts_dev : (int32_t*)take(E * 4);
@@ -1497,7 +1503,6 @@ moe_status moe_route_static(void* stream, int32_t dtype, const void* x_dev, cons
     p.poff = (int32_t*)take((E + 1) * 4);
     p.nbatch = (int32_t*)take(E * 4);
     p.exec_order = exec_order_dev ? exec_order_dev : (int32_t*)take(E * 4);
-    p.meta = (int32_t*)take(16 * 4);
     p.perm = perm_dev ? perm_dev : (int32_t*)take(A * 4);
     p.inv_perm = inv_perm_dev ? inv_perm_dev : (int32_t*)take(A * 4);
     p.blk_counts = (int32_t*)take(nchunks * E * 4);
