@@ -907,7 +907,17 @@ void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) {
     }
     const int units = a.f / 16;
     int v = a.variant;
-    if (v == 0) v = a.full_tiles ? 3 : 1;
+    if (v == 0) {
+        v = a.full_tiles ? 3 : 1;
+        if (!a.full_tiles) {
+            // small tiles: the chip works through the workgroups in rounds of one per compute unit
+            // (LDS); seven wavefronts per workgroup instead of eight when that fills the last
+            // round better (rounds x units per workgroup is what the launch costs)
+            const long tiles = a.est_tiles > 0 ? a.est_tiles : 1;
+            auto cost = [&](int w) { return ((tiles * ((units + w - 1) / w) + 255) / 256) * w; };
+            if (cost(7) < cost(8)) v = 2;
+        }
+    }
     if (v == 3 && units >= 2)
         launch_up<4, 2>(st, a);
     else if (v == 2)

@@ -91,3 +91,35 @@ def test_static_route_refuses_sizes_beyond_its_array():
     assert ei.value.status == B.MOE_ERR_INVALID_ARG
     B.route_static(st, B.MOE_BF16, x, wg, 2, [0, 4])     # a legal call still works afterwards
     st.synchronize()
+
+
+def test_static_route_replays_from_a_graph():
+    """The callers this entry point is for include code under HIP graph capture: the call records
+    nothing but its kernels, and replays reproduce the eager outputs, with eager calls (which use
+    the same static array) and synchronisation between the replays."""
+    w = I.Workload("static_graph", "bf16", 256, 512, 16, 4, batch_tokens=(33, 0, 60, 7))
+    data, _ = I.gen_layer(w, 0, with_experts=False)
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream()
+    wg, x = data.wg.to(dev), data.x.to(dev)
+    bo = [int(v) for v in w.batch_offsets]
+    out = H.alloc_route_outputs(w, w.n_tokens, dev)
+    with torch.cuda.stream(st):
+        B.route_static(st, B.MOE_BF16, x, wg, w.top_k, bo, out)
+    st.synchronize()
+    want = {f: getattr(out, f).clone() for f in FIELDS}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=st):
+        B.route_static(st, B.MOE_BF16, x, wg, w.top_k, bo, out)
+    other = H.alloc_route_outputs(w, bo[2], dev)
+    for rep in range(3):
+        for f in FIELDS:
+            getattr(out, f).fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for f in FIELDS:
+            assert torch.equal(getattr(out, f).view(torch.int32), want[f].view(torch.int32)), (rep, f)
+        with torch.cuda.stream(st):               # an eager call on a smaller group in between
+            B.route_static(st, B.MOE_BF16, x[:bo[2]], wg, w.top_k, bo[:3], other)
+        st.synchronize()
