@@ -166,6 +166,22 @@ def measure_attention_batch(w, n_seq, torch, pos: int = 512) -> float:
     return best
 
 
+_STREAMS = {}
+
+
+def shared_streams(torch):
+    """One compute and one copy stream for the whole run, created once and in this order.  The
+    runtime maps streams onto a few hardware queues as they are created and destroyed; with fresh
+    streams for every leg the copy stream of a later leg now and then lands on the compute
+    stream's queue, and its copies then wait behind the expert kernels (measured: 281 instead of
+    235 ms per pass on the fine-grained stack, depending only on how many streams earlier legs had
+    created)."""
+    if not _STREAMS:
+        _STREAMS["compute"] = torch.cuda.Stream()
+        _STREAMS["copy"] = torch.cuda.Stream()
+    return _STREAMS["compute"], _STREAMS["copy"]
+
+
 def release_memory(torch):
     """Hand cached device and pinned host blocks back (the streamed stacks pin tens of GiB each)."""
     import gc
@@ -179,7 +195,7 @@ def measure_link_peak(torch, nbytes: int = 1 << 30, reps: int = 5) -> float:
     """Best host->device rate of one large copy from pinned memory on this machine, GB/s."""
     src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
     dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
-    st = torch.cuda.Stream()
+    st = shared_streams(torch)[1]
     best = 0.0
     with torch.cuda.stream(st):
         for _ in range(reps):
@@ -200,7 +216,7 @@ def bench_streamed(w, args):
     from paper_2502_06888_amd import binding as B
     from paper_2502_06888_amd import inputs as I
     dev = torch.device("cuda:0")
-    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    compute, copy = shared_streams(torch)
     q4 = args.weight_bits == 4
     cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, w.n_layers,
                         w.window_layers, w.n_tokens, w.n_batches, B.MOE_BF16, 1, 4 if q4 else 0)
@@ -476,7 +492,7 @@ def bench_resident(w, args, data=None, steps=None, warmup=None, with_cpu_baselin
     q4 = args.weight_bits == 4
     if data is None:
         data, _ = I.gen_layer(w, 0, threads=16, with_experts=not q4)
-    compute = torch.cuda.Stream()
+    compute = shared_streams(torch)[0]
     cfg = B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_shared, 1, 0, w.n_tokens,
                         w.n_batches, B.MOE_F32 if w.dtype == "f32" else B.MOE_BF16, 1, 4 if q4 else 0)
     ctx = B.MoeContext(cfg, compute)
@@ -668,18 +684,27 @@ def main():
     wd = I.WORKLOADS["mixtral8x7b_decode"]
     out, data = bench_resident(wd, args)
     if not args.no_legs:
+        # a leg that cannot run on this machine (say, not enough pinnable host memory for the 36 GiB
+        # stack) is reported as such; the headline above stands on its own
         legs = {}
+
+        def run_leg(key, fn):
+            try:
+                leg = fn()
+                legs[key] = {k: leg[k] for k in LEG_KEYS if k in leg}
+            except Exception as exc:                # noqa: BLE001 - reported, not hidden
+                legs[key] = {"error": f"{type(exc).__name__}: {exc}"[:300]}
+            release_memory(torch)
+
         wp = I.WORKLOADS["mixtral8x7b_prefill"]     # matrix-core roofline: same layer, 16384 tokens
         dp = I.LayerData(x=I.gen_x_gaussian(wp), wg=data.wg, w1=data.w1, w3=data.w3, w2=data.w2)
-        leg, _ = bench_resident(wp, args, data=dp, steps=min(args.steps, 20), warmup=min(args.warmup, 5),
-                                with_cpu_baseline=False)
-        legs[wp.name] = {k: leg[k] for k in LEG_KEYS if k in leg}
+        run_leg(wp.name, lambda: bench_resident(wp, args, data=dp, steps=min(args.steps, 20),
+                                                warmup=min(args.warmup, 5), with_cpu_baseline=False)[0])
         del data, dp
         release_memory(torch)
         for name, bits in (("finegrained_stream", 16), ("finegrained_stream", 4), ("mixtral8x22b_stream", 16)):
             args.weight_bits = bits                 # host-link roofline and the pipeline's bubbles
-            leg = bench_streamed(I.WORKLOADS[name], args)
-            legs[name + ("_4bit" if bits == 4 else "")] = {k: leg[k] for k in LEG_KEYS if k in leg}
+            run_leg(name + ("_4bit" if bits == 4 else ""), lambda: bench_streamed(I.WORKLOADS[name], args))
         out["legs"] = legs
     print(json.dumps(out))
 

@@ -2,8 +2,10 @@
 //
 // Every expert is an FFN evaluated once over all of its tokens from all batches of the batch
 // group, experts in execution order (paper Section 2.1 and Section 5).  Two launches:
-//   up  : H = silu(X W1^T) .* (X W3^T)   reduction over d, H stored as bf16 in fragment order
-//   down: O = H W2^T                      reduction over f, fp32, optional split-K partials
+//   up  : H = silu(X W1^T) .* (X W3^T)   reduction over d on the bf16 MFMA; H stored in fragment order as
+//                                        fp16 plus a plane with its rounding remainder (bf16 experts)
+//   down: O = H W2^T                      reduction over f on the fp16 MFMA (W2 placed as fp16), the
+//                                        remainder plane only where needed; fp32 split-K partials
 //
 // Work split.  A tile is one expert x up to 8 row blocks of 32 tokens.  A workgroup takes a tile
 // and WAVES * U output units; a wavefront owns U units for all rows of the tile, so every weight
@@ -31,9 +33,6 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef int i32x8 __attribute__((ext_vector_type(8)));
-typedef short i16x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte unit as a first-class value
 typedef const __attribute__((address_space(1))) u32x4* gptr;  // global (HBM) address space
 
@@ -50,12 +49,6 @@ __device__ __forceinline__ gptr as_global(const void* p) { return (gptr)(uintptr
 __device__ __forceinline__ u32x4 load_stream(gptr p) { return __builtin_nontemporal_load(p); }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-__device__ __forceinline__ uint32_t bf16_bits_rne(float v) {
-    uint32_t a = __float_as_uint(v);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    return a >> 16;
-}
 
 // One LDS stage holds, per row block, SX reduction steps of 16 for PL planes of the activations
 // (SX * PL == 8): SX = 8, PL = 1 normally; SX = 4, PL = 2 when the down projection also

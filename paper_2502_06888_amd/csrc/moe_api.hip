@@ -366,9 +366,7 @@ moe_status stream_one(moe_ctx* ctx, int layer, int e, bool prefetch) {
     if (!ls.host[e]) return fail(ctx, MOE_ERR_STATE, "layer %d expert %d has no weights", layer, e);
     if (ls.slot_of[e] >= 0) return MOE_OK;  // already in flight or loaded
     // The free slot released longest ago: its readers are the furthest behind the head of the
-    // compute stream, so the copy stream's wait for them is the least likely to stall.  (Taking
-    // the first free slot by index drifts, over many passes, towards slots released a moment
-    // ago, whose readers still wait for copies that sit just ahead in the same copy stream.)
+    // compute stream, so the copy stream's wait for them is the least likely to stall.
     int pick = -1;
     for (size_t i = 0; i < ctx->slots.size(); ++i)
         if (ctx->slots[i].state == SLOT_FREE &&
