@@ -367,6 +367,28 @@ def test_f32_maximum_topk_and_many_experts():
     run_case(w)
 
 
+def test_per_tile_choice_holds_the_tolerance_across_output_scales():
+    """The same layer with W2 scaled by 1, 2, 4, ... 128: the outputs grow from rms ~1 to rms ~100,
+    the absolute part of the tolerance shrinks next to them, and somewhere on the way the tiles
+    start to take the remainder plane of the intermediate.  At every scale, also where some tiles
+    take it and others do not, the default mode must stay inside the tolerance; the number of
+    workgroups that take the remainder plane never falls as the outputs grow."""
+    w = I.Workload("scales", "bf16", 512, 2048, 4, 2, n_shared=1, batch_tokens=(90, 130, 75), w_std=0.05)
+    data, _ = I.gen_layer(w, 0)
+    taken = []
+    for scale in (1, 2, 4, 8, 16, 32, 64, 128):
+        d2 = I.LayerData(x=data.x, wg=data.wg, w1=data.w1, w3=data.w3,
+                         w2=[I.to_storage(I.as_f32(t) * scale, "bf16") for t in data.w2])   # exact: a power of two
+        ctx = H.make_ctx(w)
+        H.place_layer(ctx, w, 0, d2)
+        ctx.reset_stats()
+        got, want, err = run_case(w, data=d2, ctx=ctx)
+        taken.append(ctx.stats()["h_remainder_wgs"])
+        ctx.close()
+    assert taken[0] == 0 and taken[-1] > 0, taken
+    assert taken == sorted(taken), taken
+
+
 def test_weights_beyond_the_fp16_range_are_placed_scaled():
     """W2 is placed as fp16.  An expert whose W2 holds a weight beyond 65504 is stored times a
     power of two that brings it into range (exact), and the outputs are scaled back: same oracle,
