@@ -603,9 +603,9 @@ def bench_resident(w, args, data=None, steps=None, warmup=None, with_cpu_baselin
                    "n_experts": w.n_experts, "top_k": w.top_k, "n_batches": w.n_batches,
                    "tokens": w.n_tokens, "experts": "resident in HBM", "weight_bits": args.weight_bits,
                    "n_active": n_active,
-                   "h_format": "f32" if w.dtype == "f32" else ("bf16 pair" if q4 else
+                   "h_format": "f32" if w.dtype == "f32" else
                                "fp16 + fp16 remainder plane (" + ("always multiplied" if args.h_planes == 2
-                                                                   else "multiplied where needed") + ")"),
+                                                                  else "multiplied where needed") + ")",
                    "remainder_plane_workgroups_per_step": st["h_remainder_wgs"] / reps,
                    "h_values_clamped": st["h_saturated"],
                    "settle_steps_untimed": settle_steps,

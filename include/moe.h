@@ -168,7 +168,9 @@ moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const voi
  * consecutive weights of a row.  For each of W1, W3 ([f, d]) and W2 ([d, f]), all device
  * pointers: q = codes, uint8 [rows, cols / 2], the even column in the low nibble; s, z = bf16
  * [rows, cols / 64].  How s and z were fitted is the caller's business.  The kernels turn a
- * weight back into bf16 (fp32 fma, one rounding) right before it is multiplied.  Everything
+ * weight back into bf16 (fp32 fma, one rounding) right before it is multiplied.  (If an expert's
+ * dequantised W2 would leave the fp16 range of the down projection, the packed copy of its scales
+ * is multiplied by a power of two, undone on the outputs: exact.)  Everything
  * else as moe_set_expert; the packed blob has moe_plan().expert_bytes = 27/16 * d * f bytes.
  */
 moe_status moe_set_expert_q4(moe_ctx* ctx, int32_t layer, int32_t expert, const void* q1_dev,
@@ -265,7 +267,7 @@ moe_status moe_reset_stats(moe_ctx* ctx);
 /*
  * moe_set_tuning -- knobs, 0 keeps the current value.  split_k: split of the down projection's
  * reduction (auto by default).
- * h_planes (bf16 experts): the intermediate H = silu(X W1^T) .* (X W3^T) is handed from the up
+ * h_planes (bf16 path): the intermediate H = silu(X W1^T) .* (X W3^T) is handed from the up
  * projections to the down projection as fp16 (W2 is placed as fp16 as well, times a power of two
  * when it holds weights beyond the fp16 range, undone on the outputs), together with a second
  * fp16 plane holding the rounding remainder H - fp16(H).  1 (default): the down projection
@@ -274,8 +276,8 @@ moe_status moe_reset_stats(moe_ctx* ctx);
  * threshold (6 standard deviations of the remainders' contribution to an output within 0.8 of
  * the 1e-2 absolute tolerance, from the row energies of W2 taken at placement) is computed from
  * the value plane alone, at half the matrix-core work.  2: the remainder plane is always
- * multiplied (outputs then never depend on which tokens share a tile).  4-bit experts carry H as
- * a bf16 pair and always multiply both planes.
+ * multiplied (outputs then never depend on which tokens share a tile).  4-bit experts use the same
+ * format: their W2 is turned back into bf16 in registers and handed to the fp16 MFMA as fp16.
  * variant: launch shape of the bf16 expert kernels, ones digit: 1 = 8 wavefronts x 1 output unit,
  * 2 = 7 x 1, 3 = 4 x 2 (0 = chosen by tile size); tens digit p (1..6): on full tiles the workgroups
  * an XCD runs together cover 2^(p-1) tiles x 32/2^(p-1) unit groups (0 = 4 x 8); -1 selects the

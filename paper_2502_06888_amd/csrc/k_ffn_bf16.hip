@@ -1,4 +1,5 @@
-// Grouped SwiGLU expert FFN on bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulate.
+// Grouped SwiGLU expert FFN on the 32x32x16 MFMA (bf16 for the up projections, fp16 for the down
+// projection), fp32 accumulate.
 //
 // Every expert is an FFN evaluated once over all of its tokens from all batches of the batch
 // group, experts in execution order (paper Section 2.1 and Section 5).  Two launches:
@@ -29,7 +30,6 @@ namespace kmoe {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -408,13 +408,12 @@ __device__ __forceinline__ Wg locate(const FfnArgs& a, int n_groups, int split) 
 // register r + 8 the up value of the same feature: exactly the lane's 16-byte unit in the
 // fragment order of the down projection, so H is written with one 16-byte store per row block.
 //
-// Format of H.  bf16 experts (h_mode 0, 1): fp16 (nearest even, clamped to the largest finite
-// value; clamped values are counted), plus a second plane with the rounding remainder
-// h - fp16(h), also fp16.  The down projection multiplies the remainder plane only for tiles that
-// need it: the up kernel adds, per token row, the energy of the remainders (sum of squares over
-// the features of this workgroup) to herr[row], in integer units of 2^-20 of the expert's
-// threshold, so that the total does not depend on the order of the atomic additions.
-// 4-bit experts (h_mode 2): a bf16 pair (value and remainder), both always multiplied.
+// Format of H: fp16 (nearest even, clamped to the largest finite value; clamped values are
+// counted), plus a second plane with the rounding remainder h - fp16(h), also fp16.  The down
+// projection multiplies the remainder plane only for tiles that need it: the up kernel adds, per
+// token row, the energy of the remainders (sum of squares over the features of this workgroup) to
+// herr[row], in integer units of 2^-20 of the expert's threshold, so that the total does not
+// depend on the order of the atomic additions.
 constexpr float kErrUnit = 1048576.f;  // herr counts in units of threshold / 2^20
 template <int NB, int WAVES, int U>
 __device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U][NB], int nblk,
@@ -422,7 +421,6 @@ __device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U
     const int lane = threadIdx.x & 63;
     u32x4* hp = reinterpret_cast<u32x4*>(a.out);
     const size_t ksteps_h = (size_t)a.f / 16;
-    const bool pair_bf16 = a.h_mode == 2;
     float esum[NB];
     int sat = 0;
 #pragma unroll
@@ -444,25 +442,18 @@ __device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U
                         const float gv = acc[u][b][2 * q + t];
                         h[t] = gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[u][b][2 * q + t + 8];
                     }
-                    if (pair_bf16) {
-                        const bf16x2 v = {(__bf16)h[0], (__bf16)h[1]};
-                        const bf16x2 l = {(__bf16)(h[0] - (float)v[0]), (__bf16)(h[1] - (float)v[1])};
-                        hi[q] = __builtin_bit_cast(uint32_t, v);
-                        lo[q] = __builtin_bit_cast(uint32_t, l);
-                    } else {
-                        float r[2];
-                        f16x2 v, l;
+                    float r[2];
+                    f16x2 v, l;
 #pragma unroll
-                        for (int t = 0; t < 2; ++t) {
-                            sat += __builtin_fabsf(h[t]) > 65504.f ? 1 : 0;
-                            v[t] = (_Float16)__builtin_fminf(__builtin_fmaxf(h[t], -65504.f), 65504.f);
-                            r[t] = h[t] - (float)v[t];  // exact in fp32
-                            l[t] = (_Float16)__builtin_fminf(__builtin_fmaxf(r[t], -65504.f), 65504.f);
-                            esum[b] = __builtin_fmaf(r[t], r[t], esum[b]);
-                        }
-                        hi[q] = __builtin_bit_cast(uint32_t, v);
-                        lo[q] = __builtin_bit_cast(uint32_t, l);
+                    for (int t = 0; t < 2; ++t) {
+                        sat += __builtin_fabsf(h[t]) > 65504.f ? 1 : 0;
+                        v[t] = (_Float16)__builtin_fminf(__builtin_fmaxf(h[t], -65504.f), 65504.f);
+                        r[t] = h[t] - (float)v[t];  // exact in fp32
+                        l[t] = (_Float16)__builtin_fminf(__builtin_fmaxf(r[t], -65504.f), 65504.f);
+                        esum[b] = __builtin_fmaf(r[t], r[t], esum[b]);
                     }
+                    hi[q] = __builtin_bit_cast(uint32_t, v);
+                    lo[q] = __builtin_bit_cast(uint32_t, l);
                 }
                 const size_t at = ((size_t)(hblk0 + b) * ksteps_h + (size_t)(wunit + u)) * 64 + lane;
                 // streaming stores: measurably cheaper next to the weight stream than cached ones
@@ -472,8 +463,8 @@ __device__ __forceinline__ void store_up(const FfnArgs& a, const f32x16 (&acc)[U
             }
         }
     }
-    if (a.h_mode != 0) return;  // uniform over the launch
     if (sat) atomicAdd(a.sat_count, sat);
+    if (a.h_mode != 0) return;  // remainder always multiplied: no energies needed (uniform over the launch)
     // remainder energy per token row of the tile: lanes l and l + 32 hold the same token, the
     // wavefronts meet in LDS (free: every LDS read of the pass is behind a barrier), one integer
     // atomic per row and workgroup
@@ -578,6 +569,20 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
 #undef CALL
 }
 
+// True when the down projection of this tile must multiply the remainder plane of H too: the
+// launch asks for it (h_mode 1), or some token row of the tile recorded a remainder energy above
+// the expert's threshold (h_mode 0).  Uniform over the workgroup; one thread per row.
+__device__ __forceinline__ int wants_remainder(const FfnArgs& a, int nblk, int hblk0) {
+    int two = a.h_mode == 1;
+    if (a.h_mode == 0) {
+        const int over = (int)threadIdx.x < nblk * kRowBlk &&
+                         a.herr[(size_t)hblk0 * kRowBlk + threadIdx.x] > (unsigned long long)kErrUnit;
+        two = __syncthreads_or(over);
+        if (two && threadIdx.x == 0) atomicAdd(a.sat_count + 1, 1);  // workgroups that took the remainder plane
+    }
+    return two;
+}
+
 // Down projection of bf16 experts: H and W2 as fp16 on the fp16 MFMA.  The remainder plane of H
 // is multiplied as well (two planes per stage, twice the MFMAs) when the launch asks for it
 // (h_mode 1) or when, for some token row of the tile, the energy of the remainders recorded by
@@ -592,14 +597,8 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     const int hblk0 = a.tile_hblk[w.tile];
     const uint8_t* blob = blob_of(a, e);
     const float scale = a.wmeta[e].x;
-    int two = a.h_mode == 1;
-    if (a.h_mode == 0) {
-        static_assert(WAVES * 64 >= kTileBlks * kRowBlk, "one thread per token row of the tile");
-        const int over = (int)threadIdx.x < nblk * kRowBlk &&
-                         a.herr[(size_t)hblk0 * kRowBlk + threadIdx.x] > (unsigned long long)kErrUnit;
-        two = __syncthreads_or(over);
-        if (two && threadIdx.x == 0) atomicAdd(a.sat_count + 1, 1);  // workgroups that took the remainder plane
-    }
+    static_assert(WAVES * 64 >= kTileBlks * kRowBlk, "one thread per token row of the tile");
+    const int two = wants_remainder(a, nblk, hblk0);
     TileCtx c;
     c.nks = a.f / 16;
     c.ustride = (size_t)c.nks * 64;
@@ -631,7 +630,8 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
 //
 // Experts may be kept and moved as 4-bit codes with one scale and one zero point per group of 64
 // weights along the reduction axis, W = s * (W_q - z) (paper Section 7, "Quantization", Eq. 8);
-// they are converted back to bf16 right before the multiplication.  A group of 64 is exactly
+// they are converted back to bf16 right before the multiplication (and handed to the fp16 MFMA of
+// the down projection as fp16, exactly).  A group of 64 is exactly
 // four reduction steps of one fragment row, so the packed stream of an output unit is, per
 // step quad, 1 KiB of codes (lane l: four dwords = steps 4q..4q+3, eight codes each, in the
 // lane's fragment order) and 128 bytes of (s, z) bf16 pairs (one per fragment row).  The ring
@@ -644,6 +644,10 @@ struct QCtx {
     gptr32 sz;    // (s | z << 16) of this wavefront's unit (+ lane & 31), 32 dwords per quad
 };
 
+// HT = 0: the dequantised weights as bf16 (one hardware rounding of the fp32 fma).  HT = 1: the
+// same bf16 values handed over as fp16, for the down projection on the fp16 MFMA (exact: the
+// placement scales an expert's (s) by a power of two when its weights would leave the fp16 range).
+template <int HT>
 __device__ __forceinline__ bf16x8 dequant8(uint32_t codes, uint32_t sz) {
     const float s = __uint_as_float(sz << 16);
     const float z = __uint_as_float(sz & 0xffff0000u);
@@ -654,6 +658,12 @@ __device__ __forceinline__ bf16x8 dequant8(uint32_t codes, uint32_t sz) {
     bf16x8 r;
 #pragma unroll
     for (int p = 0; p < 8; ++p) r[p] = (__bf16)v[p];
+    if (HT == 1) {
+        f16x8 h;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) h[p] = (_Float16)(float)r[p];
+        return __builtin_bit_cast(bf16x8, h);
+    }
     return r;
 }
 
@@ -694,7 +704,7 @@ __device__ __forceinline__ void open_pass_q4(const TileCtx& c, const QCtx& q, Pi
     }
 }
 
-template <int MODE, int NB, int WAVES, int SX, int PL>
+template <int MODE, int NB, int WAVES, int SX, int PL, int HT>
 __device__ __forceinline__ void run_pass_q4(const TileCtx& c, const QCtx& q, PipeQ<NB, WAVES, SX>& pp,
                                             f32x16 (&acc)[1][NB]) {
     static_assert(SX * PL == kFragsPerBlk, "stage geometry");
@@ -726,8 +736,8 @@ __device__ __forceinline__ void run_pass_q4(const TileCtx& c, const QCtx& q, Pip
             for (int t = 0; t < NF; ++t) {
                 const int j = t / NS, b = (t % NS) / PL;
                 const int slot = (g % RS) * QS + j / 4;
-                if (t % NS == 0) wf = dequant8(pp.wq[slot][j % 4], pp.sz[slot]);
-                acc[0][b] = mfma<MODE>(wf, as_bf16x8(win[t % DD]), acc[0][b]);
+                if (t % NS == 0) wf = dequant8<HT>(pp.wq[slot][j % 4], pp.sz[slot]);
+                acc[0][b] = mfma<MODE, HT>(wf, as_bf16x8(win[t % DD]), acc[0][b]);
                 if (t + DD < NF) win[t % DD] = KMOE_FRAG_AT(t + DD);
                 if (t % NS == NS - 1 && j % 4 == 3) {  // the quad is consumed: next ring turn
                     const size_t quad = (size_t)((kk + RS * SX) / 4 + j / 4);
@@ -755,10 +765,10 @@ __device__ __forceinline__ void run_pass_q4(const TileCtx& c, const QCtx& q, Pip
                 for (int j = 0; j < SX; ++j) {
                     if (kk + j < c.k1) {
                         const int slot = (g % RS) * QS + j / 4;
-                        const bf16x8 wf = dequant8(pp.wq[slot][j % 4], pp.sz[slot]);
+                        const bf16x8 wf = dequant8<HT>(pp.wq[slot][j % 4], pp.sz[slot]);
 #pragma unroll
                         for (int i = 0; i < NS; ++i)
-                            acc[0][i / PL] = mfma<MODE>(wf, as_bf16x8(L[(i * SX + j) * 64]), acc[0][i / PL]);
+                            acc[0][i / PL] = mfma<MODE, HT>(wf, as_bf16x8(L[(i * SX + j) * 64]), acc[0][i / PL]);
                         if (j % 4 == 3 && kk + RS * SX + j < c.k1) {
                             const size_t quad = (size_t)((kk + RS * SX) / 4 + j / 4);
                             pp.wq[slot] = load_stream(q.nib + quad * 64);
@@ -778,7 +788,7 @@ __device__ __forceinline__ void run_pass_q4(const TileCtx& c, const QCtx& q, Pip
 template <int MODE, int NB, int WAVES, int PL>
 __device__ __forceinline__ void run_tile_q4(const FfnArgs& a, TileCtx c, const uint8_t* nib_section,
                                             const uint8_t* sz_section, int n_units, int grp,
-                                            int hblk0, int sp) {
+                                            int hblk0, int sp, int expert, float scale) {
     constexpr int SX = 8 / PL;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int unit0 = grp * WAVES + wave;
@@ -791,11 +801,11 @@ __device__ __forceinline__ void run_tile_q4(const FfnArgs& a, TileCtx c, const u
     pp.xm.init(c);
     f32x16 acc[1][NB];
     open_pass_q4<NB, WAVES, SX, PL>(c, q, pp);
-    run_pass_q4<MODE, NB, WAVES, SX, PL>(c, q, pp, acc);
+    run_pass_q4<MODE, NB, WAVES, SX, PL, MODE>(c, q, pp, acc);  // up: bf16 MFMA; down: fp16 MFMA
     if (MODE == 0)
-        store_up<NB, WAVES, 1>(a, acc, c.nblk, wunit, unit0, hblk0, 0, c.lds);  // h_mode 2: bf16 pair
+        store_up<NB, WAVES, 1>(a, acc, c.nblk, wunit, unit0, hblk0, expert, c.lds);
     else
-        store_down<NB, 1>(a, acc, c.nblk, wunit, unit0, hblk0, sp, 1.f);
+        store_down<NB, 1>(a, acc, c.nblk, wunit, unit0, hblk0, sp, scale);
 }
 
 // Blob of a 4-bit expert: [up codes d*f | up (s,z) d*f/8 | down codes d*f/2 | down (s,z) d*f/16] bytes.
@@ -819,13 +829,14 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_q4_kernel(FfnArgs a, int n_
     c.k1 = c.nks;
     c.nblk = nblk;
     const size_t df = (size_t)a.d * a.f;
-#define CALL(NB) run_tile_q4<0, NB, WAVES, 1>(a, c, blob, blob + df, a.f / 16, w.grp, hblk0, 0)
+#define CALL(NB) run_tile_q4<0, NB, WAVES, 1>(a, c, blob, blob + df, a.f / 16, w.grp, hblk0, 0, e, 1.f)
     NB_SWITCH(CALL)
 #undef CALL
 }
 
-template <int WAVES, int PL>
+template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void ffn_down_q4_kernel(FfnArgs a, int n_groups) {
+    static_assert(WAVES * 64 >= kTileBlks * kRowBlk, "one thread per token row of the tile");
     extern __shared__ u32x4 lds[];
     const Wg w = locate(a, n_groups, a.split_k);
     if (!w.live) return;
@@ -833,6 +844,8 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_q4_kernel(FfnArgs a, int 
     const int nblk = a.tile_nblk[w.tile];
     const int hblk0 = a.tile_hblk[w.tile];
     const uint8_t* blob = blob_of(a, e);
+    const float scale = a.wmeta[e].x;
+    const int two = wants_remainder(a, nblk, hblk0);
     TileCtx c;
     c.nks = a.f / 16;
     c.ustride = 0;
@@ -840,16 +853,26 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_q4_kernel(FfnArgs a, int 
     c.actbase = as_global(a.act) + (size_t)hblk0 * c.nks * 64;
     c.plane = (size_t)a.h_plane_units;
     c.lds = lds;
-    constexpr int SX = 8 / PL;
-    const int nstage = (c.nks + SX - 1) / SX;
-    c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
-    c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
     c.nblk = nblk;
     const size_t df = (size_t)a.d * a.f;
     const uint8_t* down = blob + df + df / 8;
-#define CALL(NB) run_tile_q4<1, NB, WAVES, PL>(a, c, down, down + df / 2, a.d / 32, w.grp, hblk0, w.sp)
-    NB_SWITCH(CALL)
+    if (two) {
+        constexpr int SX = 4;
+        const int nstage = (c.nks + SX - 1) / SX;
+        c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
+        c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
+#define CALL(NB) run_tile_q4<1, NB, WAVES, 2>(a, c, down, down + df / 2, a.d / 32, w.grp, hblk0, w.sp, e, scale)
+        NB_SWITCH(CALL)
 #undef CALL
+    } else {
+        constexpr int SX = 8;
+        const int nstage = (c.nks + SX - 1) / SX;
+        c.k0 = (int)((long long)w.sp * nstage / a.split_k) * SX;
+        c.k1 = min((int)((long long)(w.sp + 1) * nstage / a.split_k) * SX, c.nks);
+#define CALL(NB) run_tile_q4<1, NB, WAVES, 1>(a, c, down, down + df / 2, a.d / 32, w.grp, hblk0, w.sp, e, scale)
+        NB_SWITCH(CALL)
+#undef CALL
+    }
 }
 
 template <int WAVES, int U>
@@ -879,7 +902,7 @@ hipError_t allow_lds(K kernel) {
 int ffn_configure() {
     hipError_t e = allow_lds(&ffn_up_kernel<8, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_up_q4_kernel<8>);
-    if (e == hipSuccess) e = allow_lds(&ffn_down_q4_kernel<8, 2>);
+    if (e == hipSuccess) e = allow_lds(&ffn_down_q4_kernel<8>);
     if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<7, 1>);
     if (e == hipSuccess) e = allow_lds(&ffn_up_kernel<4, 2>);
     if (e == hipSuccess) e = allow_lds(&ffn_down_kernel<8, 1>);
@@ -920,10 +943,10 @@ void launch_ffn_up_bf16(hipStream_t st, const FfnArgs& a) {
 }
 
 void launch_ffn_down_bf16(hipStream_t st, const FfnArgs& a) {
-    if (a.weight_bits == 4) {  // 4-bit experts: bf16 pair, both planes always
+    if (a.weight_bits == 4) {  // 4-bit experts: weights dequantised in registers, same H format
         const int n_groups = (a.d / 32 + 7) / 8;
         const int grid = (a.max_tiles * n_groups * a.split_k + kXcd - 1) / kXcd * kXcd;
-        hipLaunchKernelGGL((ffn_down_q4_kernel<8, 2>), dim3(grid), dim3(512), kLdsBytes, st, a, n_groups);
+        hipLaunchKernelGGL((ffn_down_q4_kernel<8>), dim3(grid), dim3(512), kLdsBytes, st, a, n_groups);
         return;
     }
     // Two units per wavefront halve the LDS reads per MFMA: faster on full tiles (prefill layer)

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void pack_sz_q4_kernel(const uint16_t* __
                                                               const uint16_t* __restrict__ sb,
                                                               const uint16_t* __restrict__ zb,
                                                               int n_units, int nq, int half_rows,
-                                                              uint32_t* __restrict__ out) {
+                                                              float scale, uint32_t* __restrict__ out) {
     const size_t n = (size_t)n_units * nq * 32;
     for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < n;
          u += (size_t)gridDim.x * kThreads) {
@@ -113,7 +113,59 @@ __global__ __launch_bounds__(kThreads) void pack_sz_q4_kernel(const uint16_t* __
             s = sb[at];
             z = zb[at];
         }
+        // scale: a power of two times the group's scale (exact in bf16 short of underflow); the
+        // dequantised weight s * (code - z) scales with it, the zero point stays
+        if (scale != 1.f) s = __float_as_uint(__uint_as_float(s << 16) * scale) >> 16;
         out[u] = s | (z << 16);
+    }
+}
+
+// Range and row energy of a 4-bit W2 [d, f] as the kernels will see it: every weight
+// bf16(fma(code, s, -z * s)) (fp32 fma, nearest-even rounding to bf16).  Same outputs as
+// w2_stats_kernel.
+__global__ __launch_bounds__(kThreads) void w2_stats_q4_kernel(const uint8_t* __restrict__ q2,
+                                                               const uint16_t* __restrict__ s2,
+                                                               const uint16_t* __restrict__ z2, int d, int f,
+                                                               uint32_t* __restrict__ out) {
+    __shared__ float ssum[kThreads / 64];
+    __shared__ uint32_t smax[kThreads / 64];
+    for (int row = blockIdx.x; row < d; row += gridDim.x) {
+        float sum = 0.f;
+        uint32_t amax = 0;
+        for (int i = threadIdx.x; i < f; i += kThreads) {
+            const uint8_t byte = q2[(size_t)row * (f / 2) + i / 2];
+            const float code = (float)((i & 1) ? (byte >> 4) : (byte & 15));
+            const float sc = __uint_as_float((uint32_t)s2[(size_t)row * (f / 64) + i / 64] << 16);
+            const float zp = __uint_as_float((uint32_t)z2[(size_t)row * (f / 64) + i / 64] << 16);
+            float w = __builtin_fmaf(code, sc, -zp * sc);
+            uint32_t bits = __float_as_uint(w);
+            if ((bits & 0x7fffffffu) <= 0x7f800000u) bits += 0x7fffu + ((bits >> 16) & 1u);  // to bf16, nearest even
+            bits &= 0xffff0000u;
+            w = __uint_as_float(bits);
+            amax = max(amax, bits & 0x7fffffffu);
+            sum = __builtin_fmaf(w, w, sum);
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            sum += __shfl_xor(sum, m, 64);
+            amax = max(amax, (uint32_t)__shfl_xor((int)amax, m, 64));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            ssum[threadIdx.x >> 6] = sum;
+            smax[threadIdx.x >> 6] = amax;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            uint32_t m = 0;
+            for (int w = 0; w < kThreads / 64; ++w) {
+                t += ssum[w];
+                m = max(m, smax[w]);
+            }
+            atomicMax(out, m);
+            atomicMax(out + 1, __float_as_uint(t));
+        }
+        __syncthreads();
     }
 }
 
@@ -331,17 +383,22 @@ void launch_zero_u64(hipStream_t st, unsigned long long* p, size_t n) {
 
 void launch_pack_expert_q4(hipStream_t st, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
                            const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
-                           const uint16_t* s2, const uint16_t* z2, int d, int f, void* blob) {
+                           const uint16_t* s2, const uint16_t* z2, int d, int f, void* blob, float w2_scale) {
     const size_t df = (size_t)d * f;
     uint8_t* b = (uint8_t*)blob;
     hipLaunchKernelGGL(pack_up_q4_kernel, dim3(grid_for(df / 16)), dim3(kThreads), 0, st, q1, q3, d, f,
                        (uint4*)b);
     hipLaunchKernelGGL(pack_sz_q4_kernel, dim3(grid_for(df / 32)), dim3(kThreads), 0, st, s1, z1, s3, z3,
-                       f / 16, d / 64, 16, (uint32_t*)(b + df));
+                       f / 16, d / 64, 16, 1.f, (uint32_t*)(b + df));
     hipLaunchKernelGGL(pack_down_q4_kernel, dim3(grid_for(df / 32)), dim3(kThreads), 0, st, q2, d, f,
                        (uint4*)(b + df + df / 8));
     hipLaunchKernelGGL(pack_sz_q4_kernel, dim3(grid_for(df / 64)), dim3(kThreads), 0, st, s2, z2, s2, z2,
-                       d / 32, f / 64, 32, (uint32_t*)(b + df + df / 8 + df / 2));
+                       d / 32, f / 64, 32, w2_scale, (uint32_t*)(b + df + df / 8 + df / 2));
+}
+
+void launch_w2_stats_q4(hipStream_t st, const uint8_t* q2, const uint16_t* s2, const uint16_t* z2, int d, int f,
+                        uint32_t* out2) {
+    hipLaunchKernelGGL(w2_stats_q4_kernel, dim3(d < 2048 ? d : 2048), dim3(kThreads), 0, st, q2, s2, z2, d, f, out2);
 }
 
 void launch_pack_expert_f32(hipStream_t st, const void* w1, const void* w3, const void* w2, int d,

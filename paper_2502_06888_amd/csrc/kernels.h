@@ -72,9 +72,14 @@ void launch_w2_stats(hipStream_t st, const void* w2, int d, int f, uint32_t* out
 void launch_zero_u64(hipStream_t st, unsigned long long* p, size_t n);
 // The same for a 4-bit group-quantised expert: codes [rows, cols/2] (even column in the low
 // nibble), scales and zero points [rows, cols/64] as bf16, for W1, W3 ([f, d]) and W2 ([d, f]).
+// w2_scale (a power of two) multiplies the scales of W2's groups, so that the dequantised weights
+// fit the fp16 range of the down projection (launch_w2_stats_q4 gives the range).
 void launch_pack_expert_q4(hipStream_t st, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
                            const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
-                           const uint16_t* s2, const uint16_t* z2, int d, int f, void* blob);
+                           const uint16_t* s2, const uint16_t* z2, int d, int f, void* blob, float w2_scale);
+// As launch_w2_stats for a 4-bit W2 [d, f]: the dequantised weights bf16(fma(code, s, -z*s)).
+void launch_w2_stats_q4(hipStream_t st, const uint8_t* q2, const uint16_t* s2, const uint16_t* z2, int d, int f,
+                        uint32_t* out2);
 // Gather token rows per expert (and the plain rows for shared experts) into fragment order.
 // Also zeroes herr (remainder energy per H row of this call).
 void launch_gather_bf16(hipStream_t st, const void* x, const Shape& s, const PlanPtrs& p,
@@ -100,10 +105,9 @@ struct FfnArgs {
     int32_t max_tiles;           // tiles the grid was sized for
     int32_t est_tiles;           // tiles the host expects to be live (launch-shape heuristic)
     int32_t d, f;
-    int32_t h_mode;              // format of H between the projections.  0: fp16 value plane + fp16 remainder
-                                 // plane, the remainder multiplied only by tiles whose recorded remainder
-                                 // energy asks for it; 1: the same, remainder always multiplied;
-                                 // 2: bf16 value + bf16 remainder, both always (4-bit experts)
+    int32_t h_mode;              // H travels as an fp16 value plane + an fp16 remainder plane.  0: the remainder
+                                 // is multiplied only by tiles whose recorded remainder energy asks for it;
+                                 // 1: always
     int64_t h_plane_units;       // 16-byte units between the value plane and the remainder plane of H
     unsigned long long* herr;    // per H row: remainder energy in units of threshold / 2^20 (h_mode 0)
     const float2* wmeta;         // per expert of the layer: (output scale of the down projection, 1 / threshold)

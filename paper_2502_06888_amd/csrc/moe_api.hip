@@ -647,6 +647,33 @@ moe_status moe_set_gate(moe_ctx* ctx, int32_t layer, const void* wg_dev) {
 
 namespace {
 
+// Range and row energy of an expert's W2, taken on the device by `stats` (two words: bits of the
+// largest |w|, bits of the largest row sum of squares), turned into the power of two that brings
+// W2 into the fp16 range (*w2_scale, applied at packing; its inverse goes to meta->x and is
+// applied to the outputs) and into 1 / threshold of the remainder energy (meta->y, see kErrBudget).
+template <typename StatsFn>
+moe_status w2_placement_figures(moe_ctx* ctx, int layer, int expert, StatsFn stats, float* w2_scale, float2* meta) {
+    const int f = ctx->cfg.d_ff, S = ctx->cfg.n_shared;
+    uint32_t* stats_dev = (uint32_t*)(ctx->ws + ctx->L.meta) + 8;  // two spare words of the meta block
+    uint32_t st[2] = {0, 0};
+    HIP_TRY(ctx, hipMemsetAsync(stats_dev, 0, 8, ctx->compute));
+    stats(stats_dev);
+    HIP_TRY(ctx, hipGetLastError());
+    HIP_TRY(ctx, hipMemcpyAsync(st, stats_dev, 8, hipMemcpyDeviceToHost, ctx->compute));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+    if (st[0] >= 0x7f800000u || st[1] >= 0x7f800000u)
+        return fail(ctx, MOE_ERR_SHAPE, "W2 of layer %d expert %d holds non-finite weights (or its row energy overflows)", layer, expert);
+    float amax, rowsq;
+    memcpy(&amax, &st[0], 4);
+    memcpy(&rowsq, &st[1], 4);
+    int shift = 0;
+    while (std::ldexp((double)amax, -shift) > 65504.0) ++shift;
+    *w2_scale = (float)std::ldexp(1.0, -shift);
+    const double inv_tau = kSigmas * kSigmas * (1.0 + S) * (double)rowsq / ((double)f * kErrBudget * kErrBudget);
+    *meta = make_float2((float)std::ldexp(1.0, shift), (float)std::min(inv_tau, 3.0e38));
+    return MOE_OK;
+}
+
 // Common part of expert placement: validation, staging through window slot 0 for pinned
 // destinations, the pack launches (given as a callable), bookkeeping of where the blob lives.
 template <typename PackFn>
@@ -706,25 +733,10 @@ moe_status moe_set_expert(moe_ctx* ctx, int32_t layer, int32_t expert, const voi
     float2 meta = make_float2(1.f, 0.f);
     float w2_scale = 1.f;
     if (ctx->cfg.dtype == MOE_BF16) {
-        // range and row energy of W2: the power of two that brings it into the fp16 range, and the
-        // threshold below which the remainder plane of H need not be multiplied (see kErrBudget)
-        uint32_t* stats_dev = (uint32_t*)(ctx->ws + ctx->L.meta) + 8;  // two spare words of the meta block
-        uint32_t stats[2] = {0, 0};
-        HIP_TRY(ctx, hipMemsetAsync(stats_dev, 0, 8, ctx->compute));
-        launch_w2_stats(ctx->compute, w2_dev, d, f, stats_dev);
-        HIP_TRY(ctx, hipGetLastError());
-        HIP_TRY(ctx, hipMemcpyAsync(stats, stats_dev, 8, hipMemcpyDeviceToHost, ctx->compute));
-        HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
-        if (stats[0] >= 0x7f800000u || stats[1] >= 0x7f800000u)
-            return fail(ctx, MOE_ERR_SHAPE, "W2 of layer %d expert %d holds non-finite weights (or its row energy overflows)", layer, expert);
-        float amax, rowsq;
-        memcpy(&amax, &stats[0], 4);
-        memcpy(&rowsq, &stats[1], 4);
-        int shift = 0;
-        while (std::ldexp((double)amax, -shift) > 65504.0) ++shift;
-        w2_scale = (float)std::ldexp(1.0, -shift);
-        const double inv_tau = kSigmas * kSigmas * (1.0 + S) * (double)rowsq / ((double)f * kErrBudget * kErrBudget);
-        meta = make_float2((float)std::ldexp(1.0, shift), (float)std::min(inv_tau, 3.0e38));
+        moe_status ws = w2_placement_figures(ctx, layer, expert, [&](uint32_t* stats_dev) {
+            launch_w2_stats(ctx->compute, w2_dev, d, f, stats_dev);
+        }, &w2_scale, &meta);
+        if (ws != MOE_OK) return ws;
     }
     moe_status st = place_expert(ctx, layer, expert, where, packed_dst, [&](void* to) {
         if (ctx->cfg.dtype == MOE_BF16)
@@ -749,12 +761,24 @@ moe_status moe_set_expert_q4(moe_ctx* ctx, int32_t layer, int32_t expert, const 
     for (const void* p : all)
         if (((uintptr_t)p & 3u) != 0) return fail(ctx, MOE_ERR_INVALID_ARG, "quantised tensors must be 4-byte aligned");
     const int d = ctx->cfg.d_model, f = ctx->cfg.d_ff;
-    return place_expert(ctx, layer, expert, where, packed_dst, [&](void* to) {
+    const int E = ctx->cfg.n_experts, S = ctx->cfg.n_shared;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (expert < 0 || expert >= E + S) return fail(ctx, MOE_ERR_INVALID_ARG, "expert %d out of range", expert);
+    float2 meta = make_float2(1.f, 0.f);
+    float w2_scale = 1.f;
+    moe_status ws = w2_placement_figures(ctx, layer, expert, [&](uint32_t* stats_dev) {
+        launch_w2_stats_q4(ctx->compute, (const uint8_t*)q2_dev, (const uint16_t*)s2_dev, (const uint16_t*)z2_dev, d, f, stats_dev);
+    }, &w2_scale, &meta);
+    if (ws != MOE_OK) return ws;
+    moe_status st = place_expert(ctx, layer, expert, where, packed_dst, [&](void* to) {
         launch_pack_expert_q4(ctx->compute, (const uint8_t*)q1_dev, (const uint16_t*)s1_dev,
                               (const uint16_t*)z1_dev, (const uint8_t*)q3_dev, (const uint16_t*)s3_dev,
                               (const uint16_t*)z3_dev, (const uint8_t*)q2_dev, (const uint16_t*)s2_dev,
-                              (const uint16_t*)z2_dev, d, f, to);
+                              (const uint16_t*)z2_dev, d, f, to, w2_scale);
     });
+    if (st != MOE_OK) return st;
+    HIP_TRY(ctx, hipMemcpy((void*)(ctx->wmeta_dev + (size_t)layer * (E + S) + expert), &meta, 8, hipMemcpyHostToDevice));
+    return MOE_OK;
 }
 
 moe_status moe_route(moe_ctx* ctx, int32_t layer, const void* x_dev,
@@ -905,7 +929,7 @@ moe_status moe_layer_forward(moe_ctx* ctx, int32_t layer, const void* x_dev, voi
     a.variant = ctx->variant % 10;
     a.panel = ctx->variant / 10;
     a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
-    a.h_mode = ctx->cfg.weight_bits == 4 ? 2 : ctx->h_mode;
+    a.h_mode = ctx->h_mode;
     a.h_plane_units = ctx->L.h_plane_units;
     a.herr = (unsigned long long*)(w + ctx->L.herr);
     a.wmeta = ctx->wmeta_dev + (size_t)layer * (E + S);
@@ -1274,7 +1298,7 @@ moe_status moe_measure(moe_ctx* ctx, int32_t layer, const void* x_dev,
         a.variant = ctx->variant % 10;
         a.panel = ctx->variant / 10;
         a.full_tiles = ((int64_t)N * s.k / std::max(1, E) > 160) ? 1 : 0;
-        a.h_mode = ctx->cfg.weight_bits == 4 ? 2 : ctx->h_mode;
+        a.h_mode = ctx->h_mode;
         a.h_plane_units = ctx->L.h_plane_units;
         a.herr = (unsigned long long*)(w + ctx->L.herr);
         a.wmeta = ctx->wmeta_dev + (size_t)layer * (E + S);
