@@ -389,6 +389,25 @@ def test_per_tile_choice_holds_the_tolerance_across_output_scales():
     assert taken == sorted(taken), taken
 
 
+def test_intermediate_values_beyond_the_fp16_range_are_clamped_and_counted():
+    """Activations so large that silu(gate) * up leaves the fp16 range (|h| > 65504): the values are
+    clamped, counted in the stats, and the outputs stay finite.  (No comparison with the oracle:
+    a layer that saturates its intermediate is outside what the format serves.)"""
+    w = SMALL
+    data, _ = I.gen_layer(w, 0)
+    d2 = I.LayerData(x=I.to_storage(I.as_f32(data.x) * 400.0, "bf16"), wg=data.wg, w1=data.w1, w3=data.w3, w2=data.w2)
+    ctx = H.make_ctx(w)
+    H.place_layer(ctx, w, 0, d2)
+    ctx.reset_stats()
+    got = H.gpu_layer(ctx, w, 0, d2.x, w.batch_offsets)
+    assert np.all(np.isfinite(got["y"]))
+    assert ctx.stats()["h_saturated"] > 0
+    ctx.reset_stats()
+    got = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)      # the same context on sane inputs: nothing clamped
+    assert ctx.stats()["h_saturated"] == 0
+    ctx.close()
+
+
 def test_weights_beyond_the_fp16_range_are_placed_scaled():
     """W2 is placed as fp16.  An expert whose W2 holds a weight beyond 65504 is stored times a
     power of two that brings it into range (exact), and the outputs are scaled back: same oracle,
