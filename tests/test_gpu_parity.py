@@ -148,6 +148,21 @@ def test_mixtral_decode_full_size_every_output(mixtral_layer):
     assert got["counts"].sum() == 1024 and (got["counts"] > 0).all()
 
 
+def test_mixtral_decode_shape_with_skewed_routing(mixtral_layer):
+    """The decode layer's weights with a batch group whose routing is lopsided: every token has
+    expert 3 among its two (built by repeating the layer's own tokens that route there), so that
+    one expert owns 512 rows (two full tiles) while the others get ragged tiles of every size, at the
+    full reduction depths (4096 and 14336).  Every output against the oracle."""
+    w, data, ctx = mixtral_layer
+    base = H.gpu_layer(ctx, w, 0, data.x, w.batch_offsets)
+    mine = np.nonzero((base["idx"] == 3).any(axis=1))[0]
+    assert 100 < mine.size < 200
+    pick = torch.from_numpy(np.resize(mine, w.n_tokens))       # the same tokens over and over, 512 rows
+    d2 = I.LayerData(x=data.x[pick], wg=data.wg, w1=data.w1, w3=data.w3, w2=data.w2)
+    got, want, err = run_case(w, data=d2, ctx=ctx)
+    assert got["counts"][3] == w.n_tokens and sorted(got["counts"])[-2] < 256
+
+
 def test_remainder_plane_is_skipped_at_the_decode_layer_and_both_modes_agree(mixtral_layer):
     """H travels as fp16 plus an fp16 plane with its rounding remainder.  At the decode layer's
     output scale the remainders' recorded energy stays under every expert's threshold, so the
