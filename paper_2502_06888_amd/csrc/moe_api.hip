@@ -615,7 +615,7 @@ moe_status moe_create(const moe_config* cfg, void* compute_stream, void* copy_st
 
 moe_status moe_destroy(moe_ctx* ctx) {
     if (!ctx) return MOE_OK;
-    if (ctx->compute || true) (void)hipStreamSynchronize(ctx->compute);
+    (void)hipStreamSynchronize(ctx->compute);  // a null handle is the default stream
     if (ctx->copy != ctx->compute) (void)hipStreamSynchronize(ctx->copy);
     for (hipStream_t cs : ctx->copy_extra) {
         (void)hipStreamSynchronize(cs);
