@@ -504,7 +504,11 @@ def bench_resident(w, args, data=None, steps=None, warmup=None, with_cpu_baselin
             trip = I.gen_expert_q4(w, 0, e)
             ctx.set_expert_q4(0, e, tuple(tuple(t.to(dev) for t in m) for m in trip))
         else:
-            ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
+            if args.zero_weights:   # power probe: the same launches, addresses and traffic, all products zero
+                z1, z2 = torch.zeros_like(data.w1[e], device=dev), torch.zeros_like(data.w2[e], device=dev)
+                ctx.set_expert(0, e, z1, z1, z2)
+            else:
+                ctx.set_expert(0, e, data.w1[e].to(dev), data.w3[e].to(dev), data.w2[e].to(dev))
     x = data.x.to(dev)
     y = torch.empty((w.n_tokens, w.d_model), dtype=w.torch_dtype, device=dev)
     bo = [int(v) for v in w.batch_offsets]
@@ -601,7 +605,9 @@ def bench_resident(w, args, data=None, steps=None, warmup=None, with_cpu_baselin
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "d_model": w.d_model, "d_ff": w.d_ff,
                    "n_experts": w.n_experts, "top_k": w.top_k, "n_batches": w.n_batches,
-                   "tokens": w.n_tokens, "experts": "resident in HBM", "weight_bits": args.weight_bits,
+                   "tokens": w.n_tokens,
+                   "experts": "resident in HBM" + (", all-zero weights (power probe)" if args.zero_weights else ""),
+                   "weight_bits": args.weight_bits,
                    "n_active": n_active,
                    "h_format": "f32" if w.dtype == "f32" else
                                "fp16 + fp16 remainder plane (" + ("always multiplied" if args.h_planes == 2
@@ -653,6 +659,10 @@ def main():
     ap.add_argument("--plan", action="store_true",
                     help="streamed stacks: run the planner's measurement stage on layer 0, solve the "
                          "overlap inequalities for n, and sweep the number of batches per group")
+    ap.add_argument("--zero-weights", action="store_true",
+                    help="resident workloads: place all-zero expert weights (routing, launches and memory "
+                         "traffic unchanged, every product zero): what remains of the step time shows how much "
+                         "of it the data-dependent power of the matrix cores costs through the clock")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel before the "
                          "timed region, so that a counter run has a kernel of known traffic")
