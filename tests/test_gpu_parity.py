@@ -57,7 +57,36 @@ def test_bf16_small_shapes(w):
     run_case(w)
 
 
-@pytest.mark.parametrize("w", [I.WORKLOADS["tiny_f32"], SMALL], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [
+    I.scaled(SMALL, name="large_group_ragged", d_model=1024, d_ff=64, n_experts=8, top_k=3,
+             batch_tokens=(4099, 0, 4096), w_std=0.04),
+    I.scaled(SMALL, name="large_group_many_experts", d_model=2048, d_ff=64, n_experts=72, top_k=4,
+             batch_tokens=(8193,), w_std=0.03),
+    I.scaled(SMALL, name="large_group_other_router", d_model=1024, d_ff=64, n_experts=10, top_k=2,
+             batch_tokens=(8200,), w_std=0.04),
+    I.scaled(SMALL, name="large_group_k_equals_E", d_model=1024, d_ff=64, n_experts=8, top_k=8,
+             batch_tokens=(8192,), w_std=0.04),
+    I.scaled(SMALL, name="mid_group_few_experts", d_model=256, d_ff=64, n_experts=6, top_k=2,
+             batch_tokens=(1500, 1501)),
+    I.scaled(I.WORKLOADS["tiny_f32"], name="mid_group_f32", d_model=128, d_ff=64, n_experts=5, top_k=3,
+             batch_tokens=(2100,), w_std=0.1),
+], ids=lambda w: w.name)
+def test_large_batch_groups_route_bit_exactly(w):
+    """Batch groups of 8192 tokens and more take, where the shape allows, the router in which one
+    wavefront serves several tokens: token counts that leave its last wavefront partly empty,
+    several expert groups and more experts than a wavefront has lanes; and a shape it does not
+    serve (experts not in whole groups), which the one-token-per-wavefront router takes, as do
+    groups between 2049 and 8191 tokens (there with so few experts that the selection runs in
+    registers, bf16 and fp32).  Logits, top-k, weights and the whole dispatch plan bit for bit,
+    every output within the tolerance."""
+    run_case(w)
+
+
+@pytest.mark.parametrize("w", [
+    I.WORKLOADS["tiny_f32"], SMALL,
+    I.scaled(SMALL, name="large_group_plain_softmax", d_model=1024, d_ff=64, n_experts=8, top_k=2,
+             batch_tokens=(8190, 7), w_std=0.04),
+], ids=lambda w: w.name)
 def test_full_softmax_weights_without_renormalisation(w):
     """renormalize = 0: routing weights are the full-softmax probabilities of the winners."""
     data, _ = I.gen_layer(w, 0)
