@@ -425,6 +425,13 @@ __global__ __launch_bounds__(kSW * 64) void router_split_kernel(
     }
     __syncthreads();
     if (wave != 0) return;
+    if (E <= kEG && renorm) {  // few experts: every lane reads them all and selects in registers
+        float lg[kEG];
+#pragma unroll
+        for (int e = 0; e < kEG; ++e) lg[e] = e < E ? slog[e] : 0.f;
+        select_uniform_and_write(lg, E, lane, t, k, idx_out, w_out);
+        return;
+    }
     float mine[4];
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) mine[s4] = lane + 64 * s4 < E ? slog[lane + 64 * s4] : 0.f;
