@@ -10,6 +10,8 @@
 // the same lane.  For the down projection (reduction over f) position i is feature
 // 16*ks + 8*(i/4) + 4*hi + i%4, which is exactly how those values fall in the up kernel's
 // accumulator registers, so H never needs a shuffle between the two GEMMs.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace kmoe {
@@ -262,37 +264,61 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const uint4* __restrict_
 // ---- per-call gather of token rows into fragment order -------------------------------------
 // Xp: [row block][ks = d/16][lane 64] x 16 B.  Routed blocks follow the padded per-expert row
 // space; the rows of shared experts (all tokens, natural order) follow them.
+// A wavefront takes one row block and `quads` groups of four reduction steps (one group on small
+// layers, so that there are wavefronts for every compute unit; up to kGatherQuads on large ones,
+// where the look-ups are then shared by more traffic).  Per group it
+// moves four fragments (4 KiB) with four loads and four stores per lane, laid out so that both
+// sides work in whole 128-byte lines: lane (r = lane / 8, c = lane % 8) reads, for rows r, r + 8,
+// r + 16, r + 24 of the block, the 16 bytes c of the row's 128-byte piece (step c / 2 of the
+// group, half c % 2), and eight consecutive lanes store eight consecutive 16-byte units of one
+// fragment.  The token of a row is looked up once per wavefront item, not once per unit.
+constexpr int kGatherQuads = 8;
 __global__ __launch_bounds__(kThreads) void gather_kernel(const uint16_t* __restrict__ x, Shape s,
                                                           PlanPtrs p, uint4* __restrict__ xp,
-                                                          unsigned long long* __restrict__ herr) {
-    const int nks = s.d / 16;
+                                                          unsigned long long* __restrict__ herr, int quads) {
+    const int nks = s.d / 16;  // a multiple of 4: the bf16 path needs d_model % 64 == 0
     const int routed_blks = p.meta[2];
     const int shared_blks = s.S > 0 ? (s.N + kRowBlk - 1) / kRowBlk : 0;
     // the up kernel adds the remainder energy of every H row of this call to herr: start at zero
     const size_t h_rows = ((size_t)routed_blks + (size_t)s.S * ((s.N + kRowBlk - 1) / kRowBlk)) * kRowBlk;
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < h_rows; i += (size_t)gridDim.x * kThreads)
         herr[i] = 0ull;
-    const size_t units = (size_t)(routed_blks + shared_blks) * nks * 64;
-    for (size_t u = (size_t)blockIdx.x * kThreads + threadIdx.x; u < units;
-         u += (size_t)gridDim.x * kThreads) {
-        const int lane = (int)(u & 63);
-        const size_t q = u >> 6;
-        const int ks = (int)(q % nks);
-        const int blk = (int)(q / nks);
-        const int j = lane & 31, hi = lane >> 5;
-        int token = -1;
+    const int nquads = nks / 4;
+    const int groups = (nquads + quads - 1) / quads;
+    const int lane = threadIdx.x & 63, r = lane >> 3, c = lane & 7;
+    const int waves = kThreads / 64;
+    const long items = (long)(routed_blks + shared_blks) * groups;
+    for (long item = (long)blockIdx.x * waves + (threadIdx.x >> 6); item < items; item += (long)gridDim.x * waves) {
+        const int blk = (int)(item / groups), g = (int)(item % groups);
+        // tokens of rows r, r + 8, r + 16, r + 24: the block's expert and its offsets once, then the
+        // four look-ups side by side (clamped indices, no branch between them)
+        const uint16_t* src[4];
         if (blk < routed_blks) {
             const int e = p.blk_expert[blk];
-            const int rank = blk * kRowBlk + j - p.poff[e];
-            if (rank < p.counts[e]) token = p.perm[p.offsets[e] + rank] / s.k;
+            const int first = blk * kRowBlk - p.poff[e], cnt = p.counts[e], off = p.offsets[e];
+            int a[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = p.perm[off + min(first + i * 8 + r, cnt - 1)];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                src[i] = first + i * 8 + r < cnt ? x + (size_t)(a[i] / s.k) * s.d + c * 8 : nullptr;
         } else {
-            const int t = (blk - routed_blks) * kRowBlk + j;
-            if (t < s.N) token = t;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = (blk - routed_blks) * kRowBlk + i * 8 + r;
+                src[i] = t < s.N ? x + (size_t)t * s.d + c * 8 : nullptr;
+            }
         }
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (token >= 0)
-            v = *reinterpret_cast<const uint4*>(x + (size_t)token * s.d + ks * 16 + hi * 8);
-        xp[u] = v;
+        uint4* dst = xp + ((size_t)blk * nks) * 64 + (size_t)(c >> 1) * 64 + (c & 1) * 32 + r;
+        const int q1 = min((g + 1) * quads, nquads);
+        for (int q = g * quads; q < q1; ++q) {
+            uint4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                v[i] = src[i] ? *reinterpret_cast<const uint4*>(src[i] + (size_t)q * 64) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dst[(size_t)q * 256 + i * 8] = v[i];
+        }
     }
 }
 
@@ -304,6 +330,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float v) {
     return (uint16_t)(u >> 16);
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));  // first-class 16-byte value for streaming loads
+
+// A wavefront item is one token x kCombineCols float4 columns per lane: the token's rows and routing
+// weights are looked up once per item (uniform over the wavefront), and all partial rows of the
+// item are requested before the first addition.  O is read exactly once: streaming loads.
+constexpr int kCombineCols = 2;
 template <bool kBf16Out>
 __global__ __launch_bounds__(kThreads) void combine_kernel(Shape s, PlanPtrs p,
                                                            const float* __restrict__ o, int split_k,
@@ -312,43 +344,68 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(Shape s, PlanPtrs p,
     const int d4 = s.d / 4;
     const int shared_stride_rows = (s.N + kRowBlk - 1) / kRowBlk * kRowBlk;
     const int shared_row0 = p.meta[2] * kRowBlk;  // shared experts' rows follow the routed ones
-    const size_t total = (size_t)s.N * d4;
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total;
-         i += (size_t)gridDim.x * kThreads) {
-        const int t = (int)(i / d4);
-        const int c = (int)(i % d4) * 4;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int lane = threadIdx.x & 63, waves = kThreads / 64;
+    const int chunks = (d4 + 64 * kCombineCols - 1) / (64 * kCombineCols);
+    const long items = (long)s.N * chunks;
+    for (long item = (long)blockIdx.x * waves + (threadIdx.x >> 6); item < items; item += (long)gridDim.x * waves) {
+        const int t = (int)(item / chunks), ch = (int)(item % chunks);
+        float4 acc[kCombineCols];
+        int col[kCombineCols];
+#pragma unroll
+        for (int u = 0; u < kCombineCols; ++u) {
+            acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            col[u] = (ch * kCombineCols + u) * 64 + lane;  // float4 column of this lane
+        }
         for (int j = 0; j < s.k; ++j) {  // routed slots in order j = 0..k-1
             const int a = t * s.k + j;
             const int e = p.topk_idx[a];
             const int row = p.poff[e] + (p.inv_perm[a] - p.offsets[e]);
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int sp = 0; sp < split_k; ++sp) {
-                const float4 q = *reinterpret_cast<const float4*>(
-                    o + (size_t)sp * split_stride + (size_t)row * s.d + c);
-                v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
-            }
             const float w = p.topk_w[a];
-            acc.x = __builtin_fmaf(w, v.x, acc.x);
-            acc.y = __builtin_fmaf(w, v.y, acc.y);
-            acc.z = __builtin_fmaf(w, v.z, acc.z);
-            acc.w = __builtin_fmaf(w, v.w, acc.w);
+            float4 v[kCombineCols];
+#pragma unroll
+            for (int u = 0; u < kCombineCols; ++u) v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int sp = 0; sp < split_k; ++sp) {
+                const float4* src = reinterpret_cast<const float4*>(o + (size_t)sp * split_stride + (size_t)row * s.d);
+#pragma unroll
+                for (int u = 0; u < kCombineCols; ++u) {
+                    if (col[u] < d4) {
+                        const f32x4 q = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + col[u]));
+                        v[u].x += q.x; v[u].y += q.y; v[u].z += q.z; v[u].w += q.w;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kCombineCols; ++u) {
+                acc[u].x = __builtin_fmaf(w, v[u].x, acc[u].x);
+                acc[u].y = __builtin_fmaf(w, v[u].y, acc[u].y);
+                acc[u].z = __builtin_fmaf(w, v[u].z, acc[u].z);
+                acc[u].w = __builtin_fmaf(w, v[u].w, acc[u].w);
+            }
         }
         for (int sh = 0; sh < s.S; ++sh) {  // then the always-on experts, weight 1
             const size_t row = (size_t)shared_row0 + (size_t)sh * shared_stride_rows + t;
             for (int sp = 0; sp < split_k; ++sp) {
-                const float4 q = *reinterpret_cast<const float4*>(
-                    o + (size_t)sp * split_stride + row * s.d + c);
-                acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
+                const float4* src = reinterpret_cast<const float4*>(o + (size_t)sp * split_stride + row * s.d);
+#pragma unroll
+                for (int u = 0; u < kCombineCols; ++u) {
+                    if (col[u] < d4) {
+                        const f32x4 q = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + col[u]));
+                        acc[u].x += q.x; acc[u].y += q.y; acc[u].z += q.z; acc[u].w += q.w;
+                    }
+                }
             }
         }
-        if (kBf16Out) {
-            uint2 r;
-            r.x = (uint32_t)f32_to_bf16_rne(acc.x) | ((uint32_t)f32_to_bf16_rne(acc.y) << 16);
-            r.y = (uint32_t)f32_to_bf16_rne(acc.z) | ((uint32_t)f32_to_bf16_rne(acc.w) << 16);
-            *reinterpret_cast<uint2*>((uint16_t*)y + (size_t)t * s.d + c) = r;
-        } else {
-            *reinterpret_cast<float4*>((float*)y + (size_t)t * s.d + c) = acc;
+#pragma unroll
+        for (int u = 0; u < kCombineCols; ++u) {
+            if (col[u] >= d4) continue;
+            if (kBf16Out) {
+                uint2 r;
+                r.x = (uint32_t)f32_to_bf16_rne(acc[u].x) | ((uint32_t)f32_to_bf16_rne(acc[u].y) << 16);
+                r.y = (uint32_t)f32_to_bf16_rne(acc[u].z) | ((uint32_t)f32_to_bf16_rne(acc[u].w) << 16);
+                *reinterpret_cast<uint2*>((uint16_t*)y + (size_t)t * s.d + (size_t)col[u] * 4) = r;
+            } else {
+                *reinterpret_cast<float4*>((float*)y + (size_t)t * s.d + (size_t)col[u] * 4) = acc[u];
+            }
         }
     }
 }
@@ -416,14 +473,23 @@ void launch_gather_bf16(hipStream_t st, const void* x, const Shape& s, const Pla
     if (s.N <= 0) return;
     const size_t max_units =
         ((size_t)s.max_rowblks + (s.S > 0 ? (s.N + kRowBlk - 1) / kRowBlk : 0)) * (s.d / 16) * 64;
-    hipLaunchKernelGGL(gather_kernel, dim3(grid_for(max_units, 2048)), dim3(kThreads), 0, st,
-                       (const uint16_t*)x, s, p, (uint4*)xp, herr);
+    // a wavefront item is 4 * quads fragments of 64 units; four wavefronts per workgroup; at least
+    // some thousands of items, so that every compute unit has several wavefronts in flight
+    const size_t blocks_now = std::min<size_t>((size_t)s.max_rowblks, ((size_t)s.N * s.k + kRowBlk - 1) / kRowBlk + s.E) +
+                              (s.S > 0 ? (s.N + kRowBlk - 1) / kRowBlk : 0);
+    const size_t total_quads = blocks_now * (s.d / 64);
+    int quads = (int)(total_quads / 4096);
+    quads = quads < 1 ? 1 : (quads > kGatherQuads ? kGatherQuads : quads);
+    hipLaunchKernelGGL(gather_kernel, dim3(grid_for(max_units / (4 * quads) + kThreads, 2048)), dim3(kThreads), 0, st,
+                       (const uint16_t*)x, s, p, (uint4*)xp, herr, quads);
 }
 
 void launch_combine(hipStream_t st, int out_dtype, const Shape& s, const PlanPtrs& p,
                     const float* o, int split_k, int64_t o_split_stride, void* y) {
     if (s.N <= 0) return;
-    const dim3 grid(grid_for((size_t)s.N * (s.d / 4), 8192)), block(kThreads);
+    // one wavefront per (token, 64 * kCombineCols float4 columns)
+    const int chunks = (s.d / 4 + 64 * kCombineCols - 1) / (64 * kCombineCols);
+    const dim3 grid(grid_for((size_t)s.N * chunks * 64, 8192)), block(kThreads);
     if (out_dtype == 1)
         hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, st, s, p, o, split_k,
                            o_split_stride, y);
