@@ -48,6 +48,20 @@ __device__ __forceinline__ gptr as_global(const void* p) { return (gptr)(uintptr
 // taking cache lines that the re-read activations need, and measurably raises the HBM rate.
 __device__ __forceinline__ u32x4 load_stream(gptr p) { return __builtin_nontemporal_load(p); }
 
+// The activations of a tile are loaded through a buffer descriptor: the address of a load is then
+// a scalar byte offset (kept and advanced by the scalar unit) plus the lane's constant 16-byte
+// slot, and costs no vector instruction.  (Through plain pointers every activation load of the
+// reduction loop cost a 64-bit vector add; with one wavefront per SIMD those adds sit between
+// the MFMAs.  The weight stream stays on plain non-temporal loads: through a descriptor it
+// streamed measurably slower from HBM.)  A descriptor covers the live row blocks of one plane.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(gptr base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(uintptr_t)base, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load(rsrc_t r, uint32_t byte_offset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (threadIdx.x & 63u) * 16u, byte_offset, 0);
+}
+
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // One LDS stage holds, per row block, SX reduction steps of 16 for PL planes of the activations
@@ -58,11 +72,21 @@ struct TileCtx {
     size_t ustride;  // 16-byte units between the streams of consecutive output units
     gptr actbase;    // packed activations at the tile's first row block (plane 0)
     size_t plane;    // units between activation planes
+    rsrc_t ars[2];   // descriptors of the tile's activations, plane 0 and plane 1 (bind_activations)
     u32x4* lds;
     int nks;         // reduction steps of 16 in the whole reduction
     int k0, k1;      // reduction steps of this workgroup: [k0, k1), k0 a multiple of SX
     int nblk;        // live row blocks of the tile
 };
+
+// Descriptors of the tile's activations: the live row blocks of each plane (at most 8 blocks of
+// nks KiB: far below the 4 GiB a descriptor's offsets reach).  The scalar offset of a load is not
+// range-checked by the hardware; it is in bounds by the same argument as the pointer it replaces.
+__device__ __forceinline__ void bind_activations(TileCtx& c) {
+    const uint32_t bytes = (uint32_t)c.nblk * (uint32_t)c.nks * 1024u;
+    c.ars[0] = make_rsrc(c.actbase, bytes);
+    c.ars[1] = make_rsrc(c.actbase + c.plane, bytes);
+}
 
 // Unit u of a stage is (row block b, plane pl, step j, lane): u = ((b*PL + pl)*SX + j)*64 + lane.
 // Lanes past the live part of the tile re-read unit 0, steps past the end of the reduction
@@ -77,8 +101,9 @@ struct TileCtx {
 template <int PASSES, int T, int SX, int PL>
 struct XMap {
     static_assert(T % 64 == 0 && kBlkStageUnits % 64 == 0, "a pass of a wavefront is one fragment");
-    size_t base[PASSES];  // units from actbase to (row block, plane) of pass p at step 0, uniform
-    int step[PASSES];     // step of the stage, uniform
+    uint32_t off[PASSES];  // bytes from the plane's start to the row block of pass p at step 0, uniform
+    int pl[PASSES];        // plane of pass p, uniform
+    int step[PASSES];      // step of the stage, uniform
     __device__ __forceinline__ void init(const TileCtx& c) {
         const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
         const int live = c.nblk * (kBlkStageUnits / 64);
@@ -87,7 +112,8 @@ struct XMap {
             int fr = wave + p * (T / 64);  // fragment of the stage; past the live part: fragment 0
             fr = fr < live ? fr : 0;
             const int b = fr / (kBlkStageUnits / 64), r = fr % (kBlkStageUnits / 64);
-            base[p] = (size_t)(r / SX) * c.plane + (size_t)b * c.nks * 64;
+            off[p] = (uint32_t)b * (uint32_t)c.nks * 1024u;
+            pl[p] = r / SX;
             step[p] = r % SX;
         }
     }
@@ -96,7 +122,7 @@ struct XMap {
     template <bool CLAMP>
     __device__ __forceinline__ u32x4 load(const TileCtx& c, int p, int kbase) const {
         const int ks = CLAMP ? min(kbase + step[p], c.nks - 1) : kbase + step[p];
-        return (c.actbase + base[p] + (size_t)ks * 64)[threadIdx.x & 63];
+        return buf_load(PL == 1 || pl[p] == 0 ? c.ars[0] : c.ars[1], off[p] + (uint32_t)ks * 1024u);
     }
 };
 
@@ -564,6 +590,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_kernel(FfnArgs a, int n_gro
     c.k0 = 0;
     c.k1 = c.nks;
     c.nblk = nblk;
+    bind_activations(c);
 #define CALL(NB) run_tile<0, NB, WAVES, U, 1>(a, c, as_global(blob), a.f / 16, w.grp, hblk0, 0, e, 1.f)
     NB_SWITCH(CALL)
 #undef CALL
@@ -606,6 +633,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_kernel(FfnArgs a, int n_g
     c.plane = (size_t)a.h_plane_units;
     c.lds = lds;
     c.nblk = nblk;
+    bind_activations(c);
     const gptr wsec = as_global(blob + (size_t)a.d * a.f * 4);
     if (two) {
         constexpr int SX = 4;
@@ -828,6 +856,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_up_q4_kernel(FfnArgs a, int n_
     c.k0 = 0;
     c.k1 = c.nks;
     c.nblk = nblk;
+    bind_activations(c);
     const size_t df = (size_t)a.d * a.f;
 #define CALL(NB) run_tile_q4<0, NB, WAVES, 1>(a, c, blob, blob + df, a.f / 16, w.grp, hblk0, 0, e, 1.f)
     NB_SWITCH(CALL)
@@ -854,6 +883,7 @@ __global__ __launch_bounds__(WAVES * 64) void ffn_down_q4_kernel(FfnArgs a, int 
     c.plane = (size_t)a.h_plane_units;
     c.lds = lds;
     c.nblk = nblk;
+    bind_activations(c);
     const size_t df = (size_t)a.d * a.f;
     const uint8_t* down = blob + df + df / 8;
     if (two) {
