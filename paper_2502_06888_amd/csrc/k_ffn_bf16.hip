@@ -248,7 +248,9 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
 template <int NB, int WAVES, int U>
 struct Shape2 {
     static constexpr int RING = (U == 1) ? (NB <= 5 ? 16 : 8) : 8;
-    static constexpr int DX = (NB <= 5) ? 2 : 1;
+    // two stages ahead wherever the registers allow: small tiles, and the two-unit shape (one
+    // wavefront per SIMD, accumulators in AGPRs), whose full tiles miss L2 most often
+    static constexpr int DX = (NB <= 5 || U == 2) ? 2 : 1;
 };
 
 // Registers of the software pipeline of one tile pass: the weight ring (RS stages of SX steps,
