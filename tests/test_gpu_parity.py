@@ -66,6 +66,8 @@ def test_bf16_small_shapes(w):
              batch_tokens=(8200,), w_std=0.04),
     I.scaled(SMALL, name="large_group_k_equals_E", d_model=1024, d_ff=64, n_experts=8, top_k=8,
              batch_tokens=(8192,), w_std=0.04),
+    I.scaled(SMALL, name="large_group_shared_experts", d_model=512, d_ff=64, n_experts=16, top_k=4,
+             n_shared=2, batch_tokens=(4100, 4129), w_std=0.05),
     I.scaled(SMALL, name="mid_group_few_experts", d_model=256, d_ff=64, n_experts=6, top_k=2,
              batch_tokens=(1500, 1501)),
     I.scaled(I.WORKLOADS["tiny_f32"], name="mid_group_f32", d_model=128, d_ff=64, n_experts=5, top_k=3,
@@ -77,8 +79,10 @@ def test_large_batch_groups_route_bit_exactly(w):
     several expert groups and more experts than a wavefront has lanes; and a shape it does not
     serve (experts not in whole groups), which the one-token-per-wavefront router takes, as do
     groups between 2049 and 8191 tokens (there with so few experts that the selection runs in
-    registers, bf16 and fp32).  Logits, top-k, weights and the whole dispatch plan bit for bit,
-    every output within the tolerance."""
+    registers, bf16 and fp32).  One large group has always-on experts as well, so that the gather
+    (several groups of reduction steps per wavefront item, shared rows behind the routed ones) and
+    the combine run their large-layer paths on every kind of row.  Logits, top-k, weights and the
+    whole dispatch plan bit for bit, every output within the tolerance."""
     run_case(w)
 
 
