@@ -150,7 +150,12 @@ __device__ __forceinline__ void scan_body(const Shape& s, const PlanPtrs& p, int
     }
 }
 
-// P2: one block.  Sums the per-chunk histograms, then scan_body.
+// P2: one block.  Sums the per-chunk histograms, then scan_body.  The chunk histograms pass through
+// LDS in panels of kScanPanel entries (whole chunks): all threads load a panel (coalesced), one
+// thread per expert runs down its column in LDS, all threads store the exclusive bases.  (One
+// thread per expert walking global memory chunk by chunk took 34 us on a 32-chunk layer: a chain
+// of dependent loads.)
+constexpr int kScanPanel = 4096;
 __global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunks, PlanPtrs p,
                                                              int max_tiles) {
     __shared__ int32_t cnt[kMaxExperts];
@@ -159,17 +164,40 @@ __global__ __launch_bounds__(kThreads) void plan_scan_kernel(Shape s, int nchunk
     __shared__ int32_t pof[kMaxExperts + 1];
     __shared__ int32_t ord[kMaxExperts];
     __shared__ int32_t nact;
-    for (int e = threadIdx.x; e < s.E; e += kThreads) {
-        int run = 0;
-        unsigned long long m = 0ull;
-        for (int c = 0; c < nchunks; ++c) {
-            p.blk_base[(size_t)c * s.E + e] = run;
-            run += p.blk_counts[(size_t)c * s.E + e];
-            m |= p.blk_mask[(size_t)c * s.E + e];
-        }
-        cnt[e] = run;
-        nbt[e] = __popcll(m);
+    __shared__ int32_t panel[kScanPanel];
+    __shared__ unsigned long long pmask[kMaxExperts];
+    static_assert(kScanPanel >= kMaxExperts, "a panel holds at least one chunk");
+    const int E = s.E;
+    for (int e = threadIdx.x; e < E; e += kThreads) {
+        cnt[e] = 0;
+        pmask[e] = 0ull;
     }
+    __syncthreads();
+    const int per_panel = kScanPanel / E;  // whole chunks per panel
+    for (int c0 = 0; c0 < nchunks; c0 += per_panel) {
+        const int nc = min(per_panel, nchunks - c0);
+        const size_t g0 = (size_t)c0 * E;
+        for (int i = threadIdx.x; i < nc * E; i += kThreads) panel[i] = p.blk_counts[g0 + i];
+        // batch masks: or-reduced per expert (order-free)
+        for (int i = threadIdx.x; i < nc * E; i += kThreads) {
+            const unsigned long long m = p.blk_mask[g0 + i];
+            if (m) atomicOr(&pmask[i % E], m);
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < E; e += kThreads) {
+            int run = cnt[e];
+            for (int c = 0; c < nc; ++c) {
+                const int v = panel[c * E + e];
+                panel[c * E + e] = run;
+                run += v;
+            }
+            cnt[e] = run;
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < nc * E; i += kThreads) p.blk_base[g0 + i] = panel[i];
+        __syncthreads();
+    }
+    for (int e = threadIdx.x; e < E; e += kThreads) nbt[e] = __popcll(pmask[e]);
     __syncthreads();
     scan_body(s, p, max_tiles, cnt, nbt, off, pof, ord, &nact);
 }

@@ -66,6 +66,8 @@ def test_bf16_small_shapes(w):
              batch_tokens=(8200,), w_std=0.04),
     I.scaled(SMALL, name="large_group_k_equals_E", d_model=1024, d_ff=64, n_experts=8, top_k=8,
              batch_tokens=(8192,), w_std=0.04),
+    I.scaled(SMALL, name="large_group_max_experts", d_model=1024, d_ff=64, n_experts=256, top_k=2,
+             batch_tokens=(9000,), w_std=0.04),  # 18 chunks of assignments: two panels of the plan's scan
     I.scaled(SMALL, name="large_group_shared_experts", d_model=512, d_ff=64, n_experts=16, top_k=4,
              n_shared=2, batch_tokens=(4100, 4129), w_std=0.05),
     I.scaled(SMALL, name="mid_group_few_experts", d_model=256, d_ff=64, n_experts=6, top_k=2,
