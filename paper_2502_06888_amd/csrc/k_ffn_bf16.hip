@@ -47,6 +47,14 @@ __device__ __forceinline__ gptr as_global(const void* p) { return (gptr)(uintptr
 // Weights are read exactly once per tile: a streaming (non-temporal) load keeps them from
 // taking cache lines that the re-read activations need, and measurably raises the HBM rate.
 __device__ __forceinline__ u32x4 load_stream(gptr p) { return __builtin_nontemporal_load(p); }
+// Reloads of the weight ring.  The down projection on full tiles (two-unit shape) is the one place
+// where ordinary loads measure faster (1-2 %): the four tiles of a panel read the same W2 stream
+// right behind each other and find more of it in L2 when the lines are not marked as streaming.
+template <int MODE, int U>
+__device__ __forceinline__ u32x4 load_ring(gptr p) {
+    if (MODE == 1 && U == 2) return *p;
+    return __builtin_nontemporal_load(p);
+}
 
 // The activations of a tile are loaded through a buffer descriptor: the address of a load is then
 // a scalar byte offset (kept and advanced by the scalar unit) plus the lane's constant 16-byte
@@ -224,7 +232,7 @@ __device__ __forceinline__ void stage_mfma(const u32x4* L, u32x4 (&w)[SX][U], gp
         }
         if (t % NS == NS - 1) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) w[j][u] = load_stream(wnext + (size_t)u * ustride + (size_t)j * 64);
+            for (int u = 0; u < U; ++u) w[j][u] = load_ring<MODE, U>(wnext + (size_t)u * ustride + (size_t)j * 64);
         }
     }
     __builtin_amdgcn_sched_group_barrier(0x100, DD, 0);
@@ -361,8 +369,8 @@ __device__ __forceinline__ void run_pass(const TileCtx& c, Pipe<NB, WAVES, U, SX
 #pragma unroll
                             for (int u = 0; u < U; ++u)
                                 pp.wr[g % RS][j][u] =
-                                    load_stream(c.wbase + (size_t)u * c.ustride +
-                                                (size_t)(kk + RS * SX + j) * 64);
+                                    load_ring<MODE, U>(c.wbase + (size_t)u * c.ustride +
+                                                       (size_t)(kk + RS * SX + j) * 64);
                         }
                     }
                 }
